@@ -1,0 +1,236 @@
+/*
+ * C ABI of the MI355X heterogeneous-LoRA batching operator.
+ *
+ * The operator is the one VaLoRA's ATMM accelerates (paper section 4.3.1):
+ * one batch of tokens, each request (segment) bound to its own LoRA adapter,
+ * adapters of different ranks, segments of different lengths, no padding.
+ * With the LoRA definition of section 2 (an adapter's update is the product
+ * of its two low-rank factors; in unmerged inference its result is added onto
+ * the base layer's output) every token t of a segment that uses adapter a gets
+ *
+ *         y[t,:] = x[t,:] W  +  s_a * (x[t,:] A_a) B_a
+ *
+ * x [T,K], W [K,N], A_a [K,r_a], B_a [r_a,N] as mathematical objects.
+ *
+ * MEMORY LAYOUT.  Every weight is stored the way section 2 dimensions the
+ * factors (A as r x d, B as d x r) and the way torch.nn.Linear stores
+ * `weight`: [out_features, in_features] row-major, contraction index fastest.
+ *
+ *     A_a  is stored as  At_a [r_a, K]   At_a[j*K   + k] = A_a[k,j]
+ *     B_a  is stored as  Bt_a [N, r_a]   Bt_a[n*r_a + j] = B_a[j,n]
+ *     W    is stored as  Wt   [N, K]     Wt  [n*ldw + k] = W[k,n]
+ *     x [T,K] row-major (ldx), y [T,N] row-major (ldy),
+ *     v [T,R] row-major fp32, R = lora_plan_query's v_row_stride,
+ *       v[t*R + j] for j < r_a; the rest of a row is never read or written.
+ *
+ * OWNERSHIP.  The caller owns every device buffer (x, W, At_a, Bt_a, the two
+ * device arrays of adapter pointers, v, y, workspace) and the HIP stream.  The
+ * library owns only the plan: host tables, and a few small device tables that
+ * are allocated by lora_plan_upload (or by the first compute call that uses
+ * the plan) and released by lora_plan_destroy.  Compute calls enqueue kernels
+ * on the caller's stream and return; they never synchronise.  The caller must
+ * not destroy a plan while work that uses it is still in flight (the plan's
+ * device tables are recycled for later plans, not synchronised on).
+ *
+ * ERRORS.  Every function returns a lora_status; nothing throws.  All
+ * descriptor validation happens in lora_plan_create, which is pure host code
+ * and needs no GPU.  Compute calls check pointers, leading dimensions and
+ * alignment before launching and map HIP failures to LORA_ERR_DEVICE.
+ *
+ * ALIGNMENT for the tuned bf16 kernels: base pointers 16 bytes; K, ldx, ldy,
+ * ldw multiples of 8; ranks multiples of 8.  Anything else (and fp32) runs
+ * through a general kernel with no alignment demands.
+ */
+#ifndef LORA_ABI_H
+#define LORA_ABI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LORA_MAX_RANK 256
+
+typedef enum {
+    LORA_OK = 0,
+    LORA_ERR_INVALID_ARG = 1,   /* null pointer, bad segment table, id or rank out of range ... */
+    LORA_ERR_UNSUPPORTED = 2,   /* valid request this build cannot run (dtype, size limits) */
+    LORA_ERR_NOMEM = 3,         /* host or device allocation failed */
+    LORA_ERR_WORKSPACE = 4,     /* caller's workspace is too small or misaligned */
+    LORA_ERR_DEVICE = 5         /* a HIP call or kernel launch failed */
+} lora_status;
+
+typedef enum { LORA_F32 = 0, LORA_BF16 = 1 } lora_dtype;
+
+/* Kernel family selection; tests use the non-default values to drive every
+ * family over the same inputs. */
+typedef enum {
+    LORA_VARIANT_AUTO = 0,      /* planner decides per batch */
+    LORA_VARIANT_GENERAL = 1,   /* general VALU kernels only */
+    LORA_VARIANT_TILED = 2      /* tiled MFMA kernels wherever the layout allows */
+} lora_variant;
+
+typedef struct lora_plan lora_plan;   /* opaque, library-owned */
+
+/*
+ * Batch descriptor = the operator's problem statement (section 4.3.1: requests
+ * of heterogeneous length, adapters of heterogeneous rank; section 5: the
+ * request-to-adapter mapping of the batch).  All pointers are HOST pointers and
+ * are only read during lora_plan_create.
+ */
+typedef struct {
+    int32_t        num_tokens;     /* T >= 0 */
+    int32_t        num_segments;   /* S >= 0 */
+    const int32_t* seg_indptr;     /* [S+1], [0]=0, non-decreasing, [S]=T; empty segments allowed */
+    const int32_t* seg_adapter;    /* [S], in [-1, num_adapters); -1 = no adapter (y = xW) */
+    int32_t        num_adapters;   /* n_a >= 0 */
+    const int32_t* adapter_rank;   /* [n_a], 0..LORA_MAX_RANK; rank 0 = no adapter */
+    const float*   adapter_scale;  /* [n_a], finite */
+    int32_t        k;              /* in features  K >= 1 */
+    int32_t        n;              /* out features N >= 1 */
+    int32_t        dtype;          /* lora_dtype of x, At, Bt, Wt, y (v is always fp32) */
+    int32_t        variant;        /* lora_variant */
+} lora_batch_desc;
+
+/* One unit of kernel work: the rows [row0,row0+nrows) of `perm` (all of one
+ * adapter) times the columns [c0,c0+cn) -- rank indices for shrink, output
+ * features for expand. */
+typedef struct {
+    int32_t adapter;
+    int32_t row0;
+    int32_t nrows;
+    int32_t c0;
+    int32_t cn;
+    int32_t shape;      /* kernel tile shape code chosen by the planner */
+    int32_t reserved0;
+    int32_t reserved1;
+} lora_tile;
+
+/* Read-only view of a plan's host tables (valid until lora_plan_destroy). */
+typedef struct {
+    int32_t        num_tokens;
+    int32_t        num_active;      /* tokens that have an adapter of rank > 0 */
+    int32_t        num_groups;      /* distinct adapters in use */
+    int32_t        v_row_stride;    /* R */
+    int32_t        kernel_family;   /* lora_variant actually chosen (GENERAL or TILED) */
+    int32_t        shrink_waves;    /* wavefronts per workgroup of the shrink launch */
+    const int32_t* token_adapter;   /* [T]  adapter of each token, -1 = none */
+    const int32_t* perm;            /* [num_active] tokens with an adapter, stably sorted by adapter */
+    const int32_t* group_adapter;   /* [num_groups] ascending adapter ids */
+    const int32_t* group_offset;    /* [num_groups+1] exclusive prefix sums into perm */
+    const lora_tile* shrink_tiles;  int32_t num_shrink_tiles;
+    const lora_tile* expand_tiles;  int32_t num_expand_tiles;
+} lora_plan_view;
+
+/*
+ * lora_plan -- the per-batch step that stands where ATMM looks up the tile
+ * configuration for the input shapes at hand (section 4.3.1, "adaptive tiling
+ * against input shapes"; the shape-keyed table of section 4.3.2).  From the
+ * segment table and the rank table it derives: the adapter of every token, the
+ * stable grouping of tokens by adapter, and the tile lists of the shrink and
+ * expand launches (tile shape chosen per adapter group from the group's token
+ * count and rank).  Pure host code, deterministic: equal descriptors give
+ * byte-identical tables.  One plan serves every layer / projection that shares
+ * the segment table, K, N, ranks and scales.
+ *
+ * Returns LORA_ERR_INVALID_ARG for: null desc/out; negative sizes; null tables
+ * with non-zero counts; seg_indptr not starting at 0, decreasing, or not ending
+ * at T; adapter id outside [-1, n_a); rank outside [0, LORA_MAX_RANK];
+ * non-finite scale; K or N < 1; unknown dtype or variant.
+ */
+lora_status lora_plan_create(const lora_batch_desc* desc, lora_plan** out);
+void        lora_plan_destroy(lora_plan* plan);   /* NULL is allowed */
+
+/* v_row_stride R (floats), bytes of the v buffer (T*R*4), and the bytes of
+ * workspace lora_fused_forward needs (it holds v).  Any out pointer may be NULL. */
+lora_status lora_plan_query(const lora_plan* plan, int32_t* v_row_stride,
+                            size_t* v_bytes, size_t* fused_workspace_bytes);
+
+lora_status lora_plan_export(const lora_plan* plan, lora_plan_view* out);
+
+/* Copy the plan's tables to the current device (allocates the library-owned
+ * device tables; stream-ordered copy on hip_stream).  Optional: compute calls
+ * do it on first use. */
+lora_status lora_plan_upload(lora_plan* plan, void* hip_stream);
+
+/*
+ * lora_shrink -- first of the two extra products per adapted layer (section
+ * 3.2; the skinny K -> r GEMM of every adapter branch, batched by ATMM,
+ * section 4.3.1), with the adapter's scale folded in:
+ *
+ *     v[t, j] = s_a * sum_k x[t,k] * A_a[k,j]        j < r_a,  a = adapter(t)
+ *
+ * x: device, [T,K] row-major, leading dimension ldx (elements).
+ * d_At_ptrs: device array [n_a] of device pointers to At_a [r_a,K]; entries of
+ *   adapters no token uses are never dereferenced.
+ * v: device, fp32 [T,R]; rows of tokens without adapter are left untouched.
+ * fp32 accumulation; the products of two bf16 values are exact in fp32.
+ */
+lora_status lora_shrink(lora_plan* plan, const void* x, int64_t ldx,
+                        const void* const* d_At_ptrs, float* v, void* hip_stream);
+
+/*
+ * lora_expand -- the second extra product and the extra addition per adapted
+ * layer (section 3.2; the r -> N GEMM of every adapter branch, section 4.3.1):
+ *
+ *     y[t, n] = beta * y[t, n] + sum_j v[t,j] * B_a[j,n]
+ *
+ * v as written by lora_shrink (already scaled).  d_Bt_ptrs: device array [n_a]
+ * of device pointers to Bt_a [N,r_a].  y: device, [T,N], ldy; beta is 1
+ * (accumulate onto the base output) or 0 (overwrite); rows of tokens without
+ * adapter are left untouched bit for bit (also for beta = 0).
+ * fp32 accumulation, one round-to-nearest-even at the store.
+ */
+lora_status lora_expand(lora_plan* plan, const float* v,
+                        const void* const* d_Bt_ptrs, void* y, int64_t ldy,
+                        float beta, void* hip_stream);
+
+/*
+ * lora_base_gemm -- the base-model product shared by all requests of the batch
+ * (section 1 / section 2, unmerged inference):  y = x W, Wt [N,K] with ldw.
+ * bf16 MFMA with fp32 accumulation (fp32 dtype: VALU).  Used for the
+ * "separate" path base GEMM + shrink + expand.
+ */
+lora_status lora_base_gemm(int32_t num_tokens, int32_t k, int32_t n, int32_t dtype,
+                           const void* x, int64_t ldx, const void* Wt, int64_t ldw,
+                           void* y, int64_t ldy, void* hip_stream);
+
+/*
+ * lora_fused_forward -- whole layer in one call, y = x W + s_a (x A_a) B_a,
+ * with the adapter delta added to the base GEMM's fp32 accumulators before the
+ * single rounding of y (unmerged inference at close to the cost of merged
+ * inference, sections 2 and 4.4).  Runs the shrink into `workspace` (which
+ * holds v; size from lora_plan_query, 256-byte aligned), then one GEMM kernel
+ * whose epilogue applies the expand.  LORA_ERR_WORKSPACE if the workspace is
+ * too small.
+ */
+lora_status lora_fused_forward(lora_plan* plan, const void* x, int64_t ldx,
+                               const void* Wt, int64_t ldw,
+                               const void* const* d_At_ptrs, const void* const* d_Bt_ptrs,
+                               void* y, int64_t ldy,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+const char* lora_status_str(lora_status s);
+
+/*
+ * Planner tunables: the process-wide table that steers tile-shape choice, the
+ * counterpart of the shape -> tile-configuration table the paper fills by
+ * profiling (section 4.3.2, Algorithm 2).  `values` is an int32 array in the
+ * order: shrink_waves (wavefronts per shrink workgroup, 1..8),
+ * shrink_tb2_min_rows (adapter groups with at least this many tokens use
+ * 32-token shrink tiles), shrink_max_jb (rank blocks of 16 per shrink tile,
+ * 1..4), expand_wave_bytes (bytes of Bt and y one expand wavefront streams),
+ * expand_tb2_min_rows, expand_tb4_min_rows (token-count thresholds for 32- and
+ * 64-token expand tiles), tiled_min_tokens (AUTO uses the general kernels below
+ * this many active tokens).  Entries <= 0 keep the current value; plans made
+ * earlier are unaffected.  Host only.
+ */
+void lora_tuning_set(const int32_t* values, int32_t count);
+void lora_tuning_get(int32_t* values, int32_t count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORA_ABI_H */

@@ -1,0 +1,245 @@
+"""Thin ctypes binding over the C-ABI library (include/lora_abi.h).
+
+Argument marshalling only: every step of the operator runs in the HIP kernels
+of liblora_amd.so.  There is no CPU fallback; if the library has not been built
+the import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblora_amd.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2411_00915_amd.build` "
+        "(there is no fallback path)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+LORA_OK, LORA_ERR_INVALID_ARG, LORA_ERR_UNSUPPORTED, LORA_ERR_NOMEM, LORA_ERR_WORKSPACE, LORA_ERR_DEVICE = range(6)
+LORA_F32, LORA_BF16 = 0, 1
+LORA_VARIANT_AUTO, LORA_VARIANT_GENERAL, LORA_VARIANT_TILED = 0, 1, 2
+LORA_MAX_RANK = 256
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_f32p = ctypes.POINTER(ctypes.c_float)
+
+
+class BatchDesc(ctypes.Structure):
+    _fields_ = [("num_tokens", ctypes.c_int32), ("num_segments", ctypes.c_int32),
+                ("seg_indptr", _i32p), ("seg_adapter", _i32p),
+                ("num_adapters", ctypes.c_int32), ("adapter_rank", _i32p), ("adapter_scale", _f32p),
+                ("k", ctypes.c_int32), ("n", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("variant", ctypes.c_int32)]
+
+
+class Tile(ctypes.Structure):
+    _fields_ = [("adapter", ctypes.c_int32), ("row0", ctypes.c_int32), ("nrows", ctypes.c_int32),
+                ("c0", ctypes.c_int32), ("cn", ctypes.c_int32), ("shape", ctypes.c_int32),
+                ("reserved0", ctypes.c_int32), ("reserved1", ctypes.c_int32)]
+
+
+class PlanView(ctypes.Structure):
+    _fields_ = [("num_tokens", ctypes.c_int32), ("num_active", ctypes.c_int32),
+                ("num_groups", ctypes.c_int32), ("v_row_stride", ctypes.c_int32),
+                ("kernel_family", ctypes.c_int32), ("shrink_waves", ctypes.c_int32),
+                ("token_adapter", _i32p), ("perm", _i32p), ("group_adapter", _i32p), ("group_offset", _i32p),
+                ("shrink_tiles", ctypes.POINTER(Tile)), ("num_shrink_tiles", ctypes.c_int32),
+                ("expand_tiles", ctypes.POINTER(Tile)), ("num_expand_tiles", ctypes.c_int32)]
+
+
+_vp = ctypes.c_void_p
+_lib.lora_plan_create.restype = ctypes.c_int
+_lib.lora_plan_create.argtypes = [ctypes.POINTER(BatchDesc), ctypes.POINTER(_vp)]
+_lib.lora_plan_destroy.restype = None
+_lib.lora_plan_destroy.argtypes = [_vp]
+_lib.lora_plan_query.restype = ctypes.c_int
+_lib.lora_plan_query.argtypes = [_vp, _i32p, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
+_lib.lora_plan_export.restype = ctypes.c_int
+_lib.lora_plan_export.argtypes = [_vp, ctypes.POINTER(PlanView)]
+_lib.lora_plan_upload.restype = ctypes.c_int
+_lib.lora_plan_upload.argtypes = [_vp, _vp]
+_lib.lora_shrink.restype = ctypes.c_int
+_lib.lora_shrink.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, _vp]
+_lib.lora_expand.restype = ctypes.c_int
+_lib.lora_expand.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_float, _vp]
+_lib.lora_base_gemm.restype = ctypes.c_int
+_lib.lora_base_gemm.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp]
+_lib.lora_fused_forward.restype = ctypes.c_int
+_lib.lora_fused_forward.argtypes = [_vp, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp, _vp,
+                                    _vp, ctypes.c_int64, _vp, ctypes.c_size_t, _vp]
+_lib.lora_status_str.restype = ctypes.c_char_p
+_lib.lora_status_str.argtypes = [ctypes.c_int]
+_lib.lora_tuning_set.restype = None
+_lib.lora_tuning_set.argtypes = [_i32p, ctypes.c_int32]
+_lib.lora_tuning_get.restype = None
+_lib.lora_tuning_get.argtypes = [_i32p, ctypes.c_int32]
+
+EXPORTED = ["lora_plan_create", "lora_plan_destroy", "lora_plan_query", "lora_plan_export",
+            "lora_plan_upload", "lora_shrink", "lora_expand", "lora_base_gemm",
+            "lora_fused_forward", "lora_status_str", "lora_tuning_set", "lora_tuning_get"]
+
+TUNING_FIELDS = ["shrink_waves", "shrink_tb2_min_rows", "shrink_max_jb", "expand_wave_bytes",
+                 "expand_tb2_min_rows", "expand_tb4_min_rows", "tiled_min_tokens"]
+
+
+class LoraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lora_status_str(status)} (status {status})")
+
+
+def lora_status_str(status: int) -> str:
+    return _lib.lora_status_str(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != LORA_OK:
+        raise LoraError(status, where)
+
+
+def _ptr(obj) -> Optional[int]:
+    """Device/host address of a torch tensor, or an int address, or None."""
+    if obj is None:
+        return None
+    if isinstance(obj, int):
+        return obj
+    return int(obj.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def lora_tuning_get() -> dict:
+    buf = (ctypes.c_int32 * len(TUNING_FIELDS))()
+    _lib.lora_tuning_get(buf, len(TUNING_FIELDS))
+    return dict(zip(TUNING_FIELDS, list(buf)))
+
+
+def lora_tuning_set(**kw) -> None:
+    """Set planner tunables (values <= 0 or missing keep the current value)."""
+    vals = [int(kw.get(f, 0)) for f in TUNING_FIELDS]
+    unknown = set(kw) - set(TUNING_FIELDS)
+    if unknown:
+        raise KeyError(f"unknown tuning fields: {sorted(unknown)}")
+    buf = (ctypes.c_int32 * len(vals))(*vals)
+    _lib.lora_tuning_set(buf, len(vals))
+
+
+class Plan:
+    """Owner of a lora_plan handle."""
+
+    def __init__(self, handle: int, keepalive):
+        self._h = handle
+        self._keep = keepalive
+
+    @property
+    def handle(self) -> int:
+        return self._h
+
+    def destroy(self):
+        if self._h:
+            _lib.lora_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def lora_plan(num_tokens, seg_indptr, seg_adapter, adapter_rank, adapter_scale, k, n, dtype,
+              variant=LORA_VARIANT_AUTO) -> Plan:
+    """lora_plan_create; tables are host arrays (numpy or sequences)."""
+    indptr = np.ascontiguousarray(seg_indptr, dtype=np.int32)
+    seg_ad = np.ascontiguousarray(seg_adapter, dtype=np.int32)
+    rank = np.ascontiguousarray(adapter_rank, dtype=np.int32)
+    scale = np.ascontiguousarray(adapter_scale, dtype=np.float32)
+    desc = BatchDesc(int(num_tokens), int(seg_ad.shape[0]),
+                     indptr.ctypes.data_as(_i32p), seg_ad.ctypes.data_as(_i32p),
+                     int(rank.shape[0]), rank.ctypes.data_as(_i32p), scale.ctypes.data_as(_f32p),
+                     int(k), int(n), int(dtype), int(variant))
+    out = _vp()
+    _check(_lib.lora_plan_create(ctypes.byref(desc), ctypes.byref(out)), "lora_plan_create")
+    return Plan(out.value, None)
+
+
+def lora_plan_create_raw(desc: Optional[BatchDesc]):
+    """Direct call for error-path tests: returns (status, handle)."""
+    out = _vp()
+    st = _lib.lora_plan_create(ctypes.byref(desc) if desc is not None else None, ctypes.byref(out))
+    return st, out.value
+
+
+def lora_plan_destroy(plan: Plan):
+    plan.destroy()
+
+
+def lora_plan_query(plan: Plan):
+    r = ctypes.c_int32()
+    vb = ctypes.c_size_t()
+    ws = ctypes.c_size_t()
+    _check(_lib.lora_plan_query(plan.handle, ctypes.byref(r), ctypes.byref(vb), ctypes.byref(ws)), "lora_plan_query")
+    return int(r.value), int(vb.value), int(ws.value)
+
+
+def lora_plan_export(plan: Plan) -> dict:
+    """Copy of the plan's host tables as numpy arrays."""
+    v = PlanView()
+    _check(_lib.lora_plan_export(plan.handle, ctypes.byref(v)), "lora_plan_export")
+
+    def arr(p, n):
+        return np.ctypeslib.as_array(p, shape=(n,)).copy() if n > 0 else np.zeros(0, np.int32)
+
+    def tiles(p, n):
+        if n == 0:
+            return np.zeros((0, 8), np.int32)
+        raw = np.ctypeslib.as_array(ctypes.cast(p, _i32p), shape=(n * 8,)).copy()
+        return raw.reshape(n, 8)
+
+    return dict(num_tokens=v.num_tokens, num_active=v.num_active, num_groups=v.num_groups,
+                v_row_stride=v.v_row_stride, kernel_family=v.kernel_family, shrink_waves=v.shrink_waves,
+                token_adapter=arr(v.token_adapter, v.num_tokens), perm=arr(v.perm, v.num_active),
+                group_adapter=arr(v.group_adapter, v.num_groups),
+                group_offset=arr(v.group_offset, v.num_groups + 1),
+                shrink_tiles=tiles(v.shrink_tiles, v.num_shrink_tiles),
+                expand_tiles=tiles(v.expand_tiles, v.num_expand_tiles))
+
+
+def lora_plan_upload(plan: Plan, stream=None):
+    _check(_lib.lora_plan_upload(plan.handle, _stream(stream)), "lora_plan_upload")
+
+
+def lora_shrink(plan: Plan, x, ldx: int, d_At_ptrs, v, stream=None):
+    _check(_lib.lora_shrink(plan.handle, _ptr(x), int(ldx), _ptr(d_At_ptrs), _ptr(v), _stream(stream)), "lora_shrink")
+
+
+def lora_expand(plan: Plan, v, d_Bt_ptrs, y, ldy: int, beta: float = 1.0, stream=None):
+    _check(_lib.lora_expand(plan.handle, _ptr(v), _ptr(d_Bt_ptrs), _ptr(y), int(ldy), float(beta), _stream(stream)),
+           "lora_expand")
+
+
+def lora_base_gemm(num_tokens: int, k: int, n: int, dtype: int, x, ldx: int, Wt, ldw: int, y, ldy: int, stream=None):
+    _check(_lib.lora_base_gemm(int(num_tokens), int(k), int(n), int(dtype), _ptr(x), int(ldx), _ptr(Wt), int(ldw),
+                               _ptr(y), int(ldy), _stream(stream)), "lora_base_gemm")
+
+
+def lora_fused_forward(plan: Plan, x, ldx: int, Wt, ldw: int, d_At_ptrs, d_Bt_ptrs, y, ldy: int,
+                       workspace, workspace_bytes: int, stream=None):
+    _check(_lib.lora_fused_forward(plan.handle, _ptr(x), int(ldx), _ptr(Wt), int(ldw), _ptr(d_At_ptrs),
+                                   _ptr(d_Bt_ptrs), _ptr(y), int(ldy), _ptr(workspace), int(workspace_bytes),
+                                   _stream(stream)), "lora_fused_forward")

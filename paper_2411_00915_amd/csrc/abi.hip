@@ -1,0 +1,247 @@
+// C-ABI entry points that touch the device: plan upload / destroy and the
+// compute calls.  Argument checks happen here, before anything is launched.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "kernels.h"
+#include "plan_internal.h"
+
+namespace {
+
+struct cached_buf {
+    int device;
+    size_t bytes;
+    void* dev;
+    void* host;
+};
+std::mutex g_cache_mutex;
+std::vector<cached_buf> g_cache;       // released plan tables, reused by later plans
+constexpr size_t kCacheMax = 16;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+struct table_layout {
+    size_t perm, token_adapter, rank, scale, shrink_tiles, expand_tiles, total;
+};
+
+table_layout layout_of(const lora_plan* p)
+{
+    table_layout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    L.perm = take(p->perm.size() * sizeof(int32_t));
+    L.token_adapter = take(p->token_adapter.size() * sizeof(int32_t));
+    L.rank = take(p->rank.size() * sizeof(int32_t));
+    L.scale = take(p->scale.size() * sizeof(float));
+    L.shrink_tiles = take(p->shrink_tiles.size() * sizeof(lora_tile));
+    L.expand_tiles = take(p->expand_tiles.size() * sizeof(lora_tile));
+    L.total = std::max<size_t>(off, 256);
+    return L;
+}
+
+lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return LORA_ERR_DEVICE;
+    if (p->d_buf) return p->device == dev ? LORA_OK : LORA_ERR_INVALID_ARG;   // a plan lives on one device
+
+    const table_layout L = layout_of(p);
+    // size classes (powers of two from 4 KiB) so that released buffers fit later plans
+    size_t cls = 4096;
+    while (cls < L.total) cls <<= 1;
+    void* dbuf = nullptr;
+    void* hbuf = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        for (size_t i = 0; i < g_cache.size(); ++i) {
+            if (g_cache[i].device == dev && g_cache[i].bytes == cls) {
+                dbuf = g_cache[i].dev;
+                hbuf = g_cache[i].host;
+                g_cache.erase(g_cache.begin() + i);
+                break;
+            }
+        }
+    }
+    if (!dbuf) {
+        if (hipMalloc(&dbuf, cls) != hipSuccess) { (void)hipGetLastError(); return LORA_ERR_NOMEM; }
+        if (hipHostMalloc(&hbuf, cls, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(dbuf);
+            return LORA_ERR_NOMEM;
+        }
+    }
+    char* h = static_cast<char*>(hbuf);
+    auto put = [&](size_t off, const void* src, size_t bytes) { if (bytes) std::memcpy(h + off, src, bytes); };
+    put(L.perm, p->perm.data(), p->perm.size() * sizeof(int32_t));
+    put(L.token_adapter, p->token_adapter.data(), p->token_adapter.size() * sizeof(int32_t));
+    put(L.rank, p->rank.data(), p->rank.size() * sizeof(int32_t));
+    put(L.scale, p->scale.data(), p->scale.size() * sizeof(float));
+    put(L.shrink_tiles, p->shrink_tiles.data(), p->shrink_tiles.size() * sizeof(lora_tile));
+    put(L.expand_tiles, p->expand_tiles.data(), p->expand_tiles.size() * sizeof(lora_tile));
+    if (hipMemcpyAsync(dbuf, hbuf, L.total, hipMemcpyHostToDevice, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(dbuf);
+        (void)hipHostFree(hbuf);
+        return LORA_ERR_DEVICE;
+    }
+    char* d = static_cast<char*>(dbuf);
+    p->device = dev;
+    p->d_buf = dbuf;
+    p->d_bytes = cls;
+    p->h_stage = hbuf;
+    p->d_perm = reinterpret_cast<int32_t*>(d + L.perm);
+    p->d_token_adapter = reinterpret_cast<int32_t*>(d + L.token_adapter);
+    p->d_rank = reinterpret_cast<int32_t*>(d + L.rank);
+    p->d_scale = reinterpret_cast<float*>(d + L.scale);
+    p->d_shrink_tiles = reinterpret_cast<lora_tile*>(d + L.shrink_tiles);
+    p->d_expand_tiles = reinterpret_cast<lora_tile*>(d + L.expand_tiles);
+    return LORA_OK;
+}
+
+lora_dev_tables tables_of(const lora_plan* p)
+{
+    return lora_dev_tables{p->d_perm, p->d_token_adapter, p->d_rank, p->d_scale, p->d_shrink_tiles, p->d_expand_tiles};
+}
+
+size_t elem_bytes(int32_t dtype) { return dtype == LORA_F32 ? 4 : 2; }
+
+// layout the tiled kernels need at call time
+bool tiled_call_ok(const void* base, int64_t ld) { return !misaligned(base, 16) && ld % 8 == 0; }
+
+}  // namespace
+
+extern "C" void lora_plan_destroy(lora_plan* p)
+{
+    if (!p) return;
+    if (p->d_buf) {
+        // Contract: the caller destroys a plan only after the work that uses it has
+        // finished.  The tables go back to a small cache for later plans.
+        int cur = -1;
+        (void)hipGetDevice(&cur);
+        if (cur != p->device) (void)hipSetDevice(p->device);
+        bool kept = false;
+        {
+            std::lock_guard<std::mutex> lock(g_cache_mutex);
+            if (g_cache.size() < kCacheMax) {
+                g_cache.push_back(cached_buf{p->device, p->d_bytes, p->d_buf, p->h_stage});
+                kept = true;
+            }
+        }
+        if (!kept) {
+            (void)hipFree(p->d_buf);
+            (void)hipHostFree(p->h_stage);
+        }
+        if (cur != p->device && cur >= 0) (void)hipSetDevice(cur);
+    }
+    delete p;
+}
+
+extern "C" lora_status lora_plan_upload(lora_plan* p, void* hip_stream)
+{
+    if (!p) return LORA_ERR_INVALID_ARG;
+    return ensure_uploaded(p, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" lora_status lora_shrink(lora_plan* p, const void* x, int64_t ldx,
+                                   const void* const* d_At_ptrs, float* v, void* hip_stream)
+{
+    if (!p) return LORA_ERR_INVALID_ARG;
+    if (p->perm.empty()) return LORA_OK;                       // no token has an adapter: nothing to do
+    if (!x || !d_At_ptrs || !v) return LORA_ERR_INVALID_ARG;
+    if (ldx < p->K) return LORA_ERR_INVALID_ARG;
+    if (misaligned(x, elem_bytes(p->dtype)) || misaligned(v, 16) || misaligned(d_At_ptrs, 8)) return LORA_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    lora_status st = ensure_uploaded(p, stream);
+    if (st != LORA_OK) return st;
+    const lora_dev_tables d = tables_of(p);
+    hipError_t e;
+    if (p->family == LORA_VARIANT_TILED && tiled_call_ok(x, ldx))
+        e = launch_shrink_tiled(p, d, x, ldx, d_At_ptrs, v, stream);
+    else if (p->family == LORA_VARIANT_TILED && p->variant_req == LORA_VARIANT_TILED)
+        return LORA_ERR_UNSUPPORTED;                           // tiled kernels were demanded but x is not laid out for them
+    else
+        e = launch_shrink_general(p, d, x, ldx, d_At_ptrs, v, stream);
+    return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
+}
+
+extern "C" lora_status lora_expand(lora_plan* p, const float* v, const void* const* d_Bt_ptrs,
+                                   void* y, int64_t ldy, float beta, void* hip_stream)
+{
+    if (!p) return LORA_ERR_INVALID_ARG;
+    if (!(beta == 0.f || beta == 1.f)) return LORA_ERR_INVALID_ARG;
+    if (p->perm.empty()) return LORA_OK;
+    if (!v || !d_Bt_ptrs || !y) return LORA_ERR_INVALID_ARG;
+    if (ldy < p->N) return LORA_ERR_INVALID_ARG;
+    if (misaligned(y, elem_bytes(p->dtype)) || misaligned(v, 16) || misaligned(d_Bt_ptrs, 8)) return LORA_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    lora_status st = ensure_uploaded(p, stream);
+    if (st != LORA_OK) return st;
+    const lora_dev_tables d = tables_of(p);
+    hipError_t e;
+    if (p->family == LORA_VARIANT_TILED && tiled_call_ok(y, ldy))
+        e = launch_expand_tiled(p, d, v, d_Bt_ptrs, y, ldy, beta, stream);
+    else if (p->family == LORA_VARIANT_TILED && p->variant_req == LORA_VARIANT_TILED)
+        return LORA_ERR_UNSUPPORTED;
+    else
+        e = launch_expand_general(p, d, v, d_Bt_ptrs, y, ldy, beta, stream);
+    return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
+}
+
+extern "C" lora_status lora_base_gemm(int32_t T, int32_t K, int32_t N, int32_t dtype,
+                                      const void* x, int64_t ldx, const void* Wt, int64_t ldw,
+                                      void* y, int64_t ldy, void* hip_stream)
+{
+    if (T < 0 || K < 1 || N < 1) return LORA_ERR_INVALID_ARG;
+    if (dtype != LORA_F32 && dtype != LORA_BF16) return LORA_ERR_INVALID_ARG;
+    if (T == 0) return LORA_OK;
+    if (!x || !Wt || !y || ldx < K || ldw < K || ldy < N) return LORA_ERR_INVALID_ARG;
+    if ((int64_t)(T + 15) / 16 > 65535) return LORA_ERR_UNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (gemm_tiled_supported(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy))
+        e = launch_gemm_tiled(T, K, N, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, stream);
+    else
+        e = launch_gemm_general(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, stream);
+    return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
+}
+
+extern "C" lora_status lora_fused_forward(lora_plan* p, const void* x, int64_t ldx,
+                                          const void* Wt, int64_t ldw,
+                                          const void* const* d_At_ptrs, const void* const* d_Bt_ptrs,
+                                          void* y, int64_t ldy,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!p) return LORA_ERR_INVALID_ARG;
+    if (p->T == 0) return LORA_OK;
+    if (!x || !Wt || !y || ldx < p->K || ldw < p->K || ldy < p->N) return LORA_ERR_INVALID_ARG;
+    if ((int64_t)(p->T + 15) / 16 > 65535) return LORA_ERR_UNSUPPORTED;
+    const bool has_delta = !p->perm.empty();
+    if (has_delta) {
+        if (!d_At_ptrs || !d_Bt_ptrs) return LORA_ERR_INVALID_ARG;
+        size_t need = 0;
+        lora_plan_query(p, nullptr, nullptr, &need);
+        if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return LORA_ERR_WORKSPACE;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    float* v = static_cast<float*>(workspace);
+    if (has_delta) {
+        lora_status st = lora_shrink(p, x, ldx, d_At_ptrs, v, hip_stream);
+        if (st != LORA_OK) return st;
+    } else {
+        lora_status st = ensure_uploaded(p, stream);
+        if (st != LORA_OK) return st;
+    }
+    const lora_dev_tables d = tables_of(p);
+    hipError_t e;
+    if (gemm_tiled_supported(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy) &&
+        (!has_delta || p->tiled_layout_ok))
+        e = launch_gemm_tiled(p->T, p->K, p->N, x, ldx, Wt, ldw, y, ldy, p, &d, v, d_Bt_ptrs, stream);
+    else
+        e = launch_gemm_general(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy, p, &d, v, d_Bt_ptrs, stream);
+    return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
+}

@@ -1,0 +1,40 @@
+// Internal launch interface between the C-ABI layer (abi.hip) and the kernel
+// translation units.  Every function enqueues on `stream` and returns the HIP
+// status of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "plan_internal.h"
+
+struct lora_dev_tables {
+    const int32_t* perm;
+    const int32_t* token_adapter;
+    const int32_t* rank;
+    const float* scale;
+    const lora_tile* shrink_tiles;
+    const lora_tile* expand_tiles;
+};
+
+// general VALU family (any dtype, any alignment)
+hipError_t launch_shrink_general(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
+                                 const void* const* At, float* v, hipStream_t stream);
+hipError_t launch_expand_general(const lora_plan* p, const lora_dev_tables& d, const float* v,
+                                 const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream);
+
+// tiled MFMA family (bf16; K, ranks, ldx, ldy multiples of 8; 16-byte aligned bases)
+hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
+                               const void* const* At, float* v, hipStream_t stream);
+hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, const float* v,
+                               const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream);
+
+// base GEMM  y = x Wt^T  (+ optional adapter delta in the epilogue when p != nullptr)
+hipError_t launch_gemm_general(int32_t T, int32_t K, int32_t N, int32_t dtype, const void* x, int64_t ldx,
+                               const void* Wt, int64_t ldw, void* y, int64_t ldy,
+                               const lora_plan* p, const lora_dev_tables* d, const float* v,
+                               const void* const* Bt, hipStream_t stream);
+bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const void* x, int64_t ldx,
+                          const void* Wt, int64_t ldw, const void* y, int64_t ldy);
+hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx,
+                             const void* Wt, int64_t ldw, void* y, int64_t ldy,
+                             const lora_plan* p, const lora_dev_tables* d, const float* v,
+                             const void* const* Bt, hipStream_t stream);

@@ -1,0 +1,332 @@
+// Tiled bf16 shrink / expand kernels for gfx950 (CDNA4), MFMA 16x16x32.
+//
+// Operator: v = s_a (x A_a),  y = beta y + v B_a  for tokens grouped by adapter
+// (paper sections 2, 3.2 and 4.3.1).  What is kept from the paper's kernel
+// design: tiles sized per input (the planner's tile list), no padding in
+// memory, loads of the next data in flight while the current is consumed.
+// What is different here: weights are stored contraction-index-fastest
+// ([r,K] and [N,r]), so a 16-byte load per lane *is* the MFMA operand layout
+// (8 consecutive k for one row) and no LDS transposition is needed; both
+// kernels are bound by HBM, not by the matrix cores, so they are built to keep
+// many 16-byte loads in flight per wavefront and to touch each byte of
+// x / A / B / y once.
+//
+// Lane roles in v_mfma_f32_16x16x32_bf16 (D = A*B + C, A 16x32, B 32x16):
+//   lane l supplies A[row l%16][k 8*(l/16) .. +7] and B[k 8*(l/16) .. +7][col l%16]
+//   and receives D[row 4*(l/16)+i][col l%16], i = 0..3.
+#include "device_util.h"
+#include "kernels.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+
+union op16 {            // one 16-byte MFMA operand
+    uint4 u;
+    bf16x8 v;
+};
+
+__device__ __forceinline__ uint4 ld16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+
+__device__ __forceinline__ floatx4 mfma(const op16& a, const op16& b, floatx4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------
+// Shrink.  One workgroup per tile = (16*TB tokens of one adapter) x (16*JB rank
+// rows of At_a) x the whole K range.  MFMA rows = rank rows, MFMA columns =
+// tokens, so a lane ends up with 4 consecutive rank entries of one token.
+// The workgroup's wavefronts take contiguous slices of K; partial sums meet in
+// LDS, are scaled by s_a and stored once (deterministic, no atomics).
+template <int TB, int JB>
+__device__ __forceinline__ void shrink_tile(
+    const lora_tile tile, const int32_t* __restrict__ perm, const float* __restrict__ scale,
+    const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
+    float* __restrict__ v, int R, floatx4* lds)
+{
+    constexpr int U = (TB * JB >= 8) ? 2 : 4;          // k-steps whose loads are issued together
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
+    const int m = lane & 15, g = lane >> 4;
+
+    const bf16_t* xrow[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        int row = tb * 16 + m;
+        if (row >= tile.nrows) row = 0;                 // padding lanes re-read a valid row; never stored
+        xrow[tb] = x + (int64_t)perm[tile.row0 + row] * ldx + g * 8;
+    }
+    const bf16_t* arow[JB];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+        int j = jb * 16 + m;
+        if (j >= tile.cn) j = 0;
+        arow[jb] = At + (int64_t)(tile.c0 + j) * K + g * 8;
+    }
+
+    floatx4 acc[TB][JB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) acc[tb][jb] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int steps = (K + 31) >> 5;
+    const int s_begin = (int)(((int64_t)steps * wave) / W);
+    const int s_end = (int)(((int64_t)steps * (wave + 1)) / W);
+    const int kmax = K - g * 8;                          // chunk at offset k is inside the row iff k < kmax
+
+    int s = s_begin;
+    for (; s + U <= s_end; s += U) {
+        op16 xa[U][TB], aa[U][JB];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int k = (s + u) << 5;
+            const bool in = k < kmax;
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) xa[u][tb].u = in ? ld16(xrow[tb] + k) : uint4{0, 0, 0, 0};
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) aa[u][jb].u = in ? ld16(arow[jb] + k) : uint4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) acc[tb][jb] = mfma(aa[u][jb], xa[u][tb], acc[tb][jb]);
+    }
+    for (; s < s_end; ++s) {
+        const int k = s << 5;
+        const bool in = k < kmax;
+        op16 xa[TB], aa[JB];
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) xa[tb].u = in ? ld16(xrow[tb] + k) : uint4{0, 0, 0, 0};
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) aa[jb].u = in ? ld16(arow[jb] + k) : uint4{0, 0, 0, 0};
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) acc[tb][jb] = mfma(aa[jb], xa[tb], acc[tb][jb]);
+    }
+
+    // cross-wavefront reduction: lds[(wave*TB*JB + tb*JB + jb)*64 + lane]
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) lds[((wave * TB + tb) * JB + jb) * 64 + lane] = acc[tb][jb];
+    __syncthreads();
+    const float s_a = scale[tile.adapter];
+    for (int e = threadIdx.x; e < TB * JB * 64; e += blockDim.x) {
+        floatx4 sum = lds[e];
+        for (int w = 1; w < W; ++w) {
+            const floatx4 o = lds[w * TB * JB * 64 + e];
+            sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
+        }
+        const int l = e & 63, blk = e >> 6;
+        const int tb = blk / JB, jb = blk % JB;
+        const int row = tb * 16 + (l & 15);
+        const int j = jb * 16 + 4 * (l >> 4);
+        if (row < tile.nrows && j < tile.cn) {
+            const int t = perm[tile.row0 + row];
+            float4 o = make_float4(s_a * sum[0], s_a * sum[1], s_a * sum[2], s_a * sum[3]);
+            *reinterpret_cast<float4*>(v + (int64_t)t * R + tile.c0 + j) = o;
+        }
+    }
+}
+
+extern __shared__ floatx4 shrink_lds[];
+
+__global__ __launch_bounds__(512) void shrink_tiled_kernel(
+    const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm, const float* __restrict__ scale,
+    const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* const* __restrict__ At_ptrs, int K,
+    float* __restrict__ v, int R)
+{
+    const lora_tile tile = tiles[blockIdx.x];
+    const bf16_t* At = At_ptrs[tile.adapter];
+    const int tb = tile.shape & 15, jb = (tile.shape >> 4) & 15;
+#define SHRINK_CASE(TB_, JB_) \
+    if (tb == TB_ && jb == JB_) { shrink_tile<TB_, JB_>(tile, perm, scale, x, ldx, At, K, v, R, shrink_lds); return; }
+    SHRINK_CASE(1, 1)
+    SHRINK_CASE(1, 2)
+    SHRINK_CASE(1, 3)
+    SHRINK_CASE(1, 4)
+    SHRINK_CASE(2, 1)
+    SHRINK_CASE(2, 2)
+    SHRINK_CASE(2, 3)
+    SHRINK_CASE(2, 4)
+#undef SHRINK_CASE
+}
+
+hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
+                               const void* const* At, float* v, hipStream_t stream)
+{
+    const int n_tiles = (int)p->shrink_tiles.size();
+    if (n_tiles == 0) return hipSuccess;
+    const int W = p->shrink_waves;
+    const size_t lds_bytes = (size_t)W * p->shrink_max_blocks * 64 * sizeof(floatx4);   // <= 8 * 8 KB
+    shrink_tiled_kernel<<<n_tiles, 64 * W, lds_bytes, stream>>>(d.shrink_tiles, d.perm, d.scale,
+        (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, p->R);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Expand.  One workgroup (4 wavefronts) per tile = (16*TB tokens of one adapter)
+// x (a range of output features, split evenly over the wavefronts in chunks of
+// 64).  MFMA rows = output features (rows of Bt_a), MFMA columns = tokens.  The
+// fp32 v operand is split into two bf16 terms (v = hi + lo, error ~2^-16 |v|) so
+// the matrix core sees v to fp32-like precision; contraction length is r <= 128.
+//
+// Within a chunk of 64 features, MFMA row 4q+i of block b stands for feature
+// 16q + 4b + i, so after the 4 blocks a lane holds 16 *consecutive* features of
+// one token: y is read and written as 32 contiguous bytes per lane.
+__device__ __forceinline__ void split_bf16(const float* f, op16& hi, op16& lo)
+{
+    uint32_t h[8], l[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const bf16_t hb = f32_to_bf16(f[i]);
+        h[i] = hb;
+        l[i] = f32_to_bf16(f[i] - bf16_to_f32(hb));
+    }
+    hi.u = uint4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+    lo.u = uint4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+}
+
+template <int TB, int KS>
+__device__ __forceinline__ void expand_tile(
+    const lora_tile tile, const int32_t* __restrict__ perm, const float* __restrict__ v, int R,
+    const bf16_t* __restrict__ Bt, int r, bf16_t* __restrict__ y, int64_t ldy, int N, float beta)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, g = lane >> 4;
+
+    // v operands (columns = tokens): lane holds v[token m][32 s + 8 g .. +7]
+    op16 vhi[TB][KS], vlo[TB][KS];
+    int tok[TB];
+    bool tok_ok[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        const int row = tb * 16 + m;
+        tok_ok[tb] = row < tile.nrows;
+        tok[tb] = perm[tile.row0 + (tok_ok[tb] ? row : 0)];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int j = s * 32 + g * 8;
+            float f[8];
+            if (j < r) {
+                const float4 a = *reinterpret_cast<const float4*>(v + (int64_t)tok[tb] * R + j);
+                const float4 b = *reinterpret_cast<const float4*>(v + (int64_t)tok[tb] * R + j + 4);
+                f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) f[i] = 0.f;
+            }
+            split_bf16(f, vhi[tb][s], vlo[tb][s]);
+        }
+    }
+
+    const int chunks = (tile.cn + 63) >> 6;
+    const int c_begin = (chunks * wave) >> 2, c_end = (chunks * (wave + 1)) >> 2;
+    const int n_end = tile.c0 + tile.cn;
+    // feature row this lane loads for block b of a chunk: base + 16*(m/4) + 4*b + m%4
+    const int row_in_chunk = 16 * (m >> 2) + (m & 3);
+
+    for (int c = c_begin; c < c_end; ++c) {
+        const int n_base = tile.c0 + (c << 6);
+        op16 bop[4][KS];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int n = n_base + row_in_chunk + 4 * b;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int j = s * 32 + g * 8;
+                bop[b][s].u = (n < n_end && j < r) ? ld16(Bt + (int64_t)n * r + j) : uint4{0, 0, 0, 0};
+            }
+        }
+        const int n_lane = n_base + 16 * g;              // first of this lane's 16 features
+        const bool full = n_lane + 16 <= n_end;
+        uint4 yin[TB][2];
+        if (beta != 0.f) {
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                if (tok_ok[tb] && full) {
+                    const bf16_t* yp = y + (int64_t)tok[tb] * ldy + n_lane;
+                    yin[tb][0] = ld16(yp);
+                    yin[tb][1] = ld16(yp + 8);
+                }
+            }
+        }
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            floatx4 acc[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    acc[b] = mfma(bop[b][s], vhi[tb][s], acc[b]);
+                    acc[b] = mfma(bop[b][s], vlo[tb][s], acc[b]);
+                }
+            }
+            if (!tok_ok[tb]) continue;
+            bf16_t* yp = y + (int64_t)tok[tb] * ldy + n_lane;
+            if (full) {
+                uint32_t out[8];
+                const uint32_t* yi = reinterpret_cast<const uint32_t*>(&yin[tb][0]);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    float e0 = acc[q >> 1][(q & 1) * 2], e1 = acc[q >> 1][(q & 1) * 2 + 1];
+                    if (beta != 0.f) {
+                        e0 = fmaf(beta, bf16_to_f32((bf16_t)(yi[q] & 0xffffu)), e0);
+                        e1 = fmaf(beta, bf16_to_f32((bf16_t)(yi[q] >> 16)), e1);
+                    }
+                    out[q] = (uint32_t)f32_to_bf16(e0) | ((uint32_t)f32_to_bf16(e1) << 16);
+                }
+                *reinterpret_cast<uint4*>(yp) = uint4{out[0], out[1], out[2], out[3]};
+                *reinterpret_cast<uint4*>(yp + 8) = uint4{out[4], out[5], out[6], out[7]};
+            } else {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    if (n_lane + q < n_end) {
+                        float e = acc[q >> 2][q & 3];
+                        if (beta != 0.f) e = fmaf(beta, bf16_to_f32(yp[q]), e);
+                        yp[q] = f32_to_bf16(e);
+                    }
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void expand_tiled_kernel(
+    const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm, const int32_t* __restrict__ rank,
+    const float* __restrict__ v, int R, const bf16_t* const* __restrict__ Bt_ptrs,
+    bf16_t* __restrict__ y, int64_t ldy, int N, float beta)
+{
+    const lora_tile tile = tiles[blockIdx.x];
+    const int r = rank[tile.adapter];
+    const bf16_t* Bt = Bt_ptrs[tile.adapter];
+    const int tb = tile.shape & 15;
+    const int ks = (r + 31) >> 5;
+#define EXPAND_CASE(TB_, KS_) \
+    if (tb == TB_ && ks == KS_) { expand_tile<TB_, KS_>(tile, perm, v, R, Bt, r, y, ldy, N, beta); return; }
+    EXPAND_CASE(1, 1)
+    EXPAND_CASE(1, 2)
+    EXPAND_CASE(1, 3)
+    EXPAND_CASE(1, 4)
+    EXPAND_CASE(2, 1)
+    EXPAND_CASE(2, 2)
+    EXPAND_CASE(2, 3)
+    EXPAND_CASE(2, 4)
+    EXPAND_CASE(4, 1)
+    EXPAND_CASE(4, 2)
+#undef EXPAND_CASE
+}
+
+hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, const float* v,
+                               const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream)
+{
+    const int n_tiles = (int)p->expand_tiles.size();
+    if (n_tiles == 0) return hipSuccess;
+    expand_tiled_kernel<<<n_tiles, 256, 0, stream>>>(d.expand_tiles, d.perm, d.rank, v, p->R,
+        (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
+    return hipGetLastError();
+}

@@ -1,0 +1,51 @@
+// Internal layout of a batch plan.  Host tables are filled by planner.cpp (no
+// HIP there); the device mirror is managed by abi.hip.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/lora_abi.h"
+
+// Tile shape code of a lora_tile:  bits 0..3 = token blocks of 16 per wave
+// tile (TB), bits 4..7 = rank blocks of 16 per wave tile (JB, shrink only).
+static inline int32_t lora_shape_code(int tb, int jb) { return (tb & 15) | ((jb & 15) << 4); }
+static inline int lora_shape_tb(int32_t code) { return code & 15; }
+static inline int lora_shape_jb(int32_t code) { return (code >> 4) & 15; }
+
+struct lora_plan {
+    int32_t T = 0, S = 0, n_a = 0, K = 0, N = 0, dtype = 0, variant_req = 0;
+    int32_t R = 8;                 // v row stride (floats)
+    int32_t family = LORA_VARIANT_GENERAL;
+    int32_t shrink_waves = 4;      // wavefronts per shrink workgroup (split the K range), 1..8
+    int32_t shrink_max_blocks = 1; // largest TB*JB among the shrink tiles (sizes the LDS reduction buffer)
+    std::vector<int32_t> token_adapter, perm, group_adapter, group_offset, rank;
+    std::vector<float> scale;
+    std::vector<lora_tile> shrink_tiles, expand_tiles;
+    bool tiled_layout_ok = false;  // K and all active ranks multiples of 8
+
+    // device mirror (one allocation), valid when d_buf != nullptr
+    int device = -1;
+    void* d_buf = nullptr;
+    size_t d_bytes = 0;
+    void* h_stage = nullptr;       // pinned staging for the stream-ordered copy
+    int32_t* d_perm = nullptr;
+    int32_t* d_token_adapter = nullptr;
+    int32_t* d_rank = nullptr;
+    float* d_scale = nullptr;
+    lora_tile* d_shrink_tiles = nullptr;
+    lora_tile* d_expand_tiles = nullptr;
+};
+
+// Process-wide planner tunables (the analogue of the paper's shape -> tile
+// table, section 4.3.2).  Defaults come from measurements on MI355X.
+struct lora_tuning {
+    int32_t shrink_waves;          // wavefronts per shrink workgroup
+    int32_t shrink_tb2_min_rows;   // groups with at least this many tokens use 32-row wave tiles
+    int32_t shrink_max_jb;         // rank blocks of 16 per shrink tile (1, 2 or 4)
+    int32_t expand_wave_bytes;     // target bytes of Bt + y one expand wavefront streams
+    int32_t expand_tb2_min_rows;   // token-count thresholds for 32 / 64 row expand tiles
+    int32_t expand_tb4_min_rows;
+    int32_t tiled_min_tokens;      // AUTO: batches with fewer active tokens use the general kernels
+};
+extern lora_tuning g_lora_tuning;

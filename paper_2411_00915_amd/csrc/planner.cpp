@@ -1,0 +1,235 @@
+// Host-side batch planner: segment table -> token/adapter maps, stable grouping
+// by adapter, and the tile lists of the shrink and expand launches.
+//
+// Stands where ATMM consults its shape-keyed table for the tile configuration of
+// the input at hand (paper section 4.3.1, adaptive tiling; section 4.3.2, the
+// table built by profiling).  No HIP calls in this file: everything here runs,
+// and is tested, without a GPU.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "plan_internal.h"
+
+lora_tuning g_lora_tuning = {
+    /*shrink_waves*/ 8,
+    /*shrink_tb2_min_rows*/ 64,
+    /*shrink_max_jb*/ 4,
+    /*expand_wave_bytes*/ 16384,
+    /*expand_tb2_min_rows*/ 64,
+    /*expand_tb4_min_rows*/ 1 << 30,
+    /*tiled_min_tokens*/ 1,
+};
+
+extern "C" void lora_tuning_set(const int32_t* values, int32_t count)
+{
+    int32_t* dst = reinterpret_cast<int32_t*>(&g_lora_tuning);
+    const int32_t n = (int32_t)(sizeof(lora_tuning) / sizeof(int32_t));
+    for (int32_t i = 0; i < count && i < n; ++i)
+        if (values[i] > 0) dst[i] = values[i];
+}
+
+extern "C" void lora_tuning_get(int32_t* values, int32_t count)
+{
+    const int32_t* src = reinterpret_cast<const int32_t*>(&g_lora_tuning);
+    const int32_t n = (int32_t)(sizeof(lora_tuning) / sizeof(int32_t));
+    for (int32_t i = 0; i < count && i < n; ++i) values[i] = src[i];
+}
+
+static bool validate(const lora_batch_desc* d)
+{
+    if (d->num_tokens < 0 || d->num_segments < 0 || d->num_adapters < 0) return false;
+    if (d->k < 1 || d->n < 1) return false;
+    if (d->dtype != LORA_F32 && d->dtype != LORA_BF16) return false;
+    if (d->variant < LORA_VARIANT_AUTO || d->variant > LORA_VARIANT_TILED) return false;
+    if (!d->seg_indptr) return false;                       // even S = 0 has the single entry [0]
+    if (d->num_segments > 0 && !d->seg_adapter) return false;
+    if (d->num_adapters > 0 && (!d->adapter_rank || !d->adapter_scale)) return false;
+    if (d->seg_indptr[0] != 0) return false;
+    for (int32_t s = 0; s < d->num_segments; ++s) {
+        if (d->seg_indptr[s + 1] < d->seg_indptr[s]) return false;
+        const int32_t a = d->seg_adapter[s];
+        if (a < -1 || a >= d->num_adapters) return false;
+    }
+    if (d->seg_indptr[d->num_segments] != d->num_tokens) return false;
+    for (int32_t a = 0; a < d->num_adapters; ++a) {
+        if (d->adapter_rank[a] < 0 || d->adapter_rank[a] > LORA_MAX_RANK) return false;
+        if (!std::isfinite(d->adapter_scale[a])) return false;
+    }
+    return true;
+}
+
+static int32_t round_up(int32_t v, int32_t m) { return (v + m - 1) / m * m; }
+
+// Tile lists of the tiled (MFMA) family.  A shrink tile is 16*TB tokens of one
+// adapter times 16*JB of its rank indices over the whole K range (the
+// workgroup's wavefronts split K).  An expand tile is 16*TB tokens times a range
+// of output features that the workgroup's four wavefronts split evenly.
+static void build_tiles(lora_plan* p)
+{
+    const lora_tuning& tu = g_lora_tuning;
+    p->shrink_waves = std::max(1, std::min(tu.shrink_waves, 8));
+    p->shrink_max_blocks = 1;
+    const int G = (int)p->group_adapter.size();
+    for (int g = 0; g < G; ++g) {
+        const int32_t a = p->group_adapter[g];
+        const int32_t r = p->rank[a];
+        const int32_t lo = p->group_offset[g], hi = p->group_offset[g + 1];
+        const int32_t m = hi - lo;
+
+        // ---- shrink ----
+        {
+            const int jblocks = (r + 15) / 16;
+            const int jb = std::min(jblocks, std::max(1, std::min(tu.shrink_max_jb, 4)));
+            const int tb = (m >= tu.shrink_tb2_min_rows) ? 2 : 1;
+            for (int32_t row = lo; row < hi; row += 16 * tb) {
+                const int32_t nrows = std::min<int32_t>(16 * tb, hi - row);
+                for (int32_t j0 = 0; j0 < r; j0 += 16 * jb) {
+                    lora_tile t{};
+                    t.adapter = a; t.row0 = row; t.nrows = nrows;
+                    t.c0 = j0; t.cn = std::min<int32_t>(16 * jb, r - j0);
+                    const int tbk = nrows > 16 ? 2 : 1, jbk = (t.cn + 15) / 16;
+                    t.shape = lora_shape_code(tbk, jbk);
+                    p->shrink_max_blocks = std::max(p->shrink_max_blocks, tbk * jbk);
+                    p->shrink_tiles.push_back(t);
+                }
+            }
+        }
+        // ---- expand ----
+        {
+            int tb = 1;
+            if (m >= tu.expand_tb4_min_rows && r <= 64) tb = 4;
+            else if (m >= tu.expand_tb2_min_rows) tb = 2;
+            // output features per wavefront: a multiple of 64, sized so that the
+            // wavefront streams about expand_wave_bytes of Bt and y
+            const int64_t per_n = 2 * (int64_t)r + 4 * 16 * (int64_t)tb;
+            int32_t nw = (int32_t)std::max<int64_t>(64, (tu.expand_wave_bytes / per_n) / 64 * 64);
+            const int32_t n_tile = 4 * nw;
+            for (int32_t row = lo; row < hi; row += 16 * tb) {
+                const int32_t nrows = std::min<int32_t>(16 * tb, hi - row);
+                for (int32_t n0 = 0; n0 < p->N; n0 += n_tile) {
+                    lora_tile t{};
+                    t.adapter = a; t.row0 = row; t.nrows = nrows;
+                    t.c0 = n0; t.cn = std::min<int32_t>(n_tile, p->N - n0);
+                    const int tbk = (nrows + 15) / 16;
+                    t.shape = lora_shape_code(tbk == 3 ? 4 : tbk, 0);
+                    p->expand_tiles.push_back(t);
+                }
+            }
+        }
+    }
+    // Heaviest tiles first so the tail of the launch is made of light ones;
+    // stable, so equal descriptors give identical lists.
+    auto weight = [&](const lora_tile& t) { return (int64_t)((t.nrows + 15) / 16) * t.cn; };
+    std::stable_sort(p->shrink_tiles.begin(), p->shrink_tiles.end(),
+                     [&](const lora_tile& x, const lora_tile& y) { return weight(x) > weight(y); });
+}
+
+extern "C" lora_status lora_plan_create(const lora_batch_desc* d, lora_plan** out)
+{
+    if (!d || !out) return LORA_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!validate(d)) return LORA_ERR_INVALID_ARG;
+    lora_plan* p = new (std::nothrow) lora_plan();
+    if (!p) return LORA_ERR_NOMEM;
+    try {
+        p->T = d->num_tokens; p->S = d->num_segments; p->n_a = d->num_adapters;
+        p->K = d->k; p->N = d->n; p->dtype = d->dtype; p->variant_req = d->variant;
+        p->rank.assign(d->adapter_rank, d->adapter_rank + p->n_a);
+        p->scale.assign(d->adapter_scale, d->adapter_scale + p->n_a);
+
+        // adapter of every token; adapters of rank 0 count as "none"
+        p->token_adapter.assign((size_t)p->T, -1);
+        std::vector<int32_t> count((size_t)p->n_a + 1, 0);
+        for (int32_t s = 0; s < p->S; ++s) {
+            int32_t a = d->seg_adapter[s];
+            if (a >= 0 && p->rank[a] == 0) a = -1;
+            for (int32_t t = d->seg_indptr[s]; t < d->seg_indptr[s + 1]; ++t) p->token_adapter[t] = a;
+            if (a >= 0) count[a] += d->seg_indptr[s + 1] - d->seg_indptr[s];
+        }
+        // counting sort by adapter id = stable grouping
+        std::vector<int32_t> start((size_t)p->n_a + 1, 0);
+        int32_t max_rank = 0;
+        bool ranks_mult8 = true;
+        p->group_offset.push_back(0);
+        for (int32_t a = 0; a < p->n_a; ++a) {
+            start[a + 1] = start[a] + count[a];
+            if (count[a] > 0) {
+                p->group_adapter.push_back(a);
+                p->group_offset.push_back(start[a + 1]);
+                max_rank = std::max(max_rank, p->rank[a]);
+                if (p->rank[a] % 8) ranks_mult8 = false;
+            }
+        }
+        p->perm.resize((size_t)start[p->n_a]);
+        std::vector<int32_t> cursor(start.begin(), start.end() - 1);
+        for (int32_t t = 0; t < p->T; ++t) {
+            const int32_t a = p->token_adapter[t];
+            if (a >= 0) p->perm[cursor[a]++] = t;
+        }
+        int32_t table_max = 0;
+        for (int32_t a = 0; a < p->n_a; ++a) table_max = std::max(table_max, p->rank[a]);
+        p->R = std::max(8, round_up(table_max, 8));
+
+        // the tiled kernels take bf16, 16-byte rows (K and ranks multiples of 8), ranks <= 128
+        p->tiled_layout_ok = (p->dtype == LORA_BF16) && (p->K % 8 == 0) && ranks_mult8 && max_rank <= 128;
+        const int32_t n_active = (int32_t)p->perm.size();
+        if (p->variant_req == LORA_VARIANT_GENERAL || !p->tiled_layout_ok)
+            p->family = LORA_VARIANT_GENERAL;
+        else if (p->variant_req == LORA_VARIANT_TILED)
+            p->family = LORA_VARIANT_TILED;
+        else
+            p->family = (n_active >= g_lora_tuning.tiled_min_tokens) ? LORA_VARIANT_TILED : LORA_VARIANT_GENERAL;
+        if (p->family == LORA_VARIANT_TILED) build_tiles(p);
+    } catch (const std::bad_alloc&) {
+        delete p;
+        return LORA_ERR_NOMEM;
+    }
+    *out = p;
+    return LORA_OK;
+}
+
+extern "C" lora_status lora_plan_query(const lora_plan* p, int32_t* v_row_stride, size_t* v_bytes,
+                                       size_t* fused_workspace_bytes)
+{
+    if (!p) return LORA_ERR_INVALID_ARG;
+    const size_t vb = (size_t)p->T * (size_t)p->R * sizeof(float);
+    if (v_row_stride) *v_row_stride = p->R;
+    if (v_bytes) *v_bytes = vb;
+    if (fused_workspace_bytes) *fused_workspace_bytes = (vb + 255) / 256 * 256;
+    return LORA_OK;
+}
+
+extern "C" lora_status lora_plan_export(const lora_plan* p, lora_plan_view* v)
+{
+    if (!p || !v) return LORA_ERR_INVALID_ARG;
+    v->num_tokens = p->T;
+    v->num_active = (int32_t)p->perm.size();
+    v->num_groups = (int32_t)p->group_adapter.size();
+    v->v_row_stride = p->R;
+    v->kernel_family = p->family;
+    v->shrink_waves = p->shrink_waves;
+    v->token_adapter = p->token_adapter.data();
+    v->perm = p->perm.data();
+    v->group_adapter = p->group_adapter.data();
+    v->group_offset = p->group_offset.data();
+    v->shrink_tiles = p->shrink_tiles.data();
+    v->num_shrink_tiles = (int32_t)p->shrink_tiles.size();
+    v->expand_tiles = p->expand_tiles.data();
+    v->num_expand_tiles = (int32_t)p->expand_tiles.size();
+    return LORA_OK;
+}
+
+extern "C" const char* lora_status_str(lora_status s)
+{
+    switch (s) {
+        case LORA_OK: return "ok";
+        case LORA_ERR_INVALID_ARG: return "invalid argument";
+        case LORA_ERR_UNSUPPORTED: return "unsupported";
+        case LORA_ERR_NOMEM: return "out of memory";
+        case LORA_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case LORA_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}

@@ -1,0 +1,239 @@
+"""GPU parity: the HIP path (through the C ABI) against the float64 CPU oracle,
+element by element on the same seeded inputs.
+
+Tolerances (bf16 inputs, fp32 accumulation, one rounding of y to bf16):
+normwise relative error <= 2e-3 and max elementwise relative error <= 1e-2 over
+|y_ref| > 1e-2.  v is fp32 and is held to 1e-5 / 1e-4; the fp32 plumbing
+configuration to 1e-5 / 1e-4.  Per-call contracts: lora_expand is compared with
+y_in (as stored) + s (x A) B; the fused call with x W + s (x A) B end to end.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from paper_2411_00915_amd import binding as B
+from paper_2411_00915_amd import device, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL = (2e-3, 1e-2)
+F32_TOL = (1e-5, 1e-4)
+V_TOL = (1e-5, 1e-4)
+DEV = "cuda:0"
+
+
+def _tol(w):
+    return F32_TOL if w.dtype == "f32" else BF16_TOL
+
+
+def _assert_close(got, ref, tol, what):
+    nrm, elem = oracle.error_metrics(got, ref)
+    print(f"    {what}: normwise {nrm:.3e} elementwise {elem:.3e}", flush=True)
+    assert nrm <= tol[0], f"{what}: normwise {nrm:.3e} > {tol[0]}"
+    assert elem <= tol[1], f"{what}: elementwise {elem:.3e} > {tol[1]}"
+
+
+def _to_np(t):
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+def _y_in(w, seed=99):
+    rng = np.random.default_rng(seed)
+    y = rng.standard_normal((w.T, w.N), dtype=np.float32)
+    return wl.round_to_bf16(y) if w.dtype == "bf16" else y
+
+
+def run_delta_case(w, variant=B.LORA_VARIANT_AUTO, ld_pad=0, check_beta0=True, rows=None):
+    """shrink + expand through the ABI vs the oracle.  `rows` limits the oracle
+    comparison of y to a sample of tokens (v is always checked in full)."""
+    print(f"  case {w.name} T={w.T} K={w.K} N={w.N} variant={variant} ld_pad={ld_pad}", flush=True)
+    dl = device.to_device(w, DEV, with_w=False)
+    tdt = device.torch_dtype(w)
+    plan = device.make_plan(w, variant)
+    view = B.lora_plan_export(plan)
+    R, v_bytes, _ = B.lora_plan_query(plan)
+    tok = oracle.token_adapter(w.T, w.seg_indptr, w.seg_adapter)
+    ad = oracle.Adapters(w.adapter_rank, w.adapter_scale, w.A, w.B)
+    ldx, ldy = w.K + ld_pad, w.N + ld_pad
+    x = torch.zeros((w.T, ldx), dtype=tdt, device=DEV)
+    x[:, :w.K] = dl.x
+    CANARY = -12345.0
+    v = torch.full((max(w.T, 1), R), CANARY, dtype=torch.float32, device=DEV)
+    y0 = _y_in(w)
+    y = torch.full((max(w.T, 1), ldy), 7.0, dtype=tdt, device=DEV)
+    y[:w.T, :w.N] = torch.from_numpy(y0).to(DEV, tdt)
+
+    B.lora_shrink(plan, x, ldx, dl.At_ptrs, v)
+    B.lora_expand(plan, v, dl.Bt_ptrs, y, ldy, 1.0)
+    torch.cuda.synchronize()
+
+    v_np = _to_np(v)[:w.T]
+    v_ref = oracle.shrink(w.x, tok, ad, apply_scale=True, R=R)
+    ranks_tok = np.where(tok >= 0, w.adapter_rank[np.clip(tok, 0, None)], 0) if w.num_adapters else np.zeros(w.T, int)
+    valid = np.arange(R)[None, :] < ranks_tok[:, None]
+    assert np.all(v_np[~valid] == CANARY), "v written outside [0, r_a) or for a token without adapter"
+    if valid.any():
+        _assert_close(np.where(valid, v_np, 0.0), v_ref, V_TOL if w.dtype == "bf16" else F32_TOL, "v")
+
+    y_np = _to_np(y)[:w.T]
+    assert np.all(y_np[:, w.N:] == 7.0), "y written beyond column N"
+    no_ad = ranks_tok == 0
+    assert np.array_equal(y_np[no_ad, :w.N], y0[no_ad]), "rows without adapter must stay bit-identical"
+    sel = np.arange(w.T) if rows is None else np.asarray(rows)
+    if w.T:
+        y_ref = oracle.expand(w.x, tok, ad, w.N, y_in=y0[sel].astype(np.float64), rows=sel)
+        _assert_close(y_np[sel, :w.N], y_ref, _tol(w), "expand beta=1")
+
+    if check_beta0 and w.T:
+        y2 = torch.full((w.T, ldy), 3.0, dtype=tdt, device=DEV)
+        B.lora_expand(plan, v, dl.Bt_ptrs, y2, ldy, 0.0)
+        torch.cuda.synchronize()
+        y2_np = _to_np(y2)
+        assert np.all(y2_np[no_ad] == 3.0) and np.all(y2_np[:, w.N:] == 3.0)
+        d_ref = oracle.expand(w.x, tok, ad, w.N, rows=sel)
+        act = ~no_ad[sel]
+        if act.any():
+            _assert_close(y2_np[sel, :w.N][act], d_ref[act], _tol(w), "expand beta=0")
+        # run-to-run determinism (no atomics anywhere in the path)
+        v_b = torch.full_like(v, CANARY)
+        y_b = torch.full((w.T, ldy), 3.0, dtype=tdt, device=DEV)
+        B.lora_shrink(plan, x, ldx, dl.At_ptrs, v_b)
+        B.lora_expand(plan, v_b, dl.Bt_ptrs, y_b, ldy, 0.0)
+        torch.cuda.synchronize()
+        assert torch.equal(v_b, v) and torch.equal(y_b, y2), "two runs differ bitwise"
+    torch.cuda.synchronize()
+    plan.destroy()
+    return view
+
+
+def run_forward_case(w, n_sample=None, seed=5, variant=B.LORA_VARIANT_AUTO):
+    """base GEMM alone and the fused forward vs the oracle (on a row sample for
+    the big configurations: first/last token of every segment + random rows)."""
+    print(f"  forward {w.name} T={w.T} K={w.K} N={w.N} sample={n_sample}", flush=True)
+    dl = device.to_device(w, DEV, with_w=True)
+    tdt = device.torch_dtype(w)
+    plan = device.make_plan(w, variant)
+    R, v_bytes, ws_bytes = B.lora_plan_query(plan)
+    tok = oracle.token_adapter(w.T, w.seg_indptr, w.seg_adapter)
+    ad = oracle.Adapters(w.adapter_rank, w.adapter_scale, w.A, w.B)
+    if n_sample is None or n_sample >= w.T:
+        rows = np.arange(w.T)
+    else:
+        rng = np.random.default_rng(seed)
+        edge = np.unique(np.concatenate([w.seg_indptr[:-1], w.seg_indptr[1:] - 1]))
+        edge = edge[(edge >= 0) & (edge < w.T)]
+        if edge.size > n_sample // 2:
+            edge = rng.choice(edge, n_sample // 2, replace=False)
+        rest = rng.choice(w.T, n_sample - edge.size, replace=False)
+        rows = np.unique(np.concatenate([edge, rest]))
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
+    y = torch.full((w.T, w.N), 9.0, dtype=tdt, device=DEV)
+    B.lora_base_gemm(w.T, w.K, w.N, dl.dtype, dl.x, w.K, dl.Wt, w.K, y, w.N)
+    torch.cuda.synchronize()
+    base_ref = oracle.base(w.x, w.W, rows=rows)
+    _assert_close(_to_np(y)[rows], base_ref, _tol(w), "base gemm")
+
+    y.fill_(9.0)
+    B.lora_fused_forward(plan, dl.x, w.K, dl.Wt, w.K, dl.At_ptrs, dl.Bt_ptrs, y, w.N, ws, ws.numel())
+    torch.cuda.synchronize()
+    y_ref = oracle.forward(w.x, w.W, tok, ad, rows=rows)
+    _assert_close(_to_np(y)[rows], y_ref, _tol(w), "fused forward")
+    plan.destroy()
+
+
+# ---------------------------------------------------------------- configurations
+def test_cfg1_tiny_fp32():
+    w = wl.cfg1()
+    run_delta_case(w)
+    run_forward_case(w)
+
+
+def test_cfg2_decode():
+    w = wl.cfg2()
+    view = run_delta_case(w)
+    assert view["kernel_family"] == B.LORA_VARIANT_TILED
+    run_delta_case(w, B.LORA_VARIANT_GENERAL, check_beta0=False)
+    run_forward_case(w)
+
+
+@pytest.mark.parametrize("projection", [0, 1, 2, 3])
+def test_cfg3_prefill(projection):
+    w = wl.cfg3(projection)
+    run_delta_case(w, check_beta0=(projection == 0))
+    if projection == 0:
+        run_forward_case(w, n_sample=256)
+
+
+def test_cfg4_mixed():
+    w = wl.cfg4()
+    run_delta_case(w, rows=np.arange(0, w.T, 4))
+    run_forward_case(w, n_sample=192)
+
+
+def test_cfg4d_mixed_with_decode_requests():
+    w = wl.cfg4d(with_w=False)
+    run_delta_case(w, rows=np.arange(0, w.T, 4), check_beta0=False)
+
+
+@pytest.mark.parametrize("shape", ["attn", "mlp"])
+def test_cfg5_large(shape):
+    w = wl.cfg5(shape)
+    run_delta_case(w, rows=np.arange(0, w.T, 8), check_beta0=False)
+    run_forward_case(w, n_sample=128)
+
+
+# ---------------------------------------------------------------- edge cases
+@pytest.mark.parametrize("variant", [B.LORA_VARIANT_TILED, B.LORA_VARIANT_GENERAL])
+def test_ragged_small_cases(variant):
+    # several tiles and ragged tails: K not a multiple of 32, N not of 64 / 16,
+    # tokens without adapter, empty segments, heterogeneous scales, all ranks
+    for seed, (T, K, N) in enumerate([(37, 72, 200), (150, 328, 1000), (9, 64, 24), (300, 520, 72)]):
+        w = wl.random_case(100 + seed, T, K, N, 7, (8, 16, 24, 32, 40, 64, 128), max_seg=40,
+                           frac_none=0.25, scales=(0.5, 1.0, 2.0, -1.5, 3.25), empty_segments=True)
+        run_delta_case(w, variant)
+        run_delta_case(w, variant, ld_pad=8, check_beta0=False)
+        run_forward_case(w, variant=variant)
+
+
+def test_general_kernels_take_odd_layouts():
+    w = wl.random_case(200, 45, 77, 53, 5, (1, 3, 5, 12, 200, 256), max_seg=9, frac_none=0.2,
+                       scales=(1.0, 2.0, -0.5))
+    run_delta_case(w)                              # odd K, N, ranks: general family
+    run_delta_case(w, ld_pad=3, check_beta0=False)
+    run_forward_case(w)
+    wf = wl.random_case(201, 33, 40, 48, 3, (4, 8), dtype="f32", max_seg=6, frac_none=0.2)
+    run_delta_case(wf)
+    run_forward_case(wf)
+
+
+def test_degenerate_batches():
+    # no tokens at all
+    w = wl.random_case(300, 0, 64, 64, 2, (8,))
+    run_delta_case(w)
+    # every token without adapter: y must equal its input bit for bit, fused = x W
+    w = wl.random_case(301, 40, 64, 128, 2, (8, 16), frac_none=1.0)
+    run_delta_case(w)
+    run_forward_case(w)
+    # one long segment, one adapter, maximum tiled rank
+    w = wl.random_case(302, 257, 256, 192, 1, (128,), max_seg=1000)
+    run_delta_case(w)
+    # single token
+    w = wl.random_case(303, 1, 128, 64, 3, (8, 64))
+    run_delta_case(w)
+    run_forward_case(w)
+
+
+def test_tiled_request_with_unaligned_leading_dimension_is_refused():
+    w = wl.random_case(304, 20, 64, 64, 2, (8,))
+    dl = device.to_device(w, DEV, with_w=False)
+    plan = device.make_plan(w, B.LORA_VARIANT_TILED)
+    R, _, _ = B.lora_plan_query(plan)
+    x = torch.zeros((w.T, w.K + 3), dtype=torch.bfloat16, device=DEV)
+    v = torch.zeros((w.T, R), dtype=torch.float32, device=DEV)
+    with pytest.raises(B.LoraError) as e:
+        B.lora_shrink(plan, x, w.K + 3, dl.At_ptrs, v)
+    assert e.value.status == B.LORA_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    plan.destroy()

@@ -1,0 +1,192 @@
+"""Host-side tests of the C-ABI library: planner tables bit-exact against an
+independent derivation, tile lists cover the work exactly once, error paths,
+exported symbols.  No GPU needed (lora_plan_create is pure host code)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from oracle import plan_ref
+from paper_2411_00915_amd import binding as B
+from paper_2411_00915_amd import device, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _export(w, variant=B.LORA_VARIANT_AUTO):
+    p = device.make_plan(w, variant)
+    v = B.lora_plan_export(p)
+    q = B.lora_plan_query(p)
+    p.destroy()
+    return v, q
+
+
+def _check_tables(w, v):
+    tok, perm, ga, go = plan_ref.tables(w.T, w.seg_indptr, w.seg_adapter, w.adapter_rank)
+    assert v["num_tokens"] == w.T
+    assert np.array_equal(v["token_adapter"], tok)
+    assert np.array_equal(v["perm"], perm)
+    assert np.array_equal(v["group_adapter"], ga)
+    assert np.array_equal(v["group_offset"], go)
+    return tok, perm
+
+
+def _check_tiles(w, v, tok, perm):
+    if v["kernel_family"] != B.LORA_VARIANT_TILED:
+        assert v["shrink_tiles"].shape[0] == 0 and v["expand_tiles"].shape[0] == 0
+        return
+    max_r = int(w.adapter_rank.max()) if w.num_adapters else 0
+    st_ = [(t[0], t[1], t[2], t[3], t[4]) for t in v["shrink_tiles"]]
+    et_ = [(t[0], t[1], t[2], t[3], t[4]) for t in v["expand_tiles"]]
+    if len(perm):
+        plan_ref.check_cover(st_, tok, perm, max(max_r, 1), adapter_rank=w.adapter_rank, rank_axis=True)
+        plan_ref.check_cover(et_, tok, perm, w.N)
+    else:
+        assert not st_ and not et_
+    for t in v["shrink_tiles"]:
+        tb, jb = t[5] & 15, (t[5] >> 4) & 15
+        assert t[2] <= 16 * tb and t[4] <= 16 * jb and tb in (1, 2) and 1 <= jb <= 4
+        assert t[3] % 16 == 0
+    for t in v["expand_tiles"]:
+        tb = t[5] & 15
+        assert t[2] <= 16 * tb and tb in (1, 2, 4) and t[3] % 64 == 0
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg4d", "cfg5"])
+def test_config_tables_bit_exact(name):
+    w = wl.CONFIGS[name](with_w=False) if name != "cfg5" else wl.cfg5("attn", with_w=False)
+    # matrices are not needed here; the tables only depend on the integer structure
+    v, q = _export(w)
+    tok, perm = _check_tables(w, v)
+    _check_tiles(w, v, tok, perm)
+    R = max(8, (int(w.adapter_rank.max()) + 7) // 8 * 8)
+    assert q[0] == R and q[1] == w.T * R * 4 and q[2] >= q[1] and q[2] % 256 == 0
+    expect = B.LORA_VARIANT_GENERAL if w.dtype == "f32" else B.LORA_VARIANT_TILED
+    assert v["kernel_family"] == expect
+
+
+@settings(max_examples=150, deadline=None)
+@given(st.lists(st.tuples(st.integers(0, 40), st.integers(-1, 5)), min_size=0, max_size=20),
+       st.lists(st.sampled_from([0, 8, 16, 24, 32, 64, 128]), min_size=6, max_size=6),
+       st.sampled_from([64, 200, 1000]))
+def test_random_tables_and_tiles(segs, ranks, N):
+    lengths = [s[0] for s in segs]
+    ads = [s[1] for s in segs]
+    T = sum(lengths)
+    indptr = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32) if segs else np.zeros(1, np.int32)
+    w = wl.Workload("h", "bf16", T, 64, N, indptr, np.asarray(ads, np.int32), np.asarray(ranks, np.int32),
+                    np.ones(6, np.float32), np.zeros((T, 64), np.float32), None)
+    v, _ = _export(w, B.LORA_VARIANT_TILED)
+    tok, perm = _check_tables(w, v)
+    _check_tiles(w, v, tok, perm)
+
+
+def test_plan_is_deterministic():
+    w = wl.cfg4(with_w=False)
+    a, _ = _export(w)
+    b, _ = _export(w)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_unaligned_layouts_take_general_kernels():
+    base = dict(seed=1, T=10, N=32, n_a=2, with_w=False)
+    w = wl.random_case(K=36, ranks=(8,), **base)           # K not a multiple of 8
+    assert _export(w)[0]["kernel_family"] == B.LORA_VARIANT_GENERAL
+    w = wl.random_case(K=64, ranks=(5,), **base)           # rank not a multiple of 8
+    assert _export(w, B.LORA_VARIANT_TILED)[0]["kernel_family"] == B.LORA_VARIANT_GENERAL
+    w = wl.random_case(K=64, ranks=(256,), **base)         # rank beyond the tiled kernels
+    assert _export(w)[0]["kernel_family"] == B.LORA_VARIANT_GENERAL
+    w = wl.random_case(K=64, ranks=(8,), **base)
+    assert _export(w, B.LORA_VARIANT_GENERAL)[0]["kernel_family"] == B.LORA_VARIANT_GENERAL
+    assert _export(w)[0]["kernel_family"] == B.LORA_VARIANT_TILED
+
+
+def _desc(T=4, indptr=(0, 2, 4), seg_ad=(0, 1), ranks=(8, 16), scales=(1.0, 2.0), k=64, n=64,
+          dtype=B.LORA_BF16, variant=0, keep=None):
+    keep = keep if keep is not None else []
+    i = np.asarray(indptr, np.int32); a = np.asarray(seg_ad, np.int32)
+    r = np.asarray(ranks, np.int32); s = np.asarray(scales, np.float32)
+    keep.extend([i, a, r, s])
+    P = ctypes.POINTER(ctypes.c_int32); F = ctypes.POINTER(ctypes.c_float)
+    return B.BatchDesc(T, len(seg_ad), i.ctypes.data_as(P), a.ctypes.data_as(P), len(ranks),
+                       r.ctypes.data_as(P), s.ctypes.data_as(F), k, n, dtype, variant), keep
+
+
+def test_error_paths():
+    ok, keep = _desc()
+    st_, h = B.lora_plan_create_raw(ok)
+    assert st_ == B.LORA_OK and h
+    B._lib.lora_plan_destroy(h)
+    bad = [
+        _desc(indptr=(1, 2, 4)),            # does not start at 0
+        _desc(indptr=(0, 3, 2)),            # decreasing / wrong end
+        _desc(indptr=(0, 2, 3)),            # does not end at T
+        _desc(seg_ad=(0, 2)),               # adapter id out of range
+        _desc(seg_ad=(0, -2)),
+        _desc(ranks=(8, 257)),              # rank beyond LORA_MAX_RANK
+        _desc(ranks=(8, -1)),
+        _desc(scales=(1.0, float("nan"))),
+        _desc(scales=(float("inf"), 1.0)),
+        _desc(k=0), _desc(n=0), _desc(dtype=7), _desc(variant=9), _desc(T=-1),
+    ]
+    for d, keep in bad:
+        st_, h = B.lora_plan_create_raw(d)
+        assert st_ == B.LORA_ERR_INVALID_ARG and not h
+    assert B.lora_plan_create_raw(None)[0] == B.LORA_ERR_INVALID_ARG
+    d, keep = _desc()
+    d.seg_indptr = None
+    assert B.lora_plan_create_raw(d)[0] == B.LORA_ERR_INVALID_ARG
+    assert B._lib.lora_plan_query(None, None, None, None) == B.LORA_ERR_INVALID_ARG
+    B._lib.lora_plan_destroy(None)           # allowed
+    assert B.lora_status_str(B.LORA_ERR_WORKSPACE).startswith("workspace")
+    # empty batch and empty segments are valid
+    st_, h = B.lora_plan_create_raw(_desc(T=0, indptr=(0,), seg_ad=())[0])
+    assert st_ == B.LORA_OK
+    B._lib.lora_plan_destroy(h)
+    st_, h = B.lora_plan_create_raw(_desc(T=4, indptr=(0, 0, 4, 4), seg_ad=(0, 1, 0))[0])
+    assert st_ == B.LORA_OK
+    B._lib.lora_plan_destroy(h)
+
+
+def test_compute_calls_reject_bad_arguments_without_a_gpu():
+    w = wl.random_case(2, 12, 64, 64, 2, (8,), with_w=False)
+    p = device.make_plan(w)
+    L = B._lib
+    assert L.lora_shrink(p.handle, None, 64, None, None, None) == B.LORA_ERR_INVALID_ARG
+    assert L.lora_shrink(None, 256, 64, 256, 256, None) == B.LORA_ERR_INVALID_ARG
+    assert L.lora_shrink(p.handle, 256, 32, 256, 256, None) == B.LORA_ERR_INVALID_ARG       # ldx < K
+    assert L.lora_expand(p.handle, 256, 256, 256, 64, ctypes.c_float(0.5), None) == B.LORA_ERR_INVALID_ARG   # beta
+    assert L.lora_expand(p.handle, 256, 256, 256, 32, ctypes.c_float(1.0), None) == B.LORA_ERR_INVALID_ARG   # ldy < N
+    assert L.lora_base_gemm(4, 0, 4, B.LORA_BF16, 256, 8, 256, 8, 256, 8, None) == B.LORA_ERR_INVALID_ARG
+    assert L.lora_fused_forward(p.handle, 256, 64, 256, 64, 256, 256, 256, 64, 256, 16, None) == B.LORA_ERR_WORKSPACE
+    p.destroy()
+
+
+def test_tuning_roundtrip_changes_tiles():
+    before = B.lora_tuning_get()
+    try:
+        w = wl.cfg3(with_w=False)
+        a = _export(w)[0]
+        B.lora_tuning_set(shrink_tb2_min_rows=1 << 20, expand_tb2_min_rows=1 << 20, shrink_waves=4)
+        b = _export(w)[0]
+        assert b["shrink_waves"] == 4
+        assert b["shrink_tiles"].shape[0] == 2 * a["shrink_tiles"].shape[0]
+        tok, perm = _check_tables(w, b)
+        _check_tiles(w, b, tok, perm)
+    finally:
+        B.lora_tuning_set(**before)
+    assert B.lora_tuning_get() == before
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "lora_abi.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(lora_[a-z_]+)\s*\(", hdr))
+    assert {"lora_plan_create", "lora_shrink", "lora_expand", "lora_fused_forward"} <= names
+    for n in sorted(names):
+        assert hasattr(B._lib, n), f"{n} is declared in lora_abi.h but not exported"
+    assert names == set(B.EXPORTED)

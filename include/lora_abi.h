@@ -230,6 +230,23 @@ const char* lora_status_str(lora_status s);
 void lora_tuning_set(const int32_t* values, int32_t count);
 void lora_tuning_get(int32_t* values, int32_t count);
 
+/*
+ * Per-kernel timing for benchmarks (the paper times its operator over repeated
+ * rounds, section 6.3.2).  Between lora_timing_begin and lora_timing_end every
+ * kernel the library launches carries its own start/stop event pair, so the
+ * recorded time is the kernel's duration on its stream without launch gaps.
+ * lora_timing_end synchronises the device and folds the pairs into per-kernel
+ * statistics that lora_timing_read returns (microseconds).  Kernel ids run from
+ * 0 to lora_kernel_count()-1; lora_kernel_name gives the kernel's name as a
+ * profiler shows it.  Not for use while another thread launches.
+ */
+lora_status lora_timing_begin(void);
+lora_status lora_timing_end(void);
+lora_status lora_timing_read(int32_t kernel_id, int64_t* count, double* total_us,
+                             double* min_us, double* max_us);
+const char* lora_kernel_name(int32_t kernel_id);
+int32_t     lora_kernel_count(void);
+
 #ifdef __cplusplus
 }
 #endif

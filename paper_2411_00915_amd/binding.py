@@ -82,7 +82,17 @@ _lib.lora_tuning_set.argtypes = [_i32p, ctypes.c_int32]
 _lib.lora_tuning_get.restype = None
 _lib.lora_tuning_get.argtypes = [_i32p, ctypes.c_int32]
 
-EXPORTED = ["lora_plan_create", "lora_plan_destroy", "lora_plan_query", "lora_plan_export",
+_lib.lora_timing_begin.restype = ctypes.c_int
+_lib.lora_timing_end.restype = ctypes.c_int
+_lib.lora_timing_read.restype = ctypes.c_int
+_lib.lora_timing_read.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double),
+                                  ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+_lib.lora_kernel_name.restype = ctypes.c_char_p
+_lib.lora_kernel_name.argtypes = [ctypes.c_int32]
+_lib.lora_kernel_count.restype = ctypes.c_int32
+
+EXPORTED = ["lora_timing_begin", "lora_timing_end", "lora_timing_read", "lora_kernel_name", "lora_kernel_count",
+            "lora_plan_create", "lora_plan_destroy", "lora_plan_query", "lora_plan_export",
             "lora_plan_upload", "lora_shrink", "lora_expand", "lora_base_gemm",
             "lora_fused_forward", "lora_status_str", "lora_tuning_set", "lora_tuning_get"]
 
@@ -137,6 +147,24 @@ def lora_tuning_set(**kw) -> None:
         raise KeyError(f"unknown tuning fields: {sorted(unknown)}")
     buf = (ctypes.c_int32 * len(vals))(*vals)
     _lib.lora_tuning_set(buf, len(vals))
+
+
+def lora_timing_begin():
+    _check(_lib.lora_timing_begin(), "lora_timing_begin")
+
+
+def lora_timing_end() -> dict:
+    """Stop timing; returns {kernel name: dict(count, avg_us, min_us, max_us)} for kernels that ran."""
+    _check(_lib.lora_timing_end(), "lora_timing_end")
+    out = {}
+    for kid in range(_lib.lora_kernel_count()):
+        c, tot, mn, mx = ctypes.c_int64(), ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+        _check(_lib.lora_timing_read(kid, ctypes.byref(c), ctypes.byref(tot), ctypes.byref(mn), ctypes.byref(mx)),
+               "lora_timing_read")
+        if c.value:
+            out[_lib.lora_kernel_name(kid).decode()] = dict(count=int(c.value), avg_us=tot.value / c.value,
+                                                            min_us=mn.value, max_us=mx.value)
+    return out
 
 
 class Plan:

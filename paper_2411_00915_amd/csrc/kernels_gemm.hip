@@ -21,6 +21,7 @@
 // 16 consecutive features 16h .. 16h+15 of its token: 32-byte stores of y.
 #include "device_util.h"
 #include "kernels.h"
+#include "launch.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
@@ -234,10 +235,11 @@ hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int
     const int tiles_n = (N + BM - 1) / BM, tiles_t = (T + BT - 1) / BT;
     const int grid = tiles_n * tiles_t;
     if (p && !p->perm.empty())
-        gemm_tiled_kernel<true><<<grid, 256, 0, stream>>>(T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
+        LORA_LAUNCH(LORA_K_GEMM_TILED_DELTA, (gemm_tiled_kernel<true>), dim3(grid), dim3(256), 0, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
             (bf16_t*)y, ldy, tiles_n, tiles_t, d->token_adapter, d->rank, v, p->R, (const bf16_t* const*)Bt);
     else
-        gemm_tiled_kernel<false><<<grid, 256, 0, stream>>>(T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
-            (bf16_t*)y, ldy, tiles_n, tiles_t, nullptr, nullptr, nullptr, 0, nullptr);
+        LORA_LAUNCH(LORA_K_GEMM_TILED, (gemm_tiled_kernel<false>), dim3(grid), dim3(256), 0, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
+            (bf16_t*)y, ldy, tiles_n, tiles_t, (const int32_t*)nullptr, (const int32_t*)nullptr, (const float*)nullptr, 0,
+            (const bf16_t* const*)nullptr);
     return hipGetLastError();
 }

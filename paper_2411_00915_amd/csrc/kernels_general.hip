@@ -7,6 +7,7 @@
 // Operator: v = s_a (x A_a),  y = beta y + v B_a   (paper sections 2, 3.2, 4.3.1).
 #include "device_util.h"
 #include "kernels.h"
+#include "launch.h"
 
 template <typename T>
 __global__ __launch_bounds__(256) void shrink_general_kernel(
@@ -60,10 +61,10 @@ hipError_t launch_shrink_general(const lora_plan* p, const lora_dev_tables& d, c
     const int n_active = (int)p->perm.size();
     if (n_active == 0) return hipSuccess;
     if (p->dtype == LORA_F32)
-        shrink_general_kernel<float><<<n_active, 256, 0, stream>>>(d.perm, d.token_adapter, d.rank, d.scale,
+        LORA_LAUNCH(LORA_K_SHRINK_GENERAL, (shrink_general_kernel<float>), dim3(n_active), dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, d.scale,
             (const float*)x, ldx, (const float* const*)At, p->K, v, p->R);
     else
-        shrink_general_kernel<bf16_t><<<n_active, 256, 0, stream>>>(d.perm, d.token_adapter, d.rank, d.scale,
+        LORA_LAUNCH(LORA_K_SHRINK_GENERAL, (shrink_general_kernel<bf16_t>), dim3(n_active), dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, d.scale,
             (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, p->R);
     return hipGetLastError();
 }
@@ -76,10 +77,10 @@ hipError_t launch_expand_general(const lora_plan* p, const lora_dev_tables& d, c
     // the grid's x extent carries the tokens (up to 2^31-1); y splits N
     dim3 grid(n_active, (unsigned)std::min<int64_t>(((int64_t)p->N + 255) / 256, 64));
     if (p->dtype == LORA_F32)
-        expand_general_kernel<float><<<grid, 256, 0, stream>>>(d.perm, d.token_adapter, d.rank, v, p->R,
+        LORA_LAUNCH(LORA_K_EXPAND_GENERAL, (expand_general_kernel<float>), grid, dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, v, p->R,
             (const float* const*)Bt, (float*)y, ldy, p->N, beta);
     else
-        expand_general_kernel<bf16_t><<<grid, 256, 0, stream>>>(d.perm, d.token_adapter, d.rank, v, p->R,
+        LORA_LAUNCH(LORA_K_EXPAND_GENERAL, (expand_general_kernel<bf16_t>), grid, dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, v, p->R,
             (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
     return hipGetLastError();
 }
@@ -137,10 +138,10 @@ hipError_t launch_gemm_general(int32_t T, int32_t K, int32_t N, int32_t dtype, c
     const int32_t* rk = p ? d->rank : nullptr;
     const int R = p ? p->R : 0;
     if (dtype == LORA_F32)
-        gemm_general_kernel<float><<<grid, 256, 0, stream>>>(T, K, N, (const float*)x, ldx, (const float*)Wt, ldw,
+        LORA_LAUNCH(LORA_K_GEMM_GENERAL, (gemm_general_kernel<float>), grid, dim3(256), 0, stream, T, K, N, (const float*)x, ldx, (const float*)Wt, ldw,
             (float*)y, ldy, ta, rk, v, R, (const float* const*)Bt);
     else
-        gemm_general_kernel<bf16_t><<<grid, 256, 0, stream>>>(T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
+        LORA_LAUNCH(LORA_K_GEMM_GENERAL, (gemm_general_kernel<bf16_t>), grid, dim3(256), 0, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
             (bf16_t*)y, ldy, ta, rk, v, R, (const bf16_t* const*)Bt);
     return hipGetLastError();
 }

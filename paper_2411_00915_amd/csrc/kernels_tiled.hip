@@ -16,6 +16,7 @@
 //   and receives D[row 4*(l/16)+i][col l%16], i = 0..3.
 #include "device_util.h"
 #include "kernels.h"
+#include "launch.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
@@ -162,7 +163,7 @@ hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, con
     if (n_tiles == 0) return hipSuccess;
     const int W = p->shrink_waves;
     const size_t lds_bytes = (size_t)W * p->shrink_max_blocks * 64 * sizeof(floatx4);   // <= 8 * 8 KB
-    shrink_tiled_kernel<<<n_tiles, 64 * W, lds_bytes, stream>>>(d.shrink_tiles, d.perm, d.scale,
+    LORA_LAUNCH(LORA_K_SHRINK_TILED, shrink_tiled_kernel, dim3(n_tiles), dim3(64 * W), lds_bytes, stream, d.shrink_tiles, d.perm, d.scale,
         (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, p->R);
     return hipGetLastError();
 }
@@ -326,7 +327,7 @@ hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, con
 {
     const int n_tiles = (int)p->expand_tiles.size();
     if (n_tiles == 0) return hipSuccess;
-    expand_tiled_kernel<<<n_tiles, 256, 0, stream>>>(d.expand_tiles, d.perm, d.rank, v, p->R,
+    LORA_LAUNCH(LORA_K_EXPAND_TILED, expand_tiled_kernel, dim3(n_tiles), dim3(256), 0, stream, d.expand_tiles, d.perm, d.rank, v, p->R,
         (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
     return hipGetLastError();
 }

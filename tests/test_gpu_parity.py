@@ -3,7 +3,7 @@ element by element on the same seeded inputs.
 
 Tolerances (bf16 inputs, fp32 accumulation, one rounding of y to bf16):
 normwise relative error <= 2e-3 and max elementwise relative error <= 1e-2 over
-|y_ref| > 1e-2.  v is fp32 and is held to 1e-5 / 1e-4; the fp32 plumbing
+|y_ref| > 1e-2.  v is fp32 and is held to 1e-5 / 1e-3; the fp32 plumbing
 configuration to 1e-5 / 1e-4.  Per-call contracts: lora_expand is compared with
 y_in (as stored) + s (x A) B; the fused call with x W + s (x A) B end to end.
 """
@@ -20,7 +20,9 @@ pytestmark = pytest.mark.gpu
 
 BF16_TOL = (2e-3, 1e-2)
 F32_TOL = (1e-5, 1e-4)
-V_TOL = (1e-5, 1e-4)
+# v: fp32 sums of K <= 5120 exact products of O(1/sqrt(K)) size; the absolute error is a few 1e-6, which on
+# entries just above the 1e-2 threshold is a relative error of a few 1e-4
+V_TOL = (1e-5, 1e-3)
 DEV = "cuda:0"
 
 

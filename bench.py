@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg4d", "cfg5"])
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time budget of the oracle leg (0 = skip)")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a known-size reference for profiler counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU kernel path; it has no multi-GPU mode. "
@@ -108,7 +110,7 @@ def main():
 
     plan0 = device.make_plan(w)
     R, v_bytes, _ = B.lora_plan_query(plan0)
-    v = torch.zeros((w.T, R), dtype=torch.float32, device=dev)
+    v = torch.zeros(v_bytes // 4, dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
     abi_dtype = device.abi_dtype(w)
 
@@ -183,6 +185,13 @@ def main():
         except Exception as exc:  # report, never hide
             graph_us_per_layer = None
             print(f"bench.py: graph replay leg failed: {exc}", file=sys.stderr)
+
+    if args.calib_copy_mb > 0:
+        src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     sh_bytes, ex_bytes, flops = algorithmic_bytes(w, beta=1.0)
     names = {"shrink": "shrink_tiled_kernel", "expand": "expand_tiled_kernel"}

@@ -20,8 +20,12 @@
  *     B_a  is stored as  Bt_a [N, r_a]   Bt_a[n*r_a + j] = B_a[j,n]
  *     W    is stored as  Wt   [N, K]     Wt  [n*ldw + k] = W[k,n]
  *     x [T,K] row-major (ldx), y [T,N] row-major (ldy),
- *     v [T,R] row-major fp32, R = lora_plan_query's v_row_stride,
- *       v[t*R + j] for j < r_a; the rest of a row is never read or written.
+ *     v [P][T,R] row-major fp32, R = lora_plan_query's v_row_stride, P = the
+ *       plan's v_parts (1, 2 or 4): the shrink may split K over P workgroups,
+ *       each writing its partial sum to its own part; the value is
+ *       v[t,j] = sum_p v[(p*T + t)*R + j] for j < r_a, and every consumer in
+ *       the library adds the parts in that order.  The rest of a row is never
+ *       read or written.  lora_plan_query's v_bytes covers all P parts.
  *
  * OWNERSHIP.  The caller owns every device buffer (x, W, At_a, Bt_a, the two
  * device arrays of adapter pointers, v, y, workspace) and the HIP stream.  The
@@ -103,9 +107,9 @@ typedef struct {
     int32_t nrows;
     int32_t c0;
     int32_t cn;
-    int32_t shape;      /* kernel tile shape code chosen by the planner */
-    int32_t reserved0;
-    int32_t reserved1;
+    int32_t shape;      /* tile shape code chosen by the planner; shrink: bits 8..11 K part, 12..15 number of K parts */
+    int32_t reserved0;  /* rank of the adapter */
+    int32_t reserved1;  /* shrink tiles: bit pattern of the adapter's scale */
 } lora_tile;
 
 /* Read-only view of a plan's host tables (valid until lora_plan_destroy). */
@@ -116,6 +120,8 @@ typedef struct {
     int32_t        v_row_stride;    /* R */
     int32_t        kernel_family;   /* lora_variant actually chosen (GENERAL or TILED) */
     int32_t        shrink_waves;    /* wavefronts per workgroup of the shrink launch */
+    int32_t        v_parts;         /* P: number of partial sums v holds (see lora_shrink) */
+    int32_t        reserved;
     const int32_t* token_adapter;   /* [T]  adapter of each token, -1 = none */
     const int32_t* perm;            /* [num_active] tokens with an adapter, stably sorted by adapter */
     const int32_t* group_adapter;   /* [num_groups] ascending adapter ids */
@@ -143,7 +149,7 @@ typedef struct {
 lora_status lora_plan_create(const lora_batch_desc* desc, lora_plan** out);
 void        lora_plan_destroy(lora_plan* plan);   /* NULL is allowed */
 
-/* v_row_stride R (floats), bytes of the v buffer (T*R*4), and the bytes of
+/* v_row_stride R (floats), bytes of the v buffer (P*T*R*4), and the bytes of
  * workspace lora_fused_forward needs (it holds v).  Any out pointer may be NULL. */
 lora_status lora_plan_query(const lora_plan* plan, int32_t* v_row_stride,
                             size_t* v_bytes, size_t* fused_workspace_bytes);
@@ -165,7 +171,8 @@ lora_status lora_plan_upload(lora_plan* plan, void* hip_stream);
  * x: device, [T,K] row-major, leading dimension ldx (elements).
  * d_At_ptrs: device array [n_a] of device pointers to At_a [r_a,K]; entries of
  *   adapters no token uses are never dereferenced.
- * v: device, fp32 [T,R]; rows of tokens without adapter are left untouched.
+ * v: device, fp32 [P][T,R] (layout above); rows of tokens without adapter are
+ *   left untouched.
  * fp32 accumulation; the products of two bf16 values are exact in fp32.
  */
 lora_status lora_shrink(lora_plan* plan, const void* x, int64_t ldx,
@@ -224,7 +231,12 @@ const char* lora_status_str(lora_status s);
  * 1..4), expand_wave_bytes (bytes of Bt and y one expand wavefront streams),
  * expand_tb2_min_rows, expand_tb4_min_rows (token-count thresholds for 32- and
  * 64-token expand tiles), tiled_min_tokens (AUTO uses the general kernels below
- * this many active tokens).  Entries <= 0 keep the current value; plans made
+ * this many active tokens), shrink_small_waves (wavefronts per shrink workgroup
+ * when every tile is small, 1..16), shrink_small_jb (rank blocks of 16 per shrink
+ * tile for adapter groups below shrink_tb2_min_rows, 1..2), shrink_target_wgs
+ * (small launches split K over up to 4 workgroups per tile until they have this
+ * many workgroups).
+ * Entries <= 0 keep the current value; plans made
  * earlier are unaffected.  Host only.
  */
 void lora_tuning_set(const int32_t* values, int32_t count);

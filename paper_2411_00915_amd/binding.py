@@ -49,6 +49,7 @@ class PlanView(ctypes.Structure):
     _fields_ = [("num_tokens", ctypes.c_int32), ("num_active", ctypes.c_int32),
                 ("num_groups", ctypes.c_int32), ("v_row_stride", ctypes.c_int32),
                 ("kernel_family", ctypes.c_int32), ("shrink_waves", ctypes.c_int32),
+                ("v_parts", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("token_adapter", _i32p), ("perm", _i32p), ("group_adapter", _i32p), ("group_offset", _i32p),
                 ("shrink_tiles", ctypes.POINTER(Tile)), ("num_shrink_tiles", ctypes.c_int32),
                 ("expand_tiles", ctypes.POINTER(Tile)), ("num_expand_tiles", ctypes.c_int32)]
@@ -97,7 +98,8 @@ EXPORTED = ["lora_timing_begin", "lora_timing_end", "lora_timing_read", "lora_ke
             "lora_fused_forward", "lora_status_str", "lora_tuning_set", "lora_tuning_get"]
 
 TUNING_FIELDS = ["shrink_waves", "shrink_tb2_min_rows", "shrink_max_jb", "expand_wave_bytes",
-                 "expand_tb2_min_rows", "expand_tb4_min_rows", "tiled_min_tokens"]
+                 "expand_tb2_min_rows", "expand_tb4_min_rows", "tiled_min_tokens",
+                 "shrink_small_waves", "shrink_small_jb", "shrink_target_wgs"]
 
 
 class LoraError(RuntimeError):
@@ -241,6 +243,7 @@ def lora_plan_export(plan: Plan) -> dict:
 
     return dict(num_tokens=v.num_tokens, num_active=v.num_active, num_groups=v.num_groups,
                 v_row_stride=v.v_row_stride, kernel_family=v.kernel_family, shrink_waves=v.shrink_waves,
+                v_parts=v.v_parts,
                 token_adapter=arr(v.token_adapter, v.num_tokens), perm=arr(v.perm, v.num_active),
                 group_adapter=arr(v.group_adapter, v.num_groups),
                 group_offset=arr(v.group_offset, v.num_groups + 1),

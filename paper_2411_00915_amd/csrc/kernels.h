@@ -6,6 +6,17 @@
 
 #include "plan_internal.h"
 
+// v is [P][T][R] fp32: P partial sums (K split over workgroups), added in order by every consumer
+struct lora_vspec {
+    int R;
+    int P;
+    long long part;   // floats between consecutive parts (T * R)
+};
+static inline lora_vspec lora_vspec_of(const lora_plan* p)
+{
+    return lora_vspec{p->R, p->v_parts, (long long)p->T * p->R};
+}
+
 struct lora_dev_tables {
     const int32_t* perm;
     const int32_t* token_adapter;

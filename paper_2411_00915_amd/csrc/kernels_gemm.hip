@@ -58,8 +58,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     int T, int K, int N, const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ Wt, int64_t ldw,
     bf16_t* __restrict__ y, int64_t ldy, int tiles_n, int tiles_t,
     const int32_t* __restrict__ token_adapter, const int32_t* __restrict__ rank,
-    const float* __restrict__ v, int R, const bf16_t* const* __restrict__ Bt_ptrs)
+    const float* __restrict__ v, lora_vspec vsp, const bf16_t* const* __restrict__ Bt_ptrs)
 {
+    const int R = vsp.R;
     __shared__ uint4 lds_w[2][BM * 8];
     __shared__ uint4 lds_x[2][BT * 8];
 
@@ -176,6 +177,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
                         const float4 p0 = *reinterpret_cast<const float4*>(v + (int64_t)t * R + j);
                         const float4 p1 = *reinterpret_cast<const float4*>(v + (int64_t)t * R + j + 4);
                         f[0] = p0.x; f[1] = p0.y; f[2] = p0.z; f[3] = p0.w; f[4] = p1.x; f[5] = p1.y; f[6] = p1.z; f[7] = p1.w;
+                        for (int q = 1; q < vsp.P; ++q) {
+                            const float* vq = v + q * vsp.part + (int64_t)t * R + j;
+                            const float4 q0 = *reinterpret_cast<const float4*>(vq);
+                            const float4 q1 = *reinterpret_cast<const float4*>(vq + 4);
+                            f[0] += q0.x; f[1] += q0.y; f[2] += q0.z; f[3] += q0.w; f[4] += q1.x; f[5] += q1.y; f[6] += q1.z; f[7] += q1.w;
+                        }
                     } else {
 #pragma unroll
                         for (int i = 0; i < 8; ++i) f[i] = 0.f;
@@ -236,10 +243,10 @@ hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int
     const int grid = tiles_n * tiles_t;
     if (p && !p->perm.empty())
         LORA_LAUNCH(LORA_K_GEMM_TILED_DELTA, (gemm_tiled_kernel<true>), dim3(grid), dim3(256), 0, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
-            (bf16_t*)y, ldy, tiles_n, tiles_t, d->token_adapter, d->rank, v, p->R, (const bf16_t* const*)Bt);
+            (bf16_t*)y, ldy, tiles_n, tiles_t, d->token_adapter, d->rank, v, lora_vspec_of(p), (const bf16_t* const*)Bt);
     else
         LORA_LAUNCH(LORA_K_GEMM_TILED, (gemm_tiled_kernel<false>), dim3(grid), dim3(256), 0, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
-            (bf16_t*)y, ldy, tiles_n, tiles_t, (const int32_t*)nullptr, (const int32_t*)nullptr, (const float*)nullptr, 0,
+            (bf16_t*)y, ldy, tiles_n, tiles_t, (const int32_t*)nullptr, (const int32_t*)nullptr, (const float*)nullptr, lora_vspec{0, 1, 0},
             (const bf16_t* const*)nullptr);
     return hipGetLastError();
 }

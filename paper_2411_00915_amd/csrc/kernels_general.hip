@@ -14,8 +14,9 @@ __global__ __launch_bounds__(256) void shrink_general_kernel(
     const int32_t* __restrict__ perm, const int32_t* __restrict__ token_adapter,
     const int32_t* __restrict__ rank, const float* __restrict__ scale,
     const T* __restrict__ x, int64_t ldx, const T* const* __restrict__ At, int K,
-    float* __restrict__ v, int R)
+    float* __restrict__ v, lora_vspec vs)
 {
+    const int R = vs.R;
     const int t = perm[blockIdx.x];
     const int a = token_adapter[t];
     const int r = rank[a];
@@ -28,21 +29,29 @@ __global__ __launch_bounds__(256) void shrink_general_kernel(
         float acc = 0.f;
         for (int k = lane; k < K; k += 64) acc = fmaf(elem<T>::load(xt + k), elem<T>::load(Aj + k), acc);
         acc = wave_sum(acc);
-        if (lane == 0) v[(int64_t)t * R + j] = s * acc;
+        if (lane == 0) {
+            v[(int64_t)t * R + j] = s * acc;
+            for (int p = 1; p < vs.P; ++p) v[p * vs.part + (int64_t)t * R + j] = 0.f;   // this kernel does not split K
+        }
     }
 }
 
 template <typename T>
 __global__ __launch_bounds__(256) void expand_general_kernel(
     const int32_t* __restrict__ perm, const int32_t* __restrict__ token_adapter,
-    const int32_t* __restrict__ rank, const float* __restrict__ v, int R,
+    const int32_t* __restrict__ rank, const float* __restrict__ v, lora_vspec vsp,
     const T* const* __restrict__ Bt, T* __restrict__ y, int64_t ldy, int N, float beta)
 {
+    const int R = vsp.R;
     __shared__ float vs[LORA_MAX_RANK];
     const int t = perm[blockIdx.x];
     const int a = token_adapter[t];
     const int r = rank[a];
-    for (int j = threadIdx.x; j < r; j += 256) vs[j] = v[(int64_t)t * R + j];
+    for (int j = threadIdx.x; j < r; j += 256) {
+        float s = v[(int64_t)t * R + j];
+        for (int p = 1; p < vsp.P; ++p) s += v[p * vsp.part + (int64_t)t * R + j];
+        vs[j] = s;
+    }
     __syncthreads();
     const T* B = Bt[a];
     for (int n = blockIdx.y * 256 + threadIdx.x; n < N; n += gridDim.y * 256) {
@@ -62,10 +71,10 @@ hipError_t launch_shrink_general(const lora_plan* p, const lora_dev_tables& d, c
     if (n_active == 0) return hipSuccess;
     if (p->dtype == LORA_F32)
         LORA_LAUNCH(LORA_K_SHRINK_GENERAL, (shrink_general_kernel<float>), dim3(n_active), dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, d.scale,
-            (const float*)x, ldx, (const float* const*)At, p->K, v, p->R);
+            (const float*)x, ldx, (const float* const*)At, p->K, v, lora_vspec_of(p));
     else
         LORA_LAUNCH(LORA_K_SHRINK_GENERAL, (shrink_general_kernel<bf16_t>), dim3(n_active), dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, d.scale,
-            (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, p->R);
+            (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, lora_vspec_of(p));
     return hipGetLastError();
 }
 
@@ -77,10 +86,10 @@ hipError_t launch_expand_general(const lora_plan* p, const lora_dev_tables& d, c
     // the grid's x extent carries the tokens (up to 2^31-1); y splits N
     dim3 grid(n_active, (unsigned)std::min<int64_t>(((int64_t)p->N + 255) / 256, 64));
     if (p->dtype == LORA_F32)
-        LORA_LAUNCH(LORA_K_EXPAND_GENERAL, (expand_general_kernel<float>), grid, dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, v, p->R,
+        LORA_LAUNCH(LORA_K_EXPAND_GENERAL, (expand_general_kernel<float>), grid, dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, v, lora_vspec_of(p),
             (const float* const*)Bt, (float*)y, ldy, p->N, beta);
     else
-        LORA_LAUNCH(LORA_K_EXPAND_GENERAL, (expand_general_kernel<bf16_t>), grid, dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, v, p->R,
+        LORA_LAUNCH(LORA_K_EXPAND_GENERAL, (expand_general_kernel<bf16_t>), grid, dim3(256), 0, stream, d.perm, d.token_adapter, d.rank, v, lora_vspec_of(p),
             (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
     return hipGetLastError();
 }
@@ -94,8 +103,9 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(
     int T_, int K, int N, const T* __restrict__ x, int64_t ldx, const T* __restrict__ Wt, int64_t ldw,
     T* __restrict__ y, int64_t ldy,
     const int32_t* __restrict__ token_adapter, const int32_t* __restrict__ rank,
-    const float* __restrict__ v, int R, const T* const* __restrict__ Bt)
+    const float* __restrict__ v, lora_vspec vsp, const T* const* __restrict__ Bt)
 {
+    const int R = vsp.R;
     __shared__ float xs[16][17];
     __shared__ float ws[16][17];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -119,7 +129,11 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(
                 const int r = rank[a];
                 const T* Bn = Bt[a] + (int64_t)n * r;
                 float d = 0.f;
-                for (int j = 0; j < r; ++j) d = fmaf(v[(int64_t)t * R + j], elem<T>::load(Bn + j), d);
+                for (int j = 0; j < r; ++j) {
+                    float vj = v[(int64_t)t * R + j];
+                    for (int q = 1; q < vsp.P; ++q) vj += v[q * vsp.part + (int64_t)t * R + j];
+                    d = fmaf(vj, elem<T>::load(Bn + j), d);
+                }
                 acc += d;
             }
         }
@@ -136,7 +150,7 @@ hipError_t launch_gemm_general(int32_t T, int32_t K, int32_t N, int32_t dtype, c
     dim3 grid((N + 15) / 16, (T + 15) / 16);
     const int32_t* ta = p ? d->token_adapter : nullptr;
     const int32_t* rk = p ? d->rank : nullptr;
-    const int R = p ? p->R : 0;
+    const lora_vspec R = p ? lora_vspec_of(p) : lora_vspec{0, 1, 0};
     if (dtype == LORA_F32)
         LORA_LAUNCH(LORA_K_GEMM_GENERAL, (gemm_general_kernel<float>), grid, dim3(256), 0, stream, T, K, N, (const float*)x, ldx, (const float*)Wt, ldw,
             (float*)y, ldy, ta, rk, v, R, (const float* const*)Bt);

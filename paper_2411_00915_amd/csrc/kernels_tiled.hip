@@ -39,13 +39,14 @@ __device__ __forceinline__ floatx4 mfma(const op16& a, const op16& b, floatx4 c)
 // tokens, so a lane ends up with 4 consecutive rank entries of one token.
 // The workgroup's wavefronts take contiguous slices of K; partial sums meet in
 // LDS, are scaled by s_a and stored once (deterministic, no atomics).
-template <int TB, int JB>
+template <int TB, int JB, int U>
 __device__ __forceinline__ void shrink_tile(
-    const lora_tile tile, const int32_t* __restrict__ perm, const float* __restrict__ scale,
+    const lora_tile tile, const int32_t* __restrict__ perm,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
-    float* __restrict__ v, int R, floatx4* lds)
+    float* __restrict__ v, lora_vspec vsp, floatx4* lds)
 {
-    constexpr int U = (TB * JB >= 8) ? 2 : 4;          // k-steps whose loads are issued together
+    // U = k-steps whose loads are issued together before any of them is consumed
+    const int R = vsp.R;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
     const int m = lane & 15, g = lane >> 4;
 
@@ -64,15 +65,33 @@ __device__ __forceinline__ void shrink_tile(
         arow[jb] = At + (int64_t)(tile.c0 + j) * K + g * 8;
     }
 
+    // Output element this thread stores after the reduction (threads beyond the
+    // tile's TB*JB*64 float4 slots store nothing).  Looked up now: no global load
+    // is left between the reduction and the store.  The tile carries s_a.
+    const float s_a = __int_as_float(tile.reserved1);
+    int out_t = -1, out_j = 0;
+    if ((int)threadIdx.x < TB * JB * 64) {
+        const int l = threadIdx.x & 63, blk = threadIdx.x >> 6;
+        const int row = (blk / JB) * 16 + (l & 15);
+        const int j = (blk % JB) * 16 + 4 * (l >> 4);
+        if (row < tile.nrows && j < tile.cn) {
+            out_t = perm[tile.row0 + row];
+            out_j = tile.c0 + j;
+        }
+    }
+
     floatx4 acc[TB][JB];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) acc[tb][jb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+    // this tile's K part, then this wavefront's slice of it (in MFMA k-steps of 32)
     const int steps = (K + 31) >> 5;
-    const int s_begin = (int)(((int64_t)steps * wave) / W);
-    const int s_end = (int)(((int64_t)steps * (wave + 1)) / W);
+    const int kpart = (tile.shape >> 8) & 15, kparts = (tile.shape >> 12) & 15;
+    const int p_begin = (int)(((int64_t)steps * kpart) / kparts), p_end = (int)(((int64_t)steps * (kpart + 1)) / kparts);
+    const int s_begin = p_begin + (int)(((int64_t)(p_end - p_begin) * wave) / W);
+    const int s_end = p_begin + (int)(((int64_t)(p_end - p_begin) * (wave + 1)) / W);
     const int kmax = K - g * 8;                          // chunk at offset k is inside the row iff k < kmax
 
     int s = s_begin;
@@ -114,45 +133,57 @@ __device__ __forceinline__ void shrink_tile(
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) lds[((wave * TB + tb) * JB + jb) * 64 + lane] = acc[tb][jb];
     __syncthreads();
-    const float s_a = scale[tile.adapter];
-    for (int e = threadIdx.x; e < TB * JB * 64; e += blockDim.x) {
-        floatx4 sum = lds[e];
-        for (int w = 1; w < W; ++w) {
-            const floatx4 o = lds[w * TB * JB * 64 + e];
-            sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
-        }
-        const int l = e & 63, blk = e >> 6;
-        const int tb = blk / JB, jb = blk % JB;
-        const int row = tb * 16 + (l & 15);
-        const int j = jb * 16 + 4 * (l >> 4);
-        if (row < tile.nrows && j < tile.cn) {
-            const int t = perm[tile.row0 + row];
-            float4 o = make_float4(s_a * sum[0], s_a * sum[1], s_a * sum[2], s_a * sum[3]);
-            *reinterpret_cast<float4*>(v + (int64_t)t * R + tile.c0 + j) = o;
-        }
+    if (out_t >= 0) {
+        // all partials are fetched before the first add, so the LDS reads overlap
+        floatx4 part[16];
+#pragma unroll
+        for (int w = 0; w < 16; ++w)
+            part[w] = (w < W) ? lds[w * TB * JB * 64 + (int)threadIdx.x] : floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 8; st > 0; st >>= 1)
+#pragma unroll
+            for (int w = 0; w < st; ++w) part[w] += part[w + st];
+        const float4 o = make_float4(s_a * part[0][0], s_a * part[0][1], s_a * part[0][2], s_a * part[0][3]);
+        *reinterpret_cast<float4*>(v + kpart * vsp.part + (int64_t)out_t * R + out_j) = o;
     }
 }
 
 extern __shared__ floatx4 shrink_lds[];
 
+// Two builds of the shrink kernel.  "small": up to 16 wavefronts per workgroup,
+// tiles of 16 tokens x 16 or 32 rank rows, every wavefront issues 8 (4) k-steps of
+// loads at once -- the decode regime, where the whole launch is little more than
+// one round of HBM latency.  "big": up to 8 wavefronts, every tile shape.
+__global__ __launch_bounds__(1024) void shrink_tiled_small_kernel(
+    const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm, const float* __restrict__ scale,
+    const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* const* __restrict__ At_ptrs, int K,
+    float* __restrict__ v, lora_vspec R)
+{
+    const lora_tile tile = tiles[blockIdx.x];
+    const bf16_t* At = At_ptrs[tile.adapter];
+    const int jb = (tile.shape >> 4) & 15;
+    if (jb == 1) shrink_tile<1, 1, 8>(tile, perm, x, ldx, At, K, v, R, shrink_lds);
+    else shrink_tile<1, 2, 4>(tile, perm, x, ldx, At, K, v, R, shrink_lds);
+}
+
 __global__ __launch_bounds__(512) void shrink_tiled_kernel(
     const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm, const float* __restrict__ scale,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* const* __restrict__ At_ptrs, int K,
-    float* __restrict__ v, int R)
+    float* __restrict__ v, lora_vspec R)
 {
     const lora_tile tile = tiles[blockIdx.x];
     const bf16_t* At = At_ptrs[tile.adapter];
     const int tb = tile.shape & 15, jb = (tile.shape >> 4) & 15;
-#define SHRINK_CASE(TB_, JB_) \
-    if (tb == TB_ && jb == JB_) { shrink_tile<TB_, JB_>(tile, perm, scale, x, ldx, At, K, v, R, shrink_lds); return; }
-    SHRINK_CASE(1, 1)
-    SHRINK_CASE(1, 2)
-    SHRINK_CASE(1, 3)
-    SHRINK_CASE(1, 4)
-    SHRINK_CASE(2, 1)
-    SHRINK_CASE(2, 2)
-    SHRINK_CASE(2, 3)
-    SHRINK_CASE(2, 4)
+#define SHRINK_CASE(TB_, JB_, U_) \
+    if (tb == TB_ && jb == JB_) { shrink_tile<TB_, JB_, U_>(tile, perm, x, ldx, At, K, v, R, shrink_lds); return; }
+    SHRINK_CASE(1, 1, 8)
+    SHRINK_CASE(1, 2, 4)
+    SHRINK_CASE(1, 3, 4)
+    SHRINK_CASE(1, 4, 4)
+    SHRINK_CASE(2, 1, 4)
+    SHRINK_CASE(2, 2, 4)
+    SHRINK_CASE(2, 3, 2)
+    SHRINK_CASE(2, 4, 2)
 #undef SHRINK_CASE
 }
 
@@ -162,9 +193,13 @@ hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, con
     const int n_tiles = (int)p->shrink_tiles.size();
     if (n_tiles == 0) return hipSuccess;
     const int W = p->shrink_waves;
-    const size_t lds_bytes = (size_t)W * p->shrink_max_blocks * 64 * sizeof(floatx4);   // <= 8 * 8 KB
-    LORA_LAUNCH(LORA_K_SHRINK_TILED, shrink_tiled_kernel, dim3(n_tiles), dim3(64 * W), lds_bytes, stream, d.shrink_tiles, d.perm, d.scale,
-        (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, p->R);
+    const size_t lds_bytes = (size_t)W * p->shrink_max_blocks * 64 * sizeof(floatx4);   // <= 64 KB
+    if (p->shrink_small)
+        LORA_LAUNCH(LORA_K_SHRINK_TILED, shrink_tiled_small_kernel, dim3(n_tiles), dim3(64 * W), lds_bytes, stream,
+                    d.shrink_tiles, d.perm, d.scale, (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, lora_vspec_of(p));
+    else
+        LORA_LAUNCH(LORA_K_SHRINK_TILED, shrink_tiled_kernel, dim3(n_tiles), dim3(64 * W), lds_bytes, stream,
+                    d.shrink_tiles, d.perm, d.scale, (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, lora_vspec_of(p));
     return hipGetLastError();
 }
 
@@ -191,16 +226,23 @@ __device__ __forceinline__ void split_bf16(const float* f, op16& hi, op16& lo)
     lo.u = uint4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
 }
 
-template <int TB, int KS>
+// NP = number of v parts when known at compile time (0: read it from vsp, up to 4)
+template <int TB, int KS, bool PREFETCH, int NP>
 __device__ __forceinline__ void expand_tile(
-    const lora_tile tile, const int32_t* __restrict__ perm, const float* __restrict__ v, int R,
+    const lora_tile tile, const int32_t* __restrict__ perm, const float* __restrict__ v, lora_vspec vsp,
     const bf16_t* __restrict__ Bt, int r, bf16_t* __restrict__ y, int64_t ldy, int N, float beta)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
+    const int R = vsp.R;
 
-    // v operands (columns = tokens): lane holds v[token m][32 s + 8 g .. +7]
-    op16 vhi[TB][KS], vlo[TB][KS];
+    const int chunks = (tile.cn + 63) >> 6;
+    const int c_begin = (chunks * wave) >> 2, c_end = (chunks * (wave + 1)) >> 2;
+    if (c_begin >= c_end) return;
+    const int n_end = tile.c0 + tile.cn;
+    // feature row this lane loads for block b of a chunk: base + 16*(m/4) + 4*b + m%4
+    const int row_in_chunk = 16 * (m >> 2) + (m & 3);
+
     int tok[TB];
     bool tok_ok[TB];
 #pragma unroll
@@ -208,31 +250,10 @@ __device__ __forceinline__ void expand_tile(
         const int row = tb * 16 + m;
         tok_ok[tb] = row < tile.nrows;
         tok[tb] = perm[tile.row0 + (tok_ok[tb] ? row : 0)];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int j = s * 32 + g * 8;
-            float f[8];
-            if (j < r) {
-                const float4 a = *reinterpret_cast<const float4*>(v + (int64_t)tok[tb] * R + j);
-                const float4 b = *reinterpret_cast<const float4*>(v + (int64_t)tok[tb] * R + j + 4);
-                f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) f[i] = 0.f;
-            }
-            split_bf16(f, vhi[tb][s], vlo[tb][s]);
-        }
     }
 
-    const int chunks = (tile.cn + 63) >> 6;
-    const int c_begin = (chunks * wave) >> 2, c_end = (chunks * (wave + 1)) >> 2;
-    const int n_end = tile.c0 + tile.cn;
-    // feature row this lane loads for block b of a chunk: base + 16*(m/4) + 4*b + m%4
-    const int row_in_chunk = 16 * (m >> 2) + (m & 3);
-
-    for (int c = c_begin; c < c_end; ++c) {
+    auto load_b = [&](int c, op16 (&bop)[4][KS]) {
         const int n_base = tile.c0 + (c << 6);
-        op16 bop[4][KS];
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const int n = n_base + row_in_chunk + 4 * b;
@@ -242,19 +263,70 @@ __device__ __forceinline__ void expand_tile(
                 bop[b][s].u = (n < n_end && j < r) ? ld16(Bt + (int64_t)n * r + j) : uint4{0, 0, 0, 0};
             }
         }
-        const int n_lane = n_base + 16 * g;              // first of this lane's 16 features
+    };
+    auto load_y = [&](int c, uint4 (&yin)[TB][2]) {
+        const int n_lane = tile.c0 + (c << 6) + 16 * g;
         const bool full = n_lane + 16 <= n_end;
-        uint4 yin[TB][2];
-        if (beta != 0.f) {
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) {
-                if (tok_ok[tb] && full) {
-                    const bf16_t* yp = y + (int64_t)tok[tb] * ldy + n_lane;
-                    yin[tb][0] = ld16(yp);
-                    yin[tb][1] = ld16(yp + 8);
-                }
+        for (int tb = 0; tb < TB; ++tb) {
+            if (beta != 0.f && tok_ok[tb] && full) {
+                const bf16_t* yp = y + (int64_t)tok[tb] * ldy + n_lane;
+                yin[tb][0] = ld16(yp);
+                yin[tb][1] = ld16(yp + 8);
+            } else {
+                yin[tb][0] = uint4{0, 0, 0, 0};
+                yin[tb][1] = uint4{0, 0, 0, 0};
             }
         }
+    };
+
+    // The loads that do not depend on v go out first: Bt and y of the first chunk.
+    op16 bop[4][KS];
+    uint4 yin[TB][2];
+    load_b(c_begin, bop);
+    load_y(c_begin, yin);
+
+    // v operands (MFMA columns = tokens): lane holds v[token m][32 s + 8 g .. +7],
+    // the sum of the P partial sums, split into two bf16 terms
+    op16 vhi[TB][KS], vlo[TB][KS];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int j = s * 32 + g * 8;
+            constexpr int MP = NP ? NP : 4;
+            float4 pa[4], pb[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {                  // all parts are fetched before the first add
+                if (q < MP && j < r && q < vsp.P) {
+                    const float* vq = v + q * vsp.part + (int64_t)tok[tb] * R + j;
+                    pa[q] = *reinterpret_cast<const float4*>(vq);
+                    pb[q] = *reinterpret_cast<const float4*>(vq + 4);
+                } else {
+                    pa[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    pb[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+            float f[8];
+            f[0] = ((pa[0].x + pa[1].x) + pa[2].x) + pa[3].x; f[1] = ((pa[0].y + pa[1].y) + pa[2].y) + pa[3].y;
+            f[2] = ((pa[0].z + pa[1].z) + pa[2].z) + pa[3].z; f[3] = ((pa[0].w + pa[1].w) + pa[2].w) + pa[3].w;
+            f[4] = ((pb[0].x + pb[1].x) + pb[2].x) + pb[3].x; f[5] = ((pb[0].y + pb[1].y) + pb[2].y) + pb[3].y;
+            f[6] = ((pb[0].z + pb[1].z) + pb[2].z) + pb[3].z; f[7] = ((pb[0].w + pb[1].w) + pb[2].w) + pb[3].w;
+            split_bf16(f, vhi[tb][s], vlo[tb][s]);
+        }
+    }
+
+    for (int c = c_begin; c < c_end; ++c) {
+        // next chunk's loads are in flight while this chunk is multiplied and stored
+        op16 bnext[4][KS];
+        uint4 ynext[TB][2];
+        const bool more = c + 1 < c_end;
+        if (PREFETCH && more) {
+            load_b(c + 1, bnext);
+            load_y(c + 1, ynext);
+        }
+        const int n_lane = tile.c0 + (c << 6) + 16 * g;      // first of this lane's 16 features
+        const bool full = n_lane + 16 <= n_end;
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
             floatx4 acc[4];
@@ -294,21 +366,49 @@ __device__ __forceinline__ void expand_tile(
                 }
             }
         }
+        if (more) {
+            if (PREFETCH) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) bop[b][s] = bnext[b][s];
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) { yin[tb][0] = ynext[tb][0]; yin[tb][1] = ynext[tb][1]; }
+            } else {
+                load_b(c + 1, bop);
+                load_y(c + 1, yin);
+            }
+        }
     }
 }
 
-__global__ __launch_bounds__(256) void expand_tiled_kernel(
-    const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm, const int32_t* __restrict__ rank,
-    const float* __restrict__ v, int R, const bf16_t* const* __restrict__ Bt_ptrs,
+// "small" build: 16-token tiles of ranks <= 64 only (the decode regime); few
+// registers, so eight wavefronts fit on a SIMD and the whole launch is resident at once.
+template <int NP>
+__global__ __launch_bounds__(256) void expand_tiled_small_kernel(
+    const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm,
+    const float* __restrict__ v, lora_vspec R, const bf16_t* const* __restrict__ Bt_ptrs,
     bf16_t* __restrict__ y, int64_t ldy, int N, float beta)
 {
     const lora_tile tile = tiles[blockIdx.x];
-    const int r = rank[tile.adapter];
+    const int r = tile.reserved0;                       // the planner stores the adapter's rank here
+    const bf16_t* Bt = Bt_ptrs[tile.adapter];
+    if (r <= 32) expand_tile<1, 1, false, NP>(tile, perm, v, R, Bt, r, y, ldy, N, beta);
+    else expand_tile<1, 2, false, NP>(tile, perm, v, R, Bt, r, y, ldy, N, beta);
+}
+
+__global__ __launch_bounds__(256) void expand_tiled_kernel(
+    const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm,
+    const float* __restrict__ v, lora_vspec R, const bf16_t* const* __restrict__ Bt_ptrs,
+    bf16_t* __restrict__ y, int64_t ldy, int N, float beta)
+{
+    const lora_tile tile = tiles[blockIdx.x];
+    const int r = tile.reserved0;
     const bf16_t* Bt = Bt_ptrs[tile.adapter];
     const int tb = tile.shape & 15;
     const int ks = (r + 31) >> 5;
 #define EXPAND_CASE(TB_, KS_) \
-    if (tb == TB_ && ks == KS_) { expand_tile<TB_, KS_>(tile, perm, v, R, Bt, r, y, ldy, N, beta); return; }
+    if (tb == TB_ && ks == KS_) { expand_tile<TB_, KS_, (TB_ * KS_ <= 4), 0>(tile, perm, v, R, Bt, r, y, ldy, N, beta); return; }
     EXPAND_CASE(1, 1)
     EXPAND_CASE(1, 2)
     EXPAND_CASE(1, 3)
@@ -327,7 +427,17 @@ hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, con
 {
     const int n_tiles = (int)p->expand_tiles.size();
     if (n_tiles == 0) return hipSuccess;
-    LORA_LAUNCH(LORA_K_EXPAND_TILED, expand_tiled_kernel, dim3(n_tiles), dim3(256), 0, stream, d.expand_tiles, d.perm, d.rank, v, p->R,
-        (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
+    if (p->expand_small && p->v_parts == 1)
+        LORA_LAUNCH(LORA_K_EXPAND_TILED, expand_tiled_small_kernel<1>, dim3(n_tiles), dim3(256), 0, stream,
+                    d.expand_tiles, d.perm, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
+    else if (p->expand_small && p->v_parts == 2)
+        LORA_LAUNCH(LORA_K_EXPAND_TILED, expand_tiled_small_kernel<2>, dim3(n_tiles), dim3(256), 0, stream,
+                    d.expand_tiles, d.perm, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
+    else if (p->expand_small)
+        LORA_LAUNCH(LORA_K_EXPAND_TILED, expand_tiled_small_kernel<4>, dim3(n_tiles), dim3(256), 0, stream,
+                    d.expand_tiles, d.perm, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
+    else
+        LORA_LAUNCH(LORA_K_EXPAND_TILED, expand_tiled_kernel, dim3(n_tiles), dim3(256), 0, stream,
+                    d.expand_tiles, d.perm, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
     return hipGetLastError();
 }

@@ -12,12 +12,18 @@
 static inline int32_t lora_shape_code(int tb, int jb) { return (tb & 15) | ((jb & 15) << 4); }
 static inline int lora_shape_tb(int32_t code) { return code & 15; }
 static inline int lora_shape_jb(int32_t code) { return (code >> 4) & 15; }
+// shrink tiles only: bits 8..11 = index of the tile's K part, bits 12..15 = number of K parts
+static inline int lora_shape_part(int32_t code) { return (code >> 8) & 15; }
+static inline int lora_shape_parts(int32_t code) { return (code >> 12) & 15; }
 
 struct lora_plan {
     int32_t T = 0, S = 0, n_a = 0, K = 0, N = 0, dtype = 0, variant_req = 0;
     int32_t R = 8;                 // v row stride (floats)
+    int32_t v_parts = 1;           // v holds this many partial sums [P][T][R]; consumers add them in order
     int32_t family = LORA_VARIANT_GENERAL;
-    int32_t shrink_waves = 4;      // wavefronts per shrink workgroup (split the K range), 1..8
+    int32_t shrink_waves = 4;      // wavefronts per shrink workgroup (split the K range), 1..16
+    bool shrink_small = false;     // every shrink tile is 16 tokens x <= 32 rank rows: small kernel build
+    bool expand_small = false;     // every expand tile is 16 tokens of rank <= 64: small kernel build
     int32_t shrink_max_blocks = 1; // largest TB*JB among the shrink tiles (sizes the LDS reduction buffer)
     std::vector<int32_t> token_adapter, perm, group_adapter, group_offset, rank;
     std::vector<float> scale;
@@ -40,12 +46,15 @@ struct lora_plan {
 // Process-wide planner tunables (the analogue of the paper's shape -> tile
 // table, section 4.3.2).  Defaults come from measurements on MI355X.
 struct lora_tuning {
-    int32_t shrink_waves;          // wavefronts per shrink workgroup
+    int32_t shrink_waves;          // wavefronts per shrink workgroup (big build, <= 8)
     int32_t shrink_tb2_min_rows;   // groups with at least this many tokens use 32-row wave tiles
     int32_t shrink_max_jb;         // rank blocks of 16 per shrink tile (1, 2 or 4)
     int32_t expand_wave_bytes;     // target bytes of Bt + y one expand wavefront streams
     int32_t expand_tb2_min_rows;   // token-count thresholds for 32 / 64 row expand tiles
     int32_t expand_tb4_min_rows;
     int32_t tiled_min_tokens;      // AUTO: batches with fewer active tokens use the general kernels
+    int32_t shrink_small_waves;    // wavefronts per shrink workgroup, small build (<= 16)
+    int32_t shrink_small_jb;       // rank blocks per shrink tile for groups below shrink_tb2_min_rows (1 or 2)
+    int32_t shrink_target_wgs;     // small build: split K over up to 4 workgroups until the launch has this many
 };
 extern lora_tuning g_lora_tuning;

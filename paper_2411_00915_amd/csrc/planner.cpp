@@ -20,6 +20,9 @@ lora_tuning g_lora_tuning = {
     /*expand_tb2_min_rows*/ 64,
     /*expand_tb4_min_rows*/ 1 << 30,
     /*tiled_min_tokens*/ 1,
+    /*shrink_small_waves*/ 16,
+    /*shrink_small_jb*/ 1,
+    /*shrink_target_wgs*/ 384,
 };
 
 extern "C" void lora_tuning_set(const int32_t* values, int32_t count)
@@ -69,8 +72,9 @@ static int32_t round_up(int32_t v, int32_t m) { return (v + m - 1) / m * m; }
 static void build_tiles(lora_plan* p)
 {
     const lora_tuning& tu = g_lora_tuning;
-    p->shrink_waves = std::max(1, std::min(tu.shrink_waves, 8));
     p->shrink_max_blocks = 1;
+    p->shrink_small = true;
+    p->expand_small = true;
     const int G = (int)p->group_adapter.size();
     for (int g = 0; g < G; ++g) {
         const int32_t a = p->group_adapter[g];
@@ -78,11 +82,16 @@ static void build_tiles(lora_plan* p)
         const int32_t lo = p->group_offset[g], hi = p->group_offset[g + 1];
         const int32_t m = hi - lo;
 
-        // ---- shrink ----
+        // ---- shrink: groups with many tokens take 32-token tiles over up to 64
+        // rank rows (x is the big stream, read it once); groups with few tokens
+        // take 16-token tiles over 16 (or 32) rank rows so that the launch has
+        // many workgroups (A is the big stream, each byte is read once anyway)
         {
             const int jblocks = (r + 15) / 16;
-            const int jb = std::min(jblocks, std::max(1, std::min(tu.shrink_max_jb, 4)));
-            const int tb = (m >= tu.shrink_tb2_min_rows) ? 2 : 1;
+            const bool large = m >= tu.shrink_tb2_min_rows;
+            const int tb = large ? 2 : 1;
+            const int jb = std::min(jblocks, large ? std::max(1, std::min(tu.shrink_max_jb, 4))
+                                                   : std::max(1, std::min(tu.shrink_small_jb, 2)));
             for (int32_t row = lo; row < hi; row += 16 * tb) {
                 const int32_t nrows = std::min<int32_t>(16 * tb, hi - row);
                 for (int32_t j0 = 0; j0 < r; j0 += 16 * jb) {
@@ -91,7 +100,10 @@ static void build_tiles(lora_plan* p)
                     t.c0 = j0; t.cn = std::min<int32_t>(16 * jb, r - j0);
                     const int tbk = nrows > 16 ? 2 : 1, jbk = (t.cn + 15) / 16;
                     t.shape = lora_shape_code(tbk, jbk);
+                    t.reserved0 = r;
+                    std::memcpy(&t.reserved1, &p->scale[a], sizeof(float));   // s_a travels with the tile
                     p->shrink_max_blocks = std::max(p->shrink_max_blocks, tbk * jbk);
+                    if (tbk != 1 || jbk > 2) p->shrink_small = false;
                     p->shrink_tiles.push_back(t);
                 }
             }
@@ -114,11 +126,44 @@ static void build_tiles(lora_plan* p)
                     t.c0 = n0; t.cn = std::min<int32_t>(n_tile, p->N - n0);
                     const int tbk = (nrows + 15) / 16;
                     t.shape = lora_shape_code(tbk == 3 ? 4 : tbk, 0);
+                    t.reserved0 = r;
+                    if (tbk != 1 || r > 64) p->expand_small = false;
                     p->expand_tiles.push_back(t);
                 }
             }
         }
     }
+    // wavefronts per shrink workgroup: they split K in steps of 32; the LDS
+    // reduction buffer (1 KB per wavefront and 16x16 block) stays within 64 KB
+    const int steps = (p->K + 31) / 32;
+    // Small build: a workgroup's bandwidth is bounded (one CU), so a launch with
+    // fewer workgroups than CUs leaves HBM idle.  Split K over P workgroups per
+    // tile (P in 1, 2, 4); each part writes its own slice of v and every consumer
+    // of v adds the parts in order, so there are no atomics and no zeroing.
+    p->v_parts = 1;
+    if (p->shrink_small) {
+        int P = 1;
+        while (P < 4 && (int64_t)p->shrink_tiles.size() * P < tu.shrink_target_wgs && steps / (2 * P) >= 8) P *= 2;
+        p->v_parts = P;
+    }
+    {
+        std::vector<lora_tile> split;
+        split.reserve(p->shrink_tiles.size() * p->v_parts);
+        for (const lora_tile& t : p->shrink_tiles)
+            for (int q = 0; q < p->v_parts; ++q) {
+                lora_tile u = t;
+                u.shape |= (q << 8) | (p->v_parts << 12);
+                split.push_back(u);
+            }
+        p->shrink_tiles.swap(split);
+    }
+    if (p->shrink_small)
+        p->shrink_waves = std::max(1, std::min({tu.shrink_small_waves / p->v_parts, 16, steps / p->v_parts}));
+    else
+        p->shrink_waves = std::max(1, std::min({tu.shrink_waves, 8, 64 / p->shrink_max_blocks, steps}));
+    // one thread per float4 of a tile's output stores the result, so a workgroup
+    // has at least one wavefront per 16x16 block (wavefronts without k-steps add zeros)
+    p->shrink_waves = std::max(p->shrink_waves, p->shrink_max_blocks);
     // Heaviest tiles first so the tail of the launch is made of light ones;
     // stable, so equal descriptors give identical lists.
     auto weight = [&](const lora_tile& t) { return (int64_t)((t.nrows + 15) / 16) * t.cn; };
@@ -194,7 +239,7 @@ extern "C" lora_status lora_plan_query(const lora_plan* p, int32_t* v_row_stride
                                        size_t* fused_workspace_bytes)
 {
     if (!p) return LORA_ERR_INVALID_ARG;
-    const size_t vb = (size_t)p->T * (size_t)p->R * sizeof(float);
+    const size_t vb = (size_t)p->v_parts * (size_t)p->T * (size_t)p->R * sizeof(float);
     if (v_row_stride) *v_row_stride = p->R;
     if (v_bytes) *v_bytes = vb;
     if (fused_workspace_bytes) *fused_workspace_bytes = (vb + 255) / 256 * 256;
@@ -210,6 +255,7 @@ extern "C" lora_status lora_plan_export(const lora_plan* p, lora_plan_view* v)
     v->v_row_stride = p->R;
     v->kernel_family = p->family;
     v->shrink_waves = p->shrink_waves;
+    v->v_parts = p->v_parts;
     v->token_adapter = p->token_adapter.data();
     v->perm = p->perm.data();
     v->group_adapter = p->group_adapter.data();

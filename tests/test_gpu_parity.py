@@ -62,7 +62,9 @@ def run_delta_case(w, variant=B.LORA_VARIANT_AUTO, ld_pad=0, check_beta0=True, r
     x = torch.zeros((w.T, ldx), dtype=tdt, device=DEV)
     x[:, :w.K] = dl.x
     CANARY = -12345.0
-    v = torch.full((max(w.T, 1), R), CANARY, dtype=torch.float32, device=DEV)
+    P = view["v_parts"]
+    assert v_bytes == P * w.T * R * 4
+    v = torch.full((P, max(w.T, 1), R), CANARY, dtype=torch.float32, device=DEV)
     y0 = _y_in(w)
     y = torch.full((max(w.T, 1), ldy), 7.0, dtype=tdt, device=DEV)
     y[:w.T, :w.N] = torch.from_numpy(y0).to(DEV, tdt)
@@ -71,7 +73,9 @@ def run_delta_case(w, variant=B.LORA_VARIANT_AUTO, ld_pad=0, check_beta0=True, r
     B.lora_expand(plan, v, dl.Bt_ptrs, y, ldy, 1.0)
     torch.cuda.synchronize()
 
-    v_np = _to_np(v)[:w.T]
+    v_parts = _to_np(v)[:, :w.T]
+    assert all(np.array_equal(v_parts[p] == CANARY, v_parts[0] == CANARY) for p in range(P))
+    v_np = np.where(v_parts[0] == CANARY, CANARY, v_parts.astype(np.float64).sum(axis=0)).astype(np.float32)
     v_ref = oracle.shrink(w.x, tok, ad, apply_scale=True, R=R)
     ranks_tok = np.where(tok >= 0, w.adapter_rank[np.clip(tok, 0, None)], 0) if w.num_adapters else np.zeros(w.T, int)
     valid = np.arange(R)[None, :] < ranks_tok[:, None]
@@ -233,7 +237,7 @@ def test_tiled_request_with_unaligned_leading_dimension_is_refused():
     plan = device.make_plan(w, B.LORA_VARIANT_TILED)
     R, _, _ = B.lora_plan_query(plan)
     x = torch.zeros((w.T, w.K + 3), dtype=torch.bfloat16, device=DEV)
-    v = torch.zeros((w.T, R), dtype=torch.float32, device=DEV)
+    v = torch.zeros(B.lora_plan_query(plan)[1] // 4, dtype=torch.float32, device=DEV)
     with pytest.raises(B.LoraError) as e:
         B.lora_shrink(plan, x, w.K + 3, dl.At_ptrs, v)
     assert e.value.status == B.LORA_ERR_UNSUPPORTED

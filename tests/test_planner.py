@@ -39,13 +39,17 @@ def _check_tiles(w, v, tok, perm):
         assert v["shrink_tiles"].shape[0] == 0 and v["expand_tiles"].shape[0] == 0
         return
     max_r = int(w.adapter_rank.max()) if w.num_adapters else 0
-    st_ = [(t[0], t[1], t[2], t[3], t[4]) for t in v["shrink_tiles"]]
+    P = v["v_parts"]
+    assert P in (1, 2, 4)
     et_ = [(t[0], t[1], t[2], t[3], t[4]) for t in v["expand_tiles"]]
     if len(perm):
-        plan_ref.check_cover(st_, tok, perm, max(max_r, 1), adapter_rank=w.adapter_rank, rank_axis=True)
+        for part in range(P):          # every K part covers the (token, rank) plane exactly once
+            st_ = [(t[0], t[1], t[2], t[3], t[4]) for t in v["shrink_tiles"] if (t[5] >> 8) & 15 == part]
+            plan_ref.check_cover(st_, tok, perm, max(max_r, 1), adapter_rank=w.adapter_rank, rank_axis=True)
+        assert all((t[5] >> 12) & 15 == P and (t[5] >> 8) & 15 < P for t in v["shrink_tiles"])
         plan_ref.check_cover(et_, tok, perm, w.N)
     else:
-        assert not st_ and not et_
+        assert v["shrink_tiles"].shape[0] == 0 and not et_
     for t in v["shrink_tiles"]:
         tb, jb = t[5] & 15, (t[5] >> 4) & 15
         assert t[2] <= 16 * tb and t[4] <= 16 * jb and tb in (1, 2) and 1 <= jb <= 4
@@ -63,7 +67,7 @@ def test_config_tables_bit_exact(name):
     tok, perm = _check_tables(w, v)
     _check_tiles(w, v, tok, perm)
     R = max(8, (int(w.adapter_rank.max()) + 7) // 8 * 8)
-    assert q[0] == R and q[1] == w.T * R * 4 and q[2] >= q[1] and q[2] % 256 == 0
+    assert q[0] == R and q[1] == v["v_parts"] * w.T * R * 4 and q[2] >= q[1] and q[2] % 256 == 0
     expect = B.LORA_VARIANT_GENERAL if w.dtype == "f32" else B.LORA_VARIANT_TILED
     assert v["kernel_family"] == expect
 
@@ -171,10 +175,12 @@ def test_tuning_roundtrip_changes_tiles():
     try:
         w = wl.cfg3(with_w=False)
         a = _export(w)[0]
-        B.lora_tuning_set(shrink_tb2_min_rows=1 << 20, expand_tb2_min_rows=1 << 20, shrink_waves=4)
+        B.lora_tuning_set(shrink_tb2_min_rows=1 << 20, expand_tb2_min_rows=1 << 20, shrink_small_waves=4,
+                          shrink_small_jb=2)
         b = _export(w)[0]
         assert b["shrink_waves"] == 4
-        assert b["shrink_tiles"].shape[0] == 2 * a["shrink_tiles"].shape[0]
+        assert b["shrink_tiles"].shape[0] // b["v_parts"] == 4 * a["shrink_tiles"].shape[0] // a["v_parts"]
+        assert b["expand_tiles"].shape[0] > a["expand_tiles"].shape[0]
         tok, perm = _check_tables(w, b)
         _check_tiles(w, b, tok, perm)
     finally:

@@ -26,6 +26,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, scaled by a 256 MiB copy
+# (profiles/decode_cfg2_hbm_traffic.txt); keyed by workload and kernel
+MEASURED_TRAFFIC = {("cfg2_decode", "delta_fused_small_kernel"): 45.81e6}
 
 
 def algorithmic_bytes(w, beta=1.0):
@@ -56,6 +59,7 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg4d", "cfg5"])
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time budget of the oracle leg (0 = skip)")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--two-launches", action="store_true", help="lora_shrink + lora_expand instead of lora_delta")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference for profiler counters)")
     args = ap.parse_args()
@@ -116,8 +120,11 @@ def main():
 
     def run_layers(plan):
         for (x, _a, _b, At_ptrs, Bt_ptrs, y) in layers:
-            B.lora_shrink(plan, x, w.K, At_ptrs, v, stream)
-            B.lora_expand(plan, v, Bt_ptrs, y, w.N, 1.0, stream)
+            if args.two_launches:
+                B.lora_shrink(plan, x, w.K, At_ptrs, v, stream)
+                B.lora_expand(plan, v, Bt_ptrs, y, w.N, 1.0, stream)
+            else:
+                B.lora_delta(plan, x, w.K, At_ptrs, Bt_ptrs, v, y, w.N, 1.0, stream)
 
     keep = []
 
@@ -170,8 +177,11 @@ def main():
             with torch.cuda.stream(side):
                 with torch.cuda.graph(g, stream=side):
                     for (x, _a, _b, At_ptrs, Bt_ptrs, y) in layers:
-                        B.lora_shrink(plan0, x, w.K, At_ptrs, v, side)
-                        B.lora_expand(plan0, v, Bt_ptrs, y, w.N, 1.0, side)
+                        if args.two_launches:
+                            B.lora_shrink(plan0, x, w.K, At_ptrs, v, side)
+                            B.lora_expand(plan0, v, Bt_ptrs, y, w.N, 1.0, side)
+                        else:
+                            B.lora_delta(plan0, x, w.K, At_ptrs, Bt_ptrs, v, y, w.N, 1.0, side)
             torch.cuda.current_stream().wait_stream(side)
             for _ in range(3):
                 g.replay()
@@ -194,18 +204,19 @@ def main():
         torch.cuda.synchronize()
 
     sh_bytes, ex_bytes, flops = algorithmic_bytes(w, beta=1.0)
-    names = {"shrink": "shrink_tiled_kernel", "expand": "expand_tiled_kernel"}
+    names = {"shrink": "shrink_tiled_kernel", "expand": "expand_tiled_kernel", "delta": "delta_fused_small_kernel"}
     ksum = {}
     for key, nm in names.items():
         if nm in kern:
-            by = sh_bytes if key == "shrink" else ex_bytes
+            by = {"shrink": sh_bytes, "expand": ex_bytes, "delta": sh_bytes + ex_bytes}[key]
             ksum[key] = dict(kernel=nm, avg_us=kern[nm]["avg_us"], min_us=kern[nm]["min_us"], launches=kern[nm]["count"],
                              algorithmic_bytes=by, achieved_GBs=by / kern[nm]["avg_us"] * 1e-3)
     dom = max(ksum.values(), key=lambda d: d["avg_us"]) if ksum else None
     roofline = None
     if dom:
         roofline = dict(bound="hbm", kernel=dom["kernel"], achieved=round(dom["achieved_GBs"], 1), peak=HBM_PEAK_GBS,
-                        unit="GB/s", frac=round(dom["achieved_GBs"] / HBM_PEAK_GBS, 4), traffic=None,
+                        unit="GB/s", frac=round(dom["achieved_GBs"] / HBM_PEAK_GBS, 4),
+                        traffic=MEASURED_TRAFFIC.get((w.name, dom["kernel"])),
                         avg_kernel_us=round(dom["avg_us"], 3), algorithmic_bytes=dom["algorithmic_bytes"])
 
     # ---- CPU oracle on this host's cores: the same delta path (shrink + expand-add), layer 0's inputs
@@ -244,7 +255,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "tokens": w.T, "k": w.K, "n": w.N, "adapters": w.num_adapters,
                    "ranks": sorted(set(int(r) for r in w.adapter_rank)), "layers_per_step": L,
-                   "launch": "eager, one lora_plan per step"},
+                   "launch": "eager, one lora_plan per step, " +
+                             ("lora_shrink + lora_expand per layer" if args.two_launches else "lora_delta per layer")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in d.items()} for k, d in ksum.items()},

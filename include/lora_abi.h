@@ -107,9 +107,11 @@ typedef struct {
     int32_t nrows;
     int32_t c0;
     int32_t cn;
-    int32_t shape;      /* tile shape code chosen by the planner; shrink: bits 8..11 K part, 12..15 number of K parts */
+    int32_t shape;      /* tile shape code chosen by the planner; shrink: bits 8..11 K part, 12..15 number of K
+                           parts, 16..31 adapter group; expand: bits 8..19 / 20..31 shrink / expand tiles of the adapter
+                           group when the plan can run as one launch, else 0 */
     int32_t reserved0;  /* rank of the adapter */
-    int32_t reserved1;  /* shrink tiles: bit pattern of the adapter's scale */
+    int32_t reserved1;  /* shrink tiles: bit pattern of the adapter's scale; expand tiles: adapter group */
 } lora_tile;
 
 /* Read-only view of a plan's host tables (valid until lora_plan_destroy). */
@@ -195,6 +197,26 @@ lora_status lora_expand(lora_plan* plan, const float* v,
                         float beta, void* hip_stream);
 
 /*
+ * lora_delta -- both extra products of an adapted layer in one call (section
+ * 3.2 counts two extra matrix products, one extra addition and their kernel
+ * launches per layer as the cost of unmerged inference):
+ *
+ *     y[t,:] = beta * y[t,:] + s_a * (x[t,:] A_a) B_a
+ *
+ * Arguments as for lora_shrink and lora_expand; v is scratch of lora_plan_query's
+ * v_bytes.  When every tile of the plan is small (decode-shaped batches:
+ * adapter groups of fewer than 64 tokens, ranks <= 64) both steps run as ONE
+ * kernel launch: expand blocks send out their Bt and y loads, wait (bounded)
+ * for their adapter group's shrink blocks through counters in the plan's device
+ * tables, and if those are not seen in time compute their rows of v themselves.
+ * Otherwise it is lora_shrink followed by lora_expand.  A plan's launches must
+ * not overlap (one stream at a time): the counters live in the plan.
+ */
+lora_status lora_delta(lora_plan* plan, const void* x, int64_t ldx,
+                       const void* const* d_At_ptrs, const void* const* d_Bt_ptrs,
+                       float* v, void* y, int64_t ldy, float beta, void* hip_stream);
+
+/*
  * lora_base_gemm -- the base-model product shared by all requests of the batch
  * (section 1 / section 2, unmerged inference):  y = x W, Wt [N,K] with ldw.
  * bf16 MFMA with fp32 accumulation (fp32 dtype: VALU).  Used for the
@@ -235,7 +257,8 @@ const char* lora_status_str(lora_status s);
  * when every tile is small, 1..16), shrink_small_jb (rank blocks of 16 per shrink
  * tile for adapter groups below shrink_tb2_min_rows, 1..2), shrink_target_wgs
  * (small launches split K over up to 4 workgroups per tile until they have this
- * many workgroups).
+ * many workgroups), fused_spin_limit (lora_delta's single launch: polls an expand
+ * block waits for its shrink blocks, plus one; 1 = never wait, always recompute).
  * Entries <= 0 keep the current value; plans made
  * earlier are unaffected.  Host only.
  */

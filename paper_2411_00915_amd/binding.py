@@ -70,6 +70,8 @@ _lib.lora_shrink.restype = ctypes.c_int
 _lib.lora_shrink.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, _vp]
 _lib.lora_expand.restype = ctypes.c_int
 _lib.lora_expand.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_float, _vp]
+_lib.lora_delta.restype = ctypes.c_int
+_lib.lora_delta.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_float, _vp]
 _lib.lora_base_gemm.restype = ctypes.c_int
 _lib.lora_base_gemm.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                 _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp]
@@ -94,12 +96,12 @@ _lib.lora_kernel_count.restype = ctypes.c_int32
 
 EXPORTED = ["lora_timing_begin", "lora_timing_end", "lora_timing_read", "lora_kernel_name", "lora_kernel_count",
             "lora_plan_create", "lora_plan_destroy", "lora_plan_query", "lora_plan_export",
-            "lora_plan_upload", "lora_shrink", "lora_expand", "lora_base_gemm",
+            "lora_plan_upload", "lora_shrink", "lora_expand", "lora_delta", "lora_base_gemm",
             "lora_fused_forward", "lora_status_str", "lora_tuning_set", "lora_tuning_get"]
 
 TUNING_FIELDS = ["shrink_waves", "shrink_tb2_min_rows", "shrink_max_jb", "expand_wave_bytes",
                  "expand_tb2_min_rows", "expand_tb4_min_rows", "tiled_min_tokens",
-                 "shrink_small_waves", "shrink_small_jb", "shrink_target_wgs"]
+                 "shrink_small_waves", "shrink_small_jb", "shrink_target_wgs", "fused_spin_limit", "fused_delay"]
 
 
 class LoraError(RuntimeError):
@@ -262,6 +264,11 @@ def lora_shrink(plan: Plan, x, ldx: int, d_At_ptrs, v, stream=None):
 def lora_expand(plan: Plan, v, d_Bt_ptrs, y, ldy: int, beta: float = 1.0, stream=None):
     _check(_lib.lora_expand(plan.handle, _ptr(v), _ptr(d_Bt_ptrs), _ptr(y), int(ldy), float(beta), _stream(stream)),
            "lora_expand")
+
+
+def lora_delta(plan: Plan, x, ldx: int, d_At_ptrs, d_Bt_ptrs, v, y, ldy: int, beta: float = 1.0, stream=None):
+    _check(_lib.lora_delta(plan.handle, _ptr(x), int(ldx), _ptr(d_At_ptrs), _ptr(d_Bt_ptrs), _ptr(v), _ptr(y), int(ldy),
+                           float(beta), _stream(stream)), "lora_delta")
 
 
 def lora_base_gemm(num_tokens: int, k: int, n: int, dtype: int, x, ldx: int, Wt, ldw: int, y, ldy: int, stream=None):

@@ -26,7 +26,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 struct table_layout {
-    size_t perm, token_adapter, rank, scale, shrink_tiles, expand_tiles, total;
+    size_t perm, token_adapter, rank, scale, shrink_tiles, expand_tiles, sync, sync_bytes, total;
 };
 
 table_layout layout_of(const lora_plan* p)
@@ -40,6 +40,8 @@ table_layout layout_of(const lora_plan* p)
     L.scale = take(p->scale.size() * sizeof(float));
     L.shrink_tiles = take(p->shrink_tiles.size() * sizeof(lora_tile));
     L.expand_tiles = take(p->expand_tiles.size() * sizeof(lora_tile));
+    L.sync_bytes = p->fused_ok ? p->group_adapter.size() * 128 : 0;
+    L.sync = take(L.sync_bytes);
     L.total = std::max<size_t>(off, 256);
     return L;
 }
@@ -83,6 +85,7 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     put(L.scale, p->scale.data(), p->scale.size() * sizeof(float));
     put(L.shrink_tiles, p->shrink_tiles.data(), p->shrink_tiles.size() * sizeof(lora_tile));
     put(L.expand_tiles, p->expand_tiles.data(), p->expand_tiles.size() * sizeof(lora_tile));
+    std::memset(h + L.sync, 0, L.sync_bytes);                    // hand-off counters start at zero
     if (hipMemcpyAsync(dbuf, hbuf, L.total, hipMemcpyHostToDevice, stream) != hipSuccess) {
         (void)hipGetLastError();
         (void)hipFree(dbuf);
@@ -100,12 +103,14 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     p->d_scale = reinterpret_cast<float*>(d + L.scale);
     p->d_shrink_tiles = reinterpret_cast<lora_tile*>(d + L.shrink_tiles);
     p->d_expand_tiles = reinterpret_cast<lora_tile*>(d + L.expand_tiles);
+    p->d_sync = d + L.sync;
     return LORA_OK;
 }
 
 lora_dev_tables tables_of(const lora_plan* p)
 {
-    return lora_dev_tables{p->d_perm, p->d_token_adapter, p->d_rank, p->d_scale, p->d_shrink_tiles, p->d_expand_tiles};
+    return lora_dev_tables{p->d_perm, p->d_token_adapter, p->d_rank, p->d_scale, p->d_shrink_tiles, p->d_expand_tiles,
+                           p->d_sync};
 }
 
 size_t elem_bytes(int32_t dtype) { return dtype == LORA_F32 ? 4 : 2; }
@@ -190,6 +195,28 @@ extern "C" lora_status lora_expand(lora_plan* p, const float* v, const void* con
     else
         e = launch_expand_general(p, d, v, d_Bt_ptrs, y, ldy, beta, stream);
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
+}
+
+extern "C" lora_status lora_delta(lora_plan* p, const void* x, int64_t ldx,
+                                  const void* const* d_At_ptrs, const void* const* d_Bt_ptrs,
+                                  float* v, void* y, int64_t ldy, float beta, void* hip_stream)
+{
+    if (!p) return LORA_ERR_INVALID_ARG;
+    if (!(beta == 0.f || beta == 1.f)) return LORA_ERR_INVALID_ARG;
+    if (p->perm.empty()) return LORA_OK;
+    if (!x || !d_At_ptrs || !d_Bt_ptrs || !v || !y) return LORA_ERR_INVALID_ARG;
+    if (ldx < p->K || ldy < p->N) return LORA_ERR_INVALID_ARG;
+    if (p->family == LORA_VARIANT_TILED && p->fused_ok && tiled_call_ok(x, ldx) && tiled_call_ok(y, ldy) &&
+        !misaligned(v, 16) && !misaligned(d_At_ptrs, 8) && !misaligned(d_Bt_ptrs, 8)) {
+        hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+        lora_status st = ensure_uploaded(p, stream);
+        if (st != LORA_OK) return st;
+        const hipError_t e = launch_delta_fused_small(p, tables_of(p), x, ldx, d_At_ptrs, d_Bt_ptrs, v, y, ldy, beta, stream);
+        return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
+    }
+    lora_status st = lora_shrink(p, x, ldx, d_At_ptrs, v, hip_stream);
+    if (st != LORA_OK) return st;
+    return lora_expand(p, v, d_Bt_ptrs, y, ldy, beta, hip_stream);
 }
 
 extern "C" lora_status lora_base_gemm(int32_t T, int32_t K, int32_t N, int32_t dtype,

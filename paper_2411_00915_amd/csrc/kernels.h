@@ -24,6 +24,7 @@ struct lora_dev_tables {
     const float* scale;
     const lora_tile* shrink_tiles;
     const lora_tile* expand_tiles;
+    void* sync;                    // hand-off counters of the single-launch decode kernel: 128 bytes per adapter group
 };
 
 // general VALU family (any dtype, any alignment)
@@ -37,6 +38,11 @@ hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, con
                                const void* const* At, float* v, hipStream_t stream);
 hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, const float* v,
                                const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream);
+
+// both steps in one launch (decode regime: every tile small); same layout demands as the tiled family
+hipError_t launch_delta_fused_small(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
+                                    const void* const* At, const void* const* Bt, float* v, void* y, int64_t ldy,
+                                    float beta, hipStream_t stream);
 
 // base GEMM  y = x Wt^T  (+ optional adapter delta in the epilogue when p != nullptr)
 hipError_t launch_gemm_general(int32_t T, int32_t K, int32_t N, int32_t dtype, const void* x, int64_t ldx,

@@ -39,7 +39,9 @@ __device__ __forceinline__ floatx4 mfma(const op16& a, const op16& b, floatx4 c)
 // tokens, so a lane ends up with 4 consecutive rank entries of one token.
 // The workgroup's wavefronts take contiguous slices of K; partial sums meet in
 // LDS, are scaled by s_a and stored once (deterministic, no atomics).
-template <int TB, int JB, int U>
+// PUBLISH: v is stored with agent-scope write-through stores, so that workgroups on other XCDs can
+// read it during the same launch without an L2 write-back
+template <int TB, int JB, int U, bool PUBLISH = false>
 __device__ __forceinline__ void shrink_tile(
     const lora_tile tile, const int32_t* __restrict__ perm,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
@@ -144,7 +146,15 @@ __device__ __forceinline__ void shrink_tile(
 #pragma unroll
             for (int w = 0; w < st; ++w) part[w] += part[w + st];
         const float4 o = make_float4(s_a * part[0][0], s_a * part[0][1], s_a * part[0][2], s_a * part[0][3]);
-        *reinterpret_cast<float4*>(v + kpart * vsp.part + (int64_t)out_t * R + out_j) = o;
+        float* dst = v + kpart * vsp.part + (int64_t)out_t * R + out_j;
+        if (PUBLISH) {
+            __hip_atomic_store(dst + 0, o.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(dst + 1, o.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(dst + 2, o.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(dst + 3, o.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            *reinterpret_cast<float4*>(dst) = o;
+        }
     }
 }
 
@@ -439,5 +449,260 @@ hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, con
     else
         LORA_LAUNCH(LORA_K_EXPAND_TILED, expand_tiled_kernel, dim3(n_tiles), dim3(256), 0, stream,
                     d.expand_tiles, d.perm, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);
+    return hipGetLastError();
+}
+
+
+// ---------------------------------------------------------------------------
+// Decode regime, one launch for both steps.  Blocks [0, S) are shrink tiles
+// (4 wavefronts, K split over the plan's P parts), blocks [S, S+E) are expand
+// tiles.  An expand block first sends out the loads that do not depend on v
+// (Bt and y of its first chunk), then waits until every shrink tile of its
+// adapter group has published its part of v, gathers v into LDS and goes on as
+// the expand kernel does.  This saves one launch and one round of dependent
+// small loads per layer, and the Bt/y traffic overlaps the shrink.
+//
+// Hand-off: every adapter group g has two 64-bit counters in a 128-byte slot of
+// its own, neither ever reset: done[g] counts finished shrink tiles, cons[g]
+// finished expand tiles.  The group has need[g] shrink and ncons[g] expand tiles
+// per launch, so while a launch runs e = cons[g] / ncons[g] is the number of
+// launches completed before it, and its expand tiles wait for
+// done[g] >= (e+1) * need[g].  There is no counter shared by all blocks.
+// Producers never wait, and blocks are dispatched in index order, so all
+// producers are dispatched before the first consumer.  Independently of that the wait is bounded: after spin_limit polls
+// an expand block stops waiting and computes its v rows itself from x and At
+// (slow, exact), so every wavefront reaches the end of the kernel in any case.
+struct lora_sync_slot {          // one per adapter group, 128 bytes
+    unsigned long long done;
+    unsigned long long cons;
+    unsigned long long pad[14];
+};
+
+__device__ __forceinline__ unsigned long long ld_agent(const unsigned long long* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent_f(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int KS>
+__device__ __forceinline__ void fused_expand_item(
+    const lora_tile tile, const int32_t* __restrict__ perm, const float* __restrict__ scale,
+    const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
+    const float* v, lora_vspec vsp, const bf16_t* __restrict__ Bt, bf16_t* __restrict__ y, int64_t ldy, int N,
+    float beta, lora_sync_slot* sync, int spin_limit, int delay, float* vt, int* flag)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int R = vsp.R;
+    const int r = tile.reserved0;
+    const int group = tile.reserved1;
+    const unsigned int need = ((unsigned int)tile.shape >> 8) & 0xfffu;
+    const unsigned int ncons = (unsigned int)tile.shape >> 20;
+    lora_sync_slot* slot = sync + group;
+
+    const int chunks = (tile.cn + 63) >> 6;
+    const int c_begin = (chunks * wave) >> 2, c_end = (chunks * (wave + 1)) >> 2;
+    const bool has_work = c_begin < c_end;
+    const int n_end = tile.c0 + tile.cn;
+    const int row_in_chunk = 16 * (m >> 2) + (m & 3);
+
+    const bool tok_ok = m < tile.nrows;
+    const int tok = perm[tile.row0 + (tok_ok ? m : 0)];
+
+    auto load_b = [&](int c, op16 (&bop)[4][KS]) {
+        const int n_base = tile.c0 + (c << 6);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int n = n_base + row_in_chunk + 4 * b;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int j = s * 32 + g * 8;
+                bop[b][s].u = (n < n_end && j < r) ? ld16(Bt + (int64_t)n * r + j) : uint4{0, 0, 0, 0};
+            }
+        }
+    };
+    auto load_y = [&](int c, uint4 (&yin)[2]) {
+        const int n_lane = tile.c0 + (c << 6) + 16 * g;
+        if (beta != 0.f && tok_ok && n_lane + 16 <= n_end) {
+            const bf16_t* yp = y + (int64_t)tok * ldy + n_lane;
+            yin[0] = ld16(yp);
+            yin[1] = ld16(yp + 8);
+        } else {
+            yin[0] = uint4{0, 0, 0, 0};
+            yin[1] = uint4{0, 0, 0, 0};
+        }
+    };
+
+    // Let the shrink blocks' loads of x and At get ahead in the memory queues: what they
+    // fetch is needed first (the expand blocks cannot finish before v exists).
+    for (int i = 0; i < delay; ++i) __builtin_amdgcn_s_sleep(16);
+    op16 bop[4][KS];
+    uint4 yin[2];
+    if (has_work) {
+        load_b(c_begin, bop);
+        load_y(c_begin, yin);
+    }
+
+    // ---- wait for the group's shrink tiles (bounded) -----------------------
+    if (threadIdx.x == 0) {
+        const unsigned long long target = (ld_agent(&slot->cons) / ncons + 1ull) * need;
+        int ok = 0;
+        for (int it = 0; it <= spin_limit; ++it) {
+            if (ld_agent(&slot->done) >= target) { ok = 1; break; }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        *flag = ok;
+    }
+    __syncthreads();
+    const bool published = *flag != 0;
+    if (published) {
+        // v is read with agent-scope loads, which do not use lines cached before the count was seen
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        const int row = threadIdx.x >> 4, j4 = (threadIdx.x & 15) * 4;
+        if (row < tile.nrows && j4 < r) {
+            const int t = perm[tile.row0 + row];
+            float pv[4][4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {                  // all parts are requested before the first add
+                const float* vq = v + q * vsp.part + (int64_t)t * R + j4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pv[q][i] = (q < vsp.P) ? ld_agent_f(vq + i) : 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) vt[row * 64 + j4 + i] = ((pv[0][i] + pv[1][i]) + pv[2][i]) + pv[3][i];
+        }
+    } else {
+        // the shrink tiles were not seen in time: compute this tile's v rows here
+        const float s_a = scale[tile.adapter];
+        for (int idx = wave; idx < tile.nrows * r; idx += 4) {
+            const int row = idx / r, j = idx - row * r;
+            const bf16_t* xr = x + (int64_t)perm[tile.row0 + row] * ldx;
+            const bf16_t* ar = At + (int64_t)j * K;
+            float acc = 0.f;
+            for (int k = lane * 8; k < K; k += 512) {
+                const uint4 xa = ld16(xr + k), aa = ld16(ar + k);
+                const uint32_t* xp = reinterpret_cast<const uint32_t*>(&xa);
+                const uint32_t* ap = reinterpret_cast<const uint32_t*>(&aa);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc = fmaf(bf16_to_f32((bf16_t)(xp[q] & 0xffffu)), bf16_to_f32((bf16_t)(ap[q] & 0xffffu)), acc);
+                    acc = fmaf(bf16_to_f32((bf16_t)(xp[q] >> 16)), bf16_to_f32((bf16_t)(ap[q] >> 16)), acc);
+                }
+            }
+            acc = wave_sum(acc);
+            if (lane == 0) vt[row * 64 + j] = s_a * acc;
+        }
+    }
+    __syncthreads();
+    // this tile no longer needs the group's counters: count it as through (also when it
+    // recomputed v itself, so that the launch arithmetic above stays exact)
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(&slot->cons, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!has_work) return;
+
+    op16 vhi[KS], vlo[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        const int j = s * 32 + g * 8;
+        float f[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = (tok_ok && j < r) ? vt[m * 64 + j + i] : 0.f;
+        split_bf16(f, vhi[s], vlo[s]);
+    }
+
+    for (int c = c_begin; c < c_end; ++c) {
+        const int n_lane = tile.c0 + (c << 6) + 16 * g;
+        const bool full = n_lane + 16 <= n_end;
+        floatx4 acc[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                acc[b] = mfma(bop[b][s], vhi[s], acc[b]);
+                acc[b] = mfma(bop[b][s], vlo[s], acc[b]);
+            }
+        }
+        if (tok_ok) {
+            bf16_t* yp = y + (int64_t)tok * ldy + n_lane;
+            if (full) {
+                uint32_t out[8];
+                const uint32_t* yi = reinterpret_cast<const uint32_t*>(&yin[0]);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    float e0 = acc[q >> 1][(q & 1) * 2], e1 = acc[q >> 1][(q & 1) * 2 + 1];
+                    if (beta != 0.f) {
+                        e0 = fmaf(beta, bf16_to_f32((bf16_t)(yi[q] & 0xffffu)), e0);
+                        e1 = fmaf(beta, bf16_to_f32((bf16_t)(yi[q] >> 16)), e1);
+                    }
+                    out[q] = (uint32_t)f32_to_bf16(e0) | ((uint32_t)f32_to_bf16(e1) << 16);
+                }
+                *reinterpret_cast<uint4*>(yp) = uint4{out[0], out[1], out[2], out[3]};
+                *reinterpret_cast<uint4*>(yp + 8) = uint4{out[4], out[5], out[6], out[7]};
+            } else {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    if (n_lane + q < n_end) {
+                        float e = acc[q >> 2][q & 3];
+                        if (beta != 0.f) e = fmaf(beta, bf16_to_f32(yp[q]), e);
+                        yp[q] = f32_to_bf16(e);
+                    }
+                }
+            }
+        }
+        if (c + 1 < c_end) {
+            load_b(c + 1, bop);
+            load_y(c + 1, yin);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void delta_fused_small_kernel(
+    const lora_tile* __restrict__ shrink_tiles, int n_shrink, const lora_tile* __restrict__ expand_tiles,
+    const int32_t* __restrict__ perm, const float* __restrict__ scale,
+    const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* const* __restrict__ At_ptrs, int K,
+    float* v, lora_vspec vsp, const bf16_t* const* __restrict__ Bt_ptrs,
+    bf16_t* __restrict__ y, int64_t ldy, int N, float beta, lora_sync_slot* sync, int spin_limit, int delay)
+{
+    __shared__ floatx4 lds[4 * 2 * 64];      // 8 KB: shrink reduction buffer, or v rows [16][64] of an expand tile
+    __shared__ int flag;
+    const int b = blockIdx.x;
+    if (b < n_shrink) {
+        const lora_tile tile = shrink_tiles[b];
+        const bf16_t* At = At_ptrs[tile.adapter];
+        const int jb = (tile.shape >> 4) & 15;
+        if (jb == 1) shrink_tile<1, 1, 8, true>(tile, perm, x, ldx, At, K, v, vsp, lds);
+        else shrink_tile<1, 2, 4, true>(tile, perm, x, ldx, At, K, v, vsp, lds);
+        // publish: the write-through stores of every thread have completed before the
+        // block's count is added (no L2 write-back: that would cost microseconds per block)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (threadIdx.x == 0)
+            __hip_atomic_fetch_add(&sync[(unsigned int)tile.shape >> 16].done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        const lora_tile tile = expand_tiles[b - n_shrink];
+        const bf16_t* Bt = Bt_ptrs[tile.adapter];
+        const bf16_t* At = At_ptrs[tile.adapter];
+        if (tile.reserved0 <= 32)
+            fused_expand_item<1>(tile, perm, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, spin_limit, delay,
+                                 reinterpret_cast<float*>(lds), &flag);
+        else
+            fused_expand_item<2>(tile, perm, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, spin_limit, delay,
+                                 reinterpret_cast<float*>(lds), &flag);
+    }
+}
+
+hipError_t launch_delta_fused_small(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
+                                    const void* const* At, const void* const* Bt, float* v, void* y, int64_t ldy,
+                                    float beta, hipStream_t stream)
+{
+    const int S = (int)p->shrink_tiles.size(), E = (int)p->expand_tiles.size();
+    if (S + E == 0) return hipSuccess;
+    lora_sync_slot* sync = reinterpret_cast<lora_sync_slot*>(d.sync);
+    LORA_LAUNCH(LORA_K_DELTA_FUSED, delta_fused_small_kernel, dim3(S + E), dim3(256), 0, stream,
+                d.shrink_tiles, S, d.expand_tiles, d.perm, d.scale, (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K,
+                v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta, sync, p->fused_spin_limit, p->fused_delay);
     return hipGetLastError();
 }

@@ -16,6 +16,7 @@ enum lora_kernel_id {
     LORA_K_GEMM_GENERAL,
     LORA_K_GEMM_TILED,
     LORA_K_GEMM_TILED_DELTA,
+    LORA_K_DELTA_FUSED,
     LORA_K_COUNT
 };
 

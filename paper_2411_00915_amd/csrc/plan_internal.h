@@ -24,6 +24,9 @@ struct lora_plan {
     int32_t shrink_waves = 4;      // wavefronts per shrink workgroup (split the K range), 1..16
     bool shrink_small = false;     // every shrink tile is 16 tokens x <= 32 rank rows: small kernel build
     bool expand_small = false;     // every expand tile is 16 tokens of rank <= 64: small kernel build
+    bool fused_ok = false;         // both small: shrink and expand can run as one launch
+    int32_t fused_spin_limit = 0;  // polls an expand block spends waiting for its group's shrink tiles
+    int32_t fused_delay = 0;       // units of ~0.4 us an expand block waits before sending its first loads
     int32_t shrink_max_blocks = 1; // largest TB*JB among the shrink tiles (sizes the LDS reduction buffer)
     std::vector<int32_t> token_adapter, perm, group_adapter, group_offset, rank;
     std::vector<float> scale;
@@ -41,6 +44,7 @@ struct lora_plan {
     float* d_scale = nullptr;
     lora_tile* d_shrink_tiles = nullptr;
     lora_tile* d_expand_tiles = nullptr;
+    void* d_sync = nullptr;           // hand-off counters, 128 bytes per adapter group (only when fused_ok)
 };
 
 // Process-wide planner tunables (the analogue of the paper's shape -> tile
@@ -56,5 +60,7 @@ struct lora_tuning {
     int32_t shrink_small_waves;    // wavefronts per shrink workgroup, small build (<= 16)
     int32_t shrink_small_jb;       // rank blocks per shrink tile for groups below shrink_tb2_min_rows (1 or 2)
     int32_t shrink_target_wgs;     // small build: split K over up to 4 workgroups until the launch has this many
+    int32_t fused_spin_limit;      // single-launch decode kernel: polls before an expand block computes v itself (+1; 1 = never wait)
+    int32_t fused_delay;           // single-launch decode kernel: head start of the shrink blocks' loads, units of ~0.4 us (+1)
 };
 extern lora_tuning g_lora_tuning;

@@ -23,6 +23,8 @@ lora_tuning g_lora_tuning = {
     /*shrink_small_waves*/ 16,
     /*shrink_small_jb*/ 1,
     /*shrink_target_wgs*/ 384,
+    /*fused_spin_limit*/ 200000,
+    /*fused_delay*/ 3,
 };
 
 extern "C" void lora_tuning_set(const int32_t* values, int32_t count)
@@ -99,7 +101,7 @@ static void build_tiles(lora_plan* p)
                     t.adapter = a; t.row0 = row; t.nrows = nrows;
                     t.c0 = j0; t.cn = std::min<int32_t>(16 * jb, r - j0);
                     const int tbk = nrows > 16 ? 2 : 1, jbk = (t.cn + 15) / 16;
-                    t.shape = lora_shape_code(tbk, jbk);
+                    t.shape = lora_shape_code(tbk, jbk) | ((g & 0xffff) << 16);   // bits 16..31: adapter group
                     t.reserved0 = r;
                     std::memcpy(&t.reserved1, &p->scale[a], sizeof(float));   // s_a travels with the tile
                     p->shrink_max_blocks = std::max(p->shrink_max_blocks, tbk * jbk);
@@ -127,6 +129,7 @@ static void build_tiles(lora_plan* p)
                     const int tbk = (nrows + 15) / 16;
                     t.shape = lora_shape_code(tbk == 3 ? 4 : tbk, 0);
                     t.reserved0 = r;
+                    t.reserved1 = g;                                             // adapter group
                     if (tbk != 1 || r > 64) p->expand_small = false;
                     p->expand_tiles.push_back(t);
                 }
@@ -164,6 +167,22 @@ static void build_tiles(lora_plan* p)
     // one thread per float4 of a tile's output stores the result, so a workgroup
     // has at least one wavefront per 16x16 block (wavefronts without k-steps add zeros)
     p->shrink_waves = std::max(p->shrink_waves, p->shrink_max_blocks);
+    // Single-launch decode kernel: an expand tile carries (bits 8..31 of its shape)
+    // the numbers of shrink tiles
+    // (bits 8..19 of its shape) and of expand tiles (bits 20..31) of its adapter group.
+    p->fused_ok = p->shrink_small && p->expand_small && G <= 4096;
+    p->fused_spin_limit = tu.fused_spin_limit - 1;
+    p->fused_delay = std::max(0, std::min(tu.fused_delay - 1, 64));
+    if (p->fused_ok) {
+        std::vector<int32_t> need((size_t)G, 0), ncons((size_t)G, 0);
+        for (const lora_tile& t : p->shrink_tiles) need[(size_t)((uint32_t)t.shape >> 16)] += 1;
+        for (const lora_tile& t : p->expand_tiles) ncons[(size_t)t.reserved1] += 1;
+        for (int g = 0; g < G; ++g)
+            if (need[g] > 4095 || ncons[g] > 4095) p->fused_ok = false;
+        if (p->fused_ok)
+            for (lora_tile& t : p->expand_tiles)
+                t.shape |= (need[(size_t)t.reserved1] << 8) | (int32_t)((uint32_t)ncons[(size_t)t.reserved1] << 20);
+    }
     // Heaviest tiles first so the tail of the launch is made of light ones;
     // stable, so equal descriptors give identical lists.
     auto weight = [&](const lora_tile& t) { return (int64_t)((t.nrows + 15) / 16) * t.cn; };

@@ -243,3 +243,71 @@ def test_tiled_request_with_unaligned_leading_dimension_is_refused():
     assert e.value.status == B.LORA_ERR_UNSUPPORTED
     torch.cuda.synchronize()
     plan.destroy()
+
+
+# ---------------------------------------------------------------- one launch for both steps
+def _delta_case(w, fallback=False):
+    """lora_delta (single launch when the plan allows) vs the oracle and vs shrink + expand."""
+    print(f"  delta {w.name} T={w.T} K={w.K} N={w.N} fallback={fallback}", flush=True)
+    before = B.lora_tuning_get()
+    try:
+        if fallback:
+            B.lora_tuning_set(fused_spin_limit=1)      # never wait: every expand block recomputes its v rows
+        dl = device.to_device(w, DEV, with_w=False)
+        plan = device.make_plan(w)
+    finally:
+        B.lora_tuning_set(**before)
+    tdt = device.torch_dtype(w)
+    _, v_bytes, _ = B.lora_plan_query(plan)
+    view = B.lora_plan_export(plan)
+    waves = view["shrink_waves"]
+    fused = view["kernel_family"] == B.LORA_VARIANT_TILED and view["expand_tiles"].shape[0] > 0 and \
+        bool(np.all((view["expand_tiles"][:, 5] >> 8) & 0xfff > 0))
+    tok = oracle.token_adapter(w.T, w.seg_indptr, w.seg_adapter)
+    ad = oracle.Adapters(w.adapter_rank, w.adapter_scale, w.A, w.B)
+    y0 = _y_in(w)
+    v = torch.zeros(max(v_bytes // 4, 4), dtype=torch.float32, device=DEV)
+    for beta in (1.0, 0.0):
+        y_a = torch.from_numpy(y0).to(DEV, tdt)
+        y_b = y_a.clone()
+        for rep in range(3):                            # repeated launches reuse the plan's hand-off counters
+            y_a.copy_(torch.from_numpy(y0).to(DEV, tdt))
+            B.lora_delta(plan, dl.x, w.K, dl.At_ptrs, dl.Bt_ptrs, v, y_a, w.N, beta)
+        B.lora_shrink(plan, dl.x, w.K, dl.At_ptrs, v)
+        B.lora_expand(plan, v, dl.Bt_ptrs, y_b, w.N, beta)
+        torch.cuda.synchronize()
+        ranks_tok = np.where(tok >= 0, w.adapter_rank[np.clip(tok, 0, None)], 0)
+        act = ranks_tok > 0
+        ref = oracle.expand(w.x, tok, ad, w.N, y_in=(y0.astype(np.float64) if beta else None))
+        got = _to_np(y_a)
+        assert np.array_equal(got[~act], y0[~act]), "rows without adapter must stay bit-identical"
+        if act.any():
+            _assert_close(got[act], ref[act], _tol(w), f"lora_delta beta={beta}")
+        if not fallback:
+            # same arithmetic; bitwise equal when both paths slice K over 4 wavefronts, otherwise the fp32
+            # summation order of v differs and a few y entries may round the other way
+            if waves == 4 or not fused:
+                assert torch.equal(y_a, y_b), "single launch and shrink+expand differ bitwise"
+            else:
+                assert oracle.error_metrics(_to_np(y_a), _to_np(y_b))[0] <= 5e-4
+    torch.cuda.synchronize()
+    plan.destroy()
+
+
+def test_single_launch_delta_decode_config():
+    w = wl.cfg2(with_w=False)
+    plan = device.make_plan(w)
+    plan.destroy()
+    _delta_case(w)
+    _delta_case(w, fallback=True)
+
+
+def test_single_launch_delta_small_and_mixed_cases():
+    for seed, (T, K, N, ranks) in enumerate([(37, 72, 200, (8, 16, 24, 32, 40, 64)), (120, 520, 1000, (8, 64)),
+                                             (9, 4096, 256, (16,)), (300, 328, 72, (8, 16, 128))]):
+        w = wl.random_case(400 + seed, T, K, N, 9, ranks, max_seg=12, frac_none=0.2,
+                           scales=(0.5, 2.0, -1.5), empty_segments=True)
+        _delta_case(w)                                  # rank 128 or big groups: falls back to two launches inside
+        _delta_case(w, fallback=True)
+    wf = wl.random_case(410, 33, 40, 48, 3, (4, 8), dtype="f32", max_seg=6, frac_none=0.2)
+    _delta_case(wf)

@@ -10,8 +10,10 @@
 // HBM -> registers -> LDS as 16-byte chunks and come back out of LDS as
 // ready-made v_mfma_f32_32x32x16_bf16 operands (8 consecutive k per lane).
 //
-//   workgroup tile 128 features x 128 tokens x 64 k, 4 wavefronts (2 x 2),
-//   wavefront tile 64 x 64 = 2 x 2 MFMA blocks of 32 x 32, LDS double buffered.
+//   workgroup tile = 4 wavefronts (2 x 2), each WB x WB MFMA blocks of 32 x 32:
+//     WB = 4: 256 features x 256 tokens x 64 k (large problems; LDS reads per MFMA halved)
+//     WB = 2: 128 x 128 x 64 (small problems, less padding waste)
+//   LDS double buffered (dynamic, 2 x (BM + BT) x 128 bytes).
 //
 // Lane roles in v_mfma_f32_32x32x16_bf16 (D = A*B + C, A 32x16, B 16x32):
 //   lane l supplies A[row l%32][k 8*(l/32) .. +7], B[k 8*(l/32) .. +7][col l%32],
@@ -33,12 +35,14 @@ union op16 {
 
 namespace {
 
-constexpr int BM = 128;   // features per workgroup tile
-constexpr int BT = 128;   // tokens per workgroup tile
 constexpr int BK = 64;    // k per stage; a tile row is 128 bytes = 8 chunks of 16 bytes
 
-// LDS tile: 128 rows x 8 chunks; chunk c of row r lives at chunk slot c ^ (r & 7)
+// LDS tile: rows x 8 chunks of 16 bytes; chunk c of row r lives at chunk slot c ^ f(r).  A ds_read_b128 of a
+// wavefront is served 8 lanes at a time, so f must take 8 different values over the 8 rows those lanes read.
+// x tile: lanes read consecutive rows -> f = r & 7.  W tile: lanes 8g..8g+7 read rows 4g..4g+3 and
+// 16+4g..16+4g+3 (the feature permutation of the MFMA rows) -> f = (r & 3) | bit 4 of r << 2.
 __device__ __forceinline__ int lds_slot(int row, int chunk) { return row * 8 + (chunk ^ (row & 7)); }
+__device__ __forceinline__ int lds_slot_w(int row, int chunk) { return row * 8 + (chunk ^ ((row & 3) | ((row >> 2) & 4))); }
 
 __device__ __forceinline__ void split_bf16(const float* f, op16& hi, op16& lo)
 {
@@ -53,16 +57,22 @@ __device__ __forceinline__ void split_bf16(const float* f, op16& hi, op16& lo)
     lo.u = uint4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
 }
 
-template <bool DELTA>
+extern __shared__ uint4 gemm_lds[];
+
+// KTAIL: K is not a multiple of 64, the last stage's chunks beyond K are zero-filled
+template <int WB, bool DELTA, bool KTAIL>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     int T, int K, int N, const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ Wt, int64_t ldw,
     bf16_t* __restrict__ y, int64_t ldy, int tiles_n, int tiles_t,
     const int32_t* __restrict__ token_adapter, const int32_t* __restrict__ rank,
     const float* __restrict__ v, lora_vspec vsp, const bf16_t* const* __restrict__ Bt_ptrs)
 {
+    constexpr int BM = 64 * WB;            // features per workgroup tile
+    constexpr int BT = 64 * WB;            // tokens per workgroup tile
+    constexpr int NLD = (BM * 8) / 256;    // 16-byte chunks of W (and of x) per thread and stage
     const int R = vsp.R;
-    __shared__ uint4 lds_w[2][BM * 8];
-    __shared__ uint4 lds_x[2][BT * 8];
+    uint4* lds_w0 = gemm_lds;                       // [2][BM * 8]
+    uint4* lds_x0 = gemm_lds + 2 * BM * 8;          // [2][BT * 8]
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
     // run of tiles (so its L2 sees neighbouring tiles), walking token tiles
@@ -72,35 +82,35 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     {
         const int per = n_wg / 8, rem = n_wg % 8;
         const int xcd = id & 7, q = id >> 3;
-        // XCD k owns per + (k < rem) tiles
-        id = xcd * per + (xcd < rem ? xcd : rem) + q;
+        id = xcd * per + (xcd < rem ? xcd : rem) + q;   // XCD k owns per + (k < rem) tiles
     }
     const int tile_t = id % tiles_t, tile_n = id / tiles_t;
     const int n0 = tile_n * BM, t0 = tile_t * BT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wn = (wave & 1) * 64, wt = (wave >> 1) * 64;       // wavefront tile origin inside the workgroup tile
+    const int wn = (wave & 1) * (32 * WB), wt = (wave >> 1) * (32 * WB);   // wavefront tile origin
 
-    // global -> register staging: 4 chunks of W and 4 chunks of x per thread and stage
-    const bf16_t* gw[4];
-    const bf16_t* gx[4];
-    int slot[4];
+    // global -> register staging
+    const bf16_t* gw[NLD];
+    const bf16_t* gx[NLD];
+    int slot[NLD], slot_w[NLD];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NLD; ++i) {
         const int q = tid + i * 256, row = q >> 3, c = q & 7;
         int nr = n0 + row; if (nr >= N) nr = N - 1;
         int tr = t0 + row; if (tr >= T) tr = T - 1;
         gw[i] = Wt + (int64_t)nr * ldw + c * 8;
         gx[i] = x + (int64_t)tr * ldx + c * 8;
         slot[i] = lds_slot(row, c);
+        slot_w[i] = lds_slot_w(row, c);
     }
     const int c_lane8 = (tid & 7) * 8;                           // this thread's k offset inside a stage
 
-    floatx16 acc[2][2];
+    floatx16 acc[WB][WB];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < WB; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < WB; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
@@ -110,51 +120,120 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     const int frow = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
 
     const int stages = (K + BK - 1) / BK;
-    uint4 rw[4], rx[4];
+    uint4 rw[NLD], rx[NLD];
     auto load_stage = [&](int s) {
         const int k = s * BK;
-        const bool in = k + c_lane8 < K;                         // K % 8 == 0: chunk is whole or absent
+        const bool in = !KTAIL || k + c_lane8 < K;               // K % 8 == 0: chunk is whole or absent
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NLD; ++i) {
             rw[i] = in ? *reinterpret_cast<const uint4*>(gw[i] + k) : uint4{0, 0, 0, 0};
             rx[i] = in ? *reinterpret_cast<const uint4*>(gx[i] + k) : uint4{0, 0, 0, 0};
         }
     };
     auto store_stage = [&](int buf) {
+        uint4* lw = lds_w0 + buf * BM * 8;
+        uint4* lx = lds_x0 + buf * BT * 8;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            lds_w[buf][slot[i]] = rw[i];
-            lds_x[buf][slot[i]] = rx[i];
+        for (int i = 0; i < NLD; ++i) {
+            lw[slot_w[i]] = rw[i];
+            lx[slot[i]] = rx[i];
         }
     };
 
+    auto read_ops = [&](const uint4* lw, const uint4* lx, int ks, op16 (&wa)[WB], op16 (&xb)[WB]) {
+        const int c = ks * 2 + h;
+#pragma unroll
+        for (int a = 0; a < WB; ++a) wa[a].u = lw[lds_slot_w(wn + a * 32 + frow, c)];
+#pragma unroll
+        for (int b = 0; b < WB; ++b) xb[b].u = lx[lds_slot(wt + b * 32 + l32, c)];
+    };
+    auto mma = [&](const op16 (&wa)[WB], const op16 (&xb)[WB]) {
+#pragma unroll
+        for (int a = 0; a < WB; ++a)
+#pragma unroll
+            for (int b = 0; b < WB; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a].v, xb[b].v, acc[a][b], 0, 0, 0);
+    };
+
+    // Software pipeline.  Global loads run two stages ahead (registers), LDS is double
+    // buffered, MFMA operands are double buffered in registers: while the matrix cores
+    // work on k-step ks the LDS reads of ks+1 are in flight, and the barrier between
+    // stages sits before the last k-step so that its MFMAs cover the first reads of the
+    // next stage.
     load_stage(0);
     store_stage(0);
+    if (stages > 1) load_stage(1);
     __syncthreads();
-    for (int s = 0; s < stages; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < stages) load_stage(s + 1);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {                          // 4 MFMA k-steps of 16 per stage
-            op16 wa[2], xb[2];
+    op16 waA[WB], xbA[WB], waB[WB], xbB[WB];
+    read_ops(lds_w0, lds_x0, 0, waA, xbA);
+    int s = 0;
+    if constexpr (WB == 4 && !KTAIL) {
+        // Steady state, written out so that every MFMA is followed by exactly one memory
+        // operation (the scheduler is pinned to that order): the 64 MFMAs of a stage carry
+        // its 32 LDS operand reads, the 16 LDS writes of the next stage and the 16 global
+        // loads of the stage after that, and the matrix cores never wait for a block of them.
+        auto one_read = [&](const uint4* lw, const uint4* lx, int ks, int i, op16 (&wa)[WB], op16 (&xb)[WB]) {
             const int c = ks * 2 + h;
+            if (i < 4) wa[i].u = lw[lds_slot_w(wn + i * 32 + frow, c)];
+            else xb[i - 4].u = lx[lds_slot(wt + (i - 4) * 32 + l32, c)];
+        };
+#define MMA1(WA, XB, IDX) \
+        acc[(IDX) >> 2][(IDX) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WA[(IDX) >> 2].v, XB[(IDX) & 3].v, acc[(IDX) >> 2][(IDX) & 3], 0, 0, 0)
+#define PIN(MASK) do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(MASK, 1, 0); } while (0)
+        for (; s + 2 < stages; ++s) {
+            const int buf = s & 1;
+            const uint4* lw = lds_w0 + buf * BM * 8;
+            const uint4* lx = lds_x0 + buf * BT * 8;
+            uint4* lw_n = lds_w0 + (buf ^ 1) * BM * 8;
+            uint4* lx_n = lds_x0 + (buf ^ 1) * BT * 8;
+            const int k2 = (s + 2) * BK;
+            // k-step 0: reads of k-step 1, W chunks of stage s+1 into LDS
 #pragma unroll
-            for (int a = 0; a < 2; ++a) wa[a].u = lds_w[buf][lds_slot(wn + a * 32 + frow, c)];
+            for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, i); one_read(lw, lx, 1, i, waB, xbB); PIN(0x100); }
 #pragma unroll
-            for (int b = 0; b < 2; ++b) xb[b].u = lds_x[buf][lds_slot(wt + b * 32 + l32, c)];
+            for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, 8 + i); lw_n[slot_w[i]] = rw[i]; PIN(0x200); }
+            // k-step 1: reads of k-step 2, x chunks of stage s+1 into LDS
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, i); one_read(lw, lx, 2, i, waA, xbA); PIN(0x100); }
 #pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a].v, xb[b].v, acc[a][b], 0, 0, 0);
+            for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, 8 + i); lx_n[slot[i]] = rx[i]; PIN(0x200); }
+            // k-step 2: reads of k-step 3, W chunks of stage s+2 from HBM
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, i); one_read(lw, lx, 3, i, waB, xbB); PIN(0x100); }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, 8 + i); rw[i] = *reinterpret_cast<const uint4*>(gw[i] + k2); PIN(0x020); }
+            __syncthreads();                             // stage s+1 is in LDS; nobody reads stage s any more
+            // k-step 3: reads of k-step 0 of stage s+1, x chunks of stage s+2 from HBM
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, i); one_read(lw_n, lx_n, 0, i, waA, xbA); PIN(0x100); }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, 8 + i); rx[i] = *reinterpret_cast<const uint4*>(gx[i] + k2); PIN(0x020); }
         }
-        if (s + 1 < stages) store_stage(buf ^ 1);
-        __syncthreads();
+#undef MMA1
+#undef PIN
+    }
+    for (; s < stages; ++s) {
+        const int buf = s & 1;
+        const uint4* lw = lds_w0 + buf * BM * 8;
+        const uint4* lx = lds_x0 + buf * BT * 8;
+        const uint4* lw_n = lds_w0 + (buf ^ 1) * BM * 8;
+        const uint4* lx_n = lds_x0 + (buf ^ 1) * BT * 8;
+        read_ops(lw, lx, 1, waB, xbB);
+        mma(waA, xbA);
+        read_ops(lw, lx, 2, waA, xbA);
+        if (s + 1 < stages) store_stage(buf ^ 1);        // stage s+1: fetched one stage ago
+        if (s + 2 < stages) load_stage(s + 2);
+        mma(waB, xbB);
+        read_ops(lw, lx, 3, waB, xbB);
+        mma(waA, xbA);
+        __syncthreads();                                 // stage s+1 is in LDS; nobody reads stage s any more
+        if (s + 1 < stages) read_ops(lw_n, lx_n, 0, waA, xbA);
+        mma(waB, xbB);
     }
 
     // ---- epilogue: adapter delta, rounding, store -------------------------
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < WB; ++b) {
         const int t = t0 + wt + b * 32 + l32;                    // this lane's token in column block b
         const bool t_ok = t < T;
         if constexpr (DELTA) {
@@ -173,24 +252,20 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
                     const int j = j0 + 8 * h;
                     op16 vhi, vlo;
                     float f[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) f[i] = 0.f;
                     if (mine && j < r) {
-                        const float4 p0 = *reinterpret_cast<const float4*>(v + (int64_t)t * R + j);
-                        const float4 p1 = *reinterpret_cast<const float4*>(v + (int64_t)t * R + j + 4);
-                        f[0] = p0.x; f[1] = p0.y; f[2] = p0.z; f[3] = p0.w; f[4] = p1.x; f[5] = p1.y; f[6] = p1.z; f[7] = p1.w;
-                        for (int q = 1; q < vsp.P; ++q) {
+                        for (int q = 0; q < vsp.P; ++q) {          // v = sum of its K parts
                             const float* vq = v + q * vsp.part + (int64_t)t * R + j;
                             const float4 q0 = *reinterpret_cast<const float4*>(vq);
                             const float4 q1 = *reinterpret_cast<const float4*>(vq + 4);
                             f[0] += q0.x; f[1] += q0.y; f[2] += q0.z; f[3] += q0.w; f[4] += q1.x; f[5] += q1.y; f[6] += q1.z; f[7] += q1.w;
                         }
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) f[i] = 0.f;
                     }
                     split_bf16(f, vhi, vlo);
 #pragma unroll
-                    for (int a = 0; a < 2; ++a) {
-                        int n = n0 + wn + a * 32 + frow;
+                    for (int a = 0; a < WB; ++a) {
+                        const int n = n0 + wn + a * 32 + frow;
                         op16 bo;
                         bo.u = (n < N && j < r) ? *reinterpret_cast<const uint4*>(Bt + (int64_t)n * r + j) : uint4{0, 0, 0, 0};
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bo.v, vhi.v, acc[a][b], 0, 0, 0);
@@ -201,7 +276,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
         }
         if (!t_ok) continue;
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
+        for (int a = 0; a < WB; ++a) {
             const int n = n0 + wn + a * 32 + 16 * h;             // first of this lane's 16 features
             bf16_t* yp = y + (int64_t)t * ldy + n;
             // acc index i = 4q + p  <->  feature offset 4q + p
@@ -221,6 +296,27 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     }
 }
 
+template <int WB, bool DELTA, bool KTAIL>
+hipError_t launch_one(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx, const void* Wt, int64_t ldw,
+                      void* y, int64_t ldy, const int32_t* token_adapter, const int32_t* rank, const float* v,
+                      lora_vspec vsp, const void* const* Bt, hipStream_t stream)
+{
+    constexpr int BM = 64 * WB;
+    const int tiles_n = (N + BM - 1) / BM, tiles_t = (T + BM - 1) / BM;
+    const size_t lds_bytes = (size_t)2 * 2 * BM * 8 * sizeof(uint4);
+    static bool attr_set = false;                 // dynamic LDS above 64 KB has to be allowed once per kernel
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<WB, DELTA, KTAIL>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    LORA_LAUNCH(DELTA ? LORA_K_GEMM_TILED_DELTA : LORA_K_GEMM_TILED, (gemm_tiled_kernel<WB, DELTA, KTAIL>),
+                dim3(tiles_n * tiles_t), dim3(256), lds_bytes, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
+                (bf16_t*)y, ldy, tiles_n, tiles_t, token_adapter, rank, v, vsp, (const bf16_t* const*)Bt);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const void* x, int64_t ldx,
@@ -230,7 +326,7 @@ bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const 
     if (dtype != LORA_BF16 || T < 1 || N < 1) return false;
     if (K % 8 || ldx % 8 || ldw % 8 || ldy % 8) return false;
     if (mis(x) || mis(Wt) || mis(y)) return false;
-    const int64_t tiles = (int64_t)((N + BM - 1) / BM) * ((T + BT - 1) / BT);
+    const int64_t tiles = (int64_t)((N + 127) / 128) * ((T + 127) / 128);
     return tiles < (1ll << 31);
 }
 
@@ -239,14 +335,20 @@ hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int
                              const lora_plan* p, const lora_dev_tables* d, const float* v,
                              const void* const* Bt, hipStream_t stream)
 {
-    const int tiles_n = (N + BM - 1) / BM, tiles_t = (T + BT - 1) / BT;
-    const int grid = tiles_n * tiles_t;
-    if (p && !p->perm.empty())
-        LORA_LAUNCH(LORA_K_GEMM_TILED_DELTA, (gemm_tiled_kernel<true>), dim3(grid), dim3(256), 0, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
-            (bf16_t*)y, ldy, tiles_n, tiles_t, d->token_adapter, d->rank, v, lora_vspec_of(p), (const bf16_t* const*)Bt);
-    else
-        LORA_LAUNCH(LORA_K_GEMM_TILED, (gemm_tiled_kernel<false>), dim3(grid), dim3(256), 0, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
-            (bf16_t*)y, ldy, tiles_n, tiles_t, (const int32_t*)nullptr, (const int32_t*)nullptr, (const float*)nullptr, lora_vspec{0, 1, 0},
-            (const bf16_t* const*)nullptr);
-    return hipGetLastError();
+    // 256 x 256 tiles once there are enough of them to fill the 256 compute units
+    const bool big = (int64_t)((N + 255) / 256) * ((T + 255) / 256) >= 192;
+    const bool delta = p && !p->perm.empty();
+    const int32_t* ta = delta ? d->token_adapter : nullptr;
+    const int32_t* rk = delta ? d->rank : nullptr;
+    const lora_vspec vsp = delta ? lora_vspec_of(p) : lora_vspec{0, 1, 0};
+    const bool ktail = (K % BK) != 0;
+#define GEMM_DISPATCH(WB_, D_, KT_) \
+    launch_one<WB_, D_, KT_>(T, K, N, x, ldx, Wt, ldw, y, ldy, ta, rk, v, vsp, Bt, stream)
+    if (big) {
+        if (delta) return ktail ? GEMM_DISPATCH(4, true, true) : GEMM_DISPATCH(4, true, false);
+        return ktail ? GEMM_DISPATCH(4, false, true) : GEMM_DISPATCH(4, false, false);
+    }
+    if (delta) return ktail ? GEMM_DISPATCH(2, true, true) : GEMM_DISPATCH(2, true, false);
+    return ktail ? GEMM_DISPATCH(2, false, true) : GEMM_DISPATCH(2, false, false);
+#undef GEMM_DISPATCH
 }

@@ -106,6 +106,17 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     }
     const int c_lane8 = (tid & 7) * 8;                           // this thread's k offset inside a stage
 
+    // adapter of this lane's token in each of its WB column blocks; fetched now, used in the epilogue
+    int my_adapter[WB];
+#pragma unroll
+    for (int b = 0; b < WB; ++b) {
+        my_adapter[b] = -1;
+        if constexpr (DELTA) {
+            const int t = t0 + wt + b * 32 + (lane & 31);
+            if (t < T) my_adapter[b] = token_adapter[t];
+        }
+    }
+
     floatx16 acc[WB][WB];
 #pragma unroll
     for (int a = 0; a < WB; ++a)
@@ -237,8 +248,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
         const int t = t0 + wt + b * 32 + l32;                    // this lane's token in column block b
         const bool t_ok = t < T;
         if constexpr (DELTA) {
-            const int my_a = t_ok ? token_adapter[t] : -1;
-            // adapters present in this 32-token column block, one pass each
+            const int my_a = my_adapter[b];
+            // adapters present in this 32-token column block, one pass each; v is masked to the
+            // pass's tokens, so other tokens of the block receive exactly zero from it
             unsigned long long todo = __ballot(my_a >= 0) & 0xffffffffull;   // lanes 0..31 and 32..63 hold the same tokens
             while (todo) {
                 const int leader = __ffsll((long long)todo) - 1;
@@ -248,28 +260,49 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
                 const int r = rank[a_id];
                 const bf16_t* Bt = Bt_ptrs[a_id];
                 const bool mine = my_a == a_id;
-                for (int j0 = 0; j0 < r; j0 += 16) {
-                    const int j = j0 + 8 * h;
-                    op16 vhi, vlo;
-                    float f[8];
+                constexpr int JS = 4;                            // k-steps of 16 whose loads go out together
+                for (int j0 = 0; j0 < r; j0 += 16 * JS) {
+                    float4 va[JS][2];
+                    uint4 bo[JS][WB];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) f[i] = 0.f;
-                    if (mine && j < r) {
-                        for (int q = 0; q < vsp.P; ++q) {          // v = sum of its K parts
-                            const float* vq = v + q * vsp.part + (int64_t)t * R + j;
-                            const float4 q0 = *reinterpret_cast<const float4*>(vq);
-                            const float4 q1 = *reinterpret_cast<const float4*>(vq + 4);
-                            f[0] += q0.x; f[1] += q0.y; f[2] += q0.z; f[3] += q0.w; f[4] += q1.x; f[5] += q1.y; f[6] += q1.z; f[7] += q1.w;
+                    for (int u = 0; u < JS; ++u) {
+                        const int j = j0 + 16 * u + 8 * h;
+                        const bool ok = j < r;
+                        if (mine && ok) {
+                            const float* vq = v + (int64_t)t * R + j;
+                            va[u][0] = *reinterpret_cast<const float4*>(vq);
+                            va[u][1] = *reinterpret_cast<const float4*>(vq + 4);
+                        } else {
+                            va[u][0] = make_float4(0.f, 0.f, 0.f, 0.f);
+                            va[u][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
+#pragma unroll
+                        for (int a = 0; a < WB; ++a) {
+                            const int n = n0 + wn + a * 32 + frow;
+                            bo[u][a] = (n < N && ok) ? *reinterpret_cast<const uint4*>(Bt + (int64_t)n * r + j) : uint4{0, 0, 0, 0};
                         }
                     }
-                    split_bf16(f, vhi, vlo);
 #pragma unroll
-                    for (int a = 0; a < WB; ++a) {
-                        const int n = n0 + wn + a * 32 + frow;
-                        op16 bo;
-                        bo.u = (n < N && j < r) ? *reinterpret_cast<const uint4*>(Bt + (int64_t)n * r + j) : uint4{0, 0, 0, 0};
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bo.v, vhi.v, acc[a][b], 0, 0, 0);
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bo.v, vlo.v, acc[a][b], 0, 0, 0);
+                    for (int u = 0; u < JS; ++u) {
+                        const int j = j0 + 16 * u + 8 * h;
+                        float f[8] = {va[u][0].x, va[u][0].y, va[u][0].z, va[u][0].w, va[u][1].x, va[u][1].y, va[u][1].z, va[u][1].w};
+                        if (mine && j < r) {
+                            for (int q = 1; q < vsp.P; ++q) {      // v = sum of its K parts (plans of small tiles only)
+                                const float* vq = v + q * vsp.part + (int64_t)t * R + j;
+                                const float4 q0 = *reinterpret_cast<const float4*>(vq);
+                                const float4 q1 = *reinterpret_cast<const float4*>(vq + 4);
+                                f[0] += q0.x; f[1] += q0.y; f[2] += q0.z; f[3] += q0.w; f[4] += q1.x; f[5] += q1.y; f[6] += q1.z; f[7] += q1.w;
+                            }
+                        }
+                        op16 vhi, vlo;
+                        split_bf16(f, vhi, vlo);
+#pragma unroll
+                        for (int a = 0; a < WB; ++a) {
+                            op16 bop;
+                            bop.u = bo[u][a];
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop.v, vhi.v, acc[a][b], 0, 0, 0);
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop.v, vlo.v, acc[a][b], 0, 0, 0);
+                        }
                     }
                 }
             }

@@ -258,7 +258,10 @@ const char* lora_status_str(lora_status s);
  * tile for adapter groups below shrink_tb2_min_rows, 1..2), shrink_target_wgs
  * (small launches split K over up to 4 workgroups per tile until they have this
  * many workgroups), fused_spin_limit (lora_delta's single launch: polls an expand
- * block waits for its shrink blocks, plus one; 1 = never wait, always recompute).
+ * block waits for its shrink blocks, plus one; 1 = never wait, always recompute),
+ * fused_delay (lora_delta's single launch: head start given to the shrink blocks'
+ * loads, units of about 0.4 us, plus one), expand_wave_bytes_big (expand_wave_bytes
+ * for adapter groups of at least expand_tb2_min_rows tokens).
  * Entries <= 0 keep the current value; plans made
  * earlier are unaffected.  Host only.
  */

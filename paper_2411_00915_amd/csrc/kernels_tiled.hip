@@ -418,7 +418,7 @@ __global__ __launch_bounds__(256) void expand_tiled_kernel(
     const int tb = tile.shape & 15;
     const int ks = (r + 31) >> 5;
 #define EXPAND_CASE(TB_, KS_) \
-    if (tb == TB_ && ks == KS_) { expand_tile<TB_, KS_, (TB_ * KS_ <= 4), 0>(tile, perm, v, R, Bt, r, y, ldy, N, beta); return; }
+    if (tb == TB_ && ks == KS_) { expand_tile<TB_, KS_, (TB_ * KS_ <= 8), 0>(tile, perm, v, R, Bt, r, y, ldy, N, beta); return; }
     EXPAND_CASE(1, 1)
     EXPAND_CASE(1, 2)
     EXPAND_CASE(1, 3)

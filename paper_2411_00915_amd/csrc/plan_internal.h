@@ -62,5 +62,6 @@ struct lora_tuning {
     int32_t shrink_target_wgs;     // small build: split K over up to 4 workgroups until the launch has this many
     int32_t fused_spin_limit;      // single-launch decode kernel: polls before an expand block computes v itself (+1; 1 = never wait)
     int32_t fused_delay;           // single-launch decode kernel: head start of the shrink blocks' loads, units of ~0.4 us (+1)
+    int32_t expand_wave_bytes_big; // like expand_wave_bytes, for adapter groups of at least expand_tb2_min_rows tokens
 };
 extern lora_tuning g_lora_tuning;

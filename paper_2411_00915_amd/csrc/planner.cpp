@@ -25,6 +25,7 @@ lora_tuning g_lora_tuning = {
     /*shrink_target_wgs*/ 384,
     /*fused_spin_limit*/ 200000,
     /*fused_delay*/ 3,
+    /*expand_wave_bytes_big*/ 131072,
 };
 
 extern "C" void lora_tuning_set(const int32_t* values, int32_t count)
@@ -118,7 +119,10 @@ static void build_tiles(lora_plan* p)
             // output features per wavefront: a multiple of 64, sized so that the
             // wavefront streams about expand_wave_bytes of Bt and y
             const int64_t per_n = 2 * (int64_t)r + 4 * 16 * (int64_t)tb;
-            int32_t nw = (int32_t)std::max<int64_t>(64, (tu.expand_wave_bytes / per_n) / 64 * 64);
+            // (long ranges for big groups and big batches: the wavefront loops with the next chunk in flight;
+            // short ranges for decode-sized batches, where the launch is one round of memory latency)
+            const int64_t wave_bytes = (tb > 1 || p->perm.size() >= 1024) ? tu.expand_wave_bytes_big : tu.expand_wave_bytes;
+            int32_t nw = (int32_t)std::max<int64_t>(64, (wave_bytes / per_n) / 64 * 64);
             const int32_t n_tile = 4 * nw;
             for (int32_t row = lo; row < hi; row += 16 * tb) {
                 const int32_t nrows = std::min<int32_t>(16 * tb, hi - row);

@@ -261,7 +261,8 @@ const char* lora_status_str(lora_status s);
  * block waits for its shrink blocks, plus one; 1 = never wait, always recompute),
  * fused_delay (lora_delta's single launch: head start given to the shrink blocks'
  * loads, units of about 0.4 us, plus one), expand_wave_bytes_big (expand_wave_bytes
- * for adapter groups of at least expand_tb2_min_rows tokens).
+ * for adapter groups of at least expand_tb2_min_rows tokens), shrink_tb4_min_rows
+ * (adapter groups with at least this many tokens use 64-token shrink tiles).
  * Entries <= 0 keep the current value; plans made
  * earlier are unaffected.  Host only.
  */

@@ -67,20 +67,26 @@ __device__ __forceinline__ void shrink_tile(
         arow[jb] = At + (int64_t)(tile.c0 + j) * K + g * 8;
     }
 
-    // Output element this thread stores after the reduction (threads beyond the
-    // tile's TB*JB*64 float4 slots store nothing).  Looked up now: no global load
-    // is left between the reduction and the store.  The tile carries s_a.
+    // Output element this thread stores first after the reduction (a tile has TB*JB*64
+    // float4 slots; threads take slots threadIdx.x, threadIdx.x + blockDim.x, ...).
+    // Looked up now: for tiles that fit the workgroup no global load is left between
+    // the reduction and the store.  The tile carries s_a.
     const float s_a = __int_as_float(tile.reserved1);
-    int out_t = -1, out_j = 0;
-    if ((int)threadIdx.x < TB * JB * 64) {
-        const int l = threadIdx.x & 63, blk = threadIdx.x >> 6;
-        const int row = (blk / JB) * 16 + (l & 15);
-        const int j = (blk % JB) * 16 + 4 * (l >> 4);
-        if (row < tile.nrows && j < tile.cn) {
-            out_t = perm[tile.row0 + row];
-            out_j = tile.c0 + j;
+    auto out_slot = [&](int e, int& t_out, int& j_out) {
+        t_out = -1;
+        j_out = 0;
+        if (e < TB * JB * 64) {
+            const int l = e & 63, blk = e >> 6;
+            const int row = (blk / JB) * 16 + (l & 15);
+            const int j = (blk % JB) * 16 + 4 * (l >> 4);
+            if (row < tile.nrows && j < tile.cn) {
+                t_out = perm[tile.row0 + row];
+                j_out = tile.c0 + j;
+            }
         }
-    }
+    };
+    int out_t, out_j;
+    out_slot((int)threadIdx.x, out_t, out_j);
 
     floatx4 acc[TB][JB];
 #pragma unroll
@@ -135,12 +141,14 @@ __device__ __forceinline__ void shrink_tile(
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) lds[((wave * TB + tb) * JB + jb) * 64 + lane] = acc[tb][jb];
     __syncthreads();
-    if (out_t >= 0) {
+    for (int e = threadIdx.x; e < TB * JB * 64; e += blockDim.x) {
+        if (e != (int)threadIdx.x) out_slot(e, out_t, out_j);
+        if (out_t < 0) continue;
         // all partials are fetched before the first add, so the LDS reads overlap
         floatx4 part[16];
 #pragma unroll
         for (int w = 0; w < 16; ++w)
-            part[w] = (w < W) ? lds[w * TB * JB * 64 + (int)threadIdx.x] : floatx4{0.f, 0.f, 0.f, 0.f};
+            part[w] = (w < W) ? lds[w * TB * JB * 64 + e] : floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int st = 8; st > 0; st >>= 1)
 #pragma unroll
@@ -194,6 +202,10 @@ __global__ __launch_bounds__(512) void shrink_tiled_kernel(
     SHRINK_CASE(2, 2, 4)
     SHRINK_CASE(2, 3, 2)
     SHRINK_CASE(2, 4, 2)
+    SHRINK_CASE(4, 1, 4)
+    SHRINK_CASE(4, 2, 2)
+    SHRINK_CASE(4, 3, 2)
+    SHRINK_CASE(4, 4, 2)
 #undef SHRINK_CASE
 }
 

@@ -63,5 +63,6 @@ struct lora_tuning {
     int32_t fused_spin_limit;      // single-launch decode kernel: polls before an expand block computes v itself (+1; 1 = never wait)
     int32_t fused_delay;           // single-launch decode kernel: head start of the shrink blocks' loads, units of ~0.4 us (+1)
     int32_t expand_wave_bytes_big; // like expand_wave_bytes, for adapter groups of at least expand_tb2_min_rows tokens
+    int32_t shrink_tb4_min_rows;   // groups with at least this many tokens use 64-token shrink tiles
 };
 extern lora_tuning g_lora_tuning;

@@ -22,10 +22,11 @@ lora_tuning g_lora_tuning = {
     /*tiled_min_tokens*/ 1,
     /*shrink_small_waves*/ 16,
     /*shrink_small_jb*/ 1,
-    /*shrink_target_wgs*/ 384,
+    /*shrink_target_wgs*/ 768,
     /*fused_spin_limit*/ 200000,
     /*fused_delay*/ 3,
     /*expand_wave_bytes_big*/ 131072,
+    /*shrink_tb4_min_rows*/ 64,
 };
 
 extern "C" void lora_tuning_set(const int32_t* values, int32_t count)
@@ -85,14 +86,14 @@ static void build_tiles(lora_plan* p)
         const int32_t lo = p->group_offset[g], hi = p->group_offset[g + 1];
         const int32_t m = hi - lo;
 
-        // ---- shrink: groups with many tokens take 32-token tiles over up to 64
-        // rank rows (x is the big stream, read it once); groups with few tokens
+        // ---- shrink: groups with many tokens take 32- or 64-token tiles over up to 64
+        // rank rows (x is the big stream, and At is re-read once per tile); groups with few tokens
         // take 16-token tiles over 16 (or 32) rank rows so that the launch has
         // many workgroups (A is the big stream, each byte is read once anyway)
         {
             const int jblocks = (r + 15) / 16;
             const bool large = m >= tu.shrink_tb2_min_rows;
-            const int tb = large ? 2 : 1;
+            const int tb = m >= tu.shrink_tb4_min_rows ? 4 : (large ? 2 : 1);
             const int jb = std::min(jblocks, large ? std::max(1, std::min(tu.shrink_max_jb, 4))
                                                    : std::max(1, std::min(tu.shrink_small_jb, 2)));
             for (int32_t row = lo; row < hi; row += 16 * tb) {
@@ -101,7 +102,7 @@ static void build_tiles(lora_plan* p)
                     lora_tile t{};
                     t.adapter = a; t.row0 = row; t.nrows = nrows;
                     t.c0 = j0; t.cn = std::min<int32_t>(16 * jb, r - j0);
-                    const int tbk = nrows > 16 ? 2 : 1, jbk = (t.cn + 15) / 16;
+                    const int tbk = nrows > 32 ? 4 : (nrows > 16 ? 2 : 1), jbk = (t.cn + 15) / 16;
                     t.shape = lora_shape_code(tbk, jbk) | ((g & 0xffff) << 16);   // bits 16..31: adapter group
                     t.reserved0 = r;
                     std::memcpy(&t.reserved1, &p->scale[a], sizeof(float));   // s_a travels with the tile
@@ -148,7 +149,7 @@ static void build_tiles(lora_plan* p)
     // tile (P in 1, 2, 4); each part writes its own slice of v and every consumer
     // of v adds the parts in order, so there are no atomics and no zeroing.
     p->v_parts = 1;
-    if (p->shrink_small) {
+    {
         int P = 1;
         while (P < 4 && (int64_t)p->shrink_tiles.size() * P < tu.shrink_target_wgs && steps / (2 * P) >= 8) P *= 2;
         p->v_parts = P;
@@ -167,10 +168,7 @@ static void build_tiles(lora_plan* p)
     if (p->shrink_small)
         p->shrink_waves = std::max(1, std::min({tu.shrink_small_waves / p->v_parts, 16, steps / p->v_parts}));
     else
-        p->shrink_waves = std::max(1, std::min({tu.shrink_waves, 8, 64 / p->shrink_max_blocks, steps}));
-    // one thread per float4 of a tile's output stores the result, so a workgroup
-    // has at least one wavefront per 16x16 block (wavefronts without k-steps add zeros)
-    p->shrink_waves = std::max(p->shrink_waves, p->shrink_max_blocks);
+        p->shrink_waves = std::max(1, std::min({tu.shrink_waves, 8, 64 / p->shrink_max_blocks, steps / p->v_parts}));
     // Single-launch decode kernel: an expand tile carries (bits 8..31 of its shape)
     // the numbers of shrink tiles
     // (bits 8..19 of its shape) and of expand tiles (bits 20..31) of its adapter group.

@@ -311,3 +311,48 @@ def test_single_launch_delta_small_and_mixed_cases():
         _delta_case(w, fallback=True)
     wf = wl.random_case(410, 33, 40, 48, 3, (4, 8), dtype="f32", max_seg=6, frac_none=0.2)
     _delta_case(wf)
+
+
+# ---------------------------------------------------------------- mixture mode through the same operator
+def test_delora_mixture_mode():
+    """Mixture inference (section 4.4.1): adapter 1 is merged into the base weight, requests of other adapters
+    run unmerged with a de-LoRA branch that removes adapter 1 again.  Expressed through the operator as a
+    concatenated adapter [A_x | A_1], [s_x B_x ; -s_1 B_1] with scale 1; requests of adapter 1 itself run
+    with no adapter on the merged weight.  The result must equal plain unmerged inference on the base weight."""
+    rng = np.random.default_rng(77)
+    T, K, N, r1, rx = 96, 256, 192, 16, 8
+    x = wl.round_to_bf16(rng.standard_normal((T, K), dtype=np.float32))
+    W = wl.round_to_bf16(rng.standard_normal((K, N), dtype=np.float32) * K ** -0.5)
+    A1 = wl.round_to_bf16(rng.standard_normal((K, r1), dtype=np.float32) * K ** -0.5)
+    B1 = wl.round_to_bf16(rng.standard_normal((r1, N), dtype=np.float32) * r1 ** -0.5)
+    Ax = wl.round_to_bf16(rng.standard_normal((K, rx), dtype=np.float32) * K ** -0.5)
+    Bx = wl.round_to_bf16(rng.standard_normal((rx, N), dtype=np.float32) * rx ** -0.5)
+    s1, sx = 2.0, 0.5                                       # powers of two: s B stays bf16-representable
+    # segments: 0..47 adapter 1 (merged), 48..95 adapter x
+    indptr = np.array([0, 48, 96], np.int32)
+    plain = wl.Workload("plain", "bf16", T, K, N, indptr, np.array([0, 1], np.int32), np.array([r1, rx], np.int32),
+                        np.array([s1, sx], np.float32), x, W, [A1, Ax], [B1, Bx])
+    tok = oracle.token_adapter(T, indptr, plain.seg_adapter)
+    y_ref = oracle.forward(x, W, tok, oracle.Adapters(plain.adapter_rank, plain.adapter_scale, plain.A, plain.B))
+    # merged weight in float64, rounded once to bf16 as a deployment would store it
+    W_merge = wl.round_to_bf16((W.astype(np.float64) + s1 * (A1.astype(np.float64) @ B1.astype(np.float64))).astype(np.float32))
+    Acat = np.concatenate([Ax, A1], axis=1)
+    Bcat = np.concatenate([sx * Bx, -s1 * B1], axis=0)
+    mixed = wl.Workload("mixed", "bf16", T, K, N, indptr, np.array([-1, 0], np.int32), np.array([rx + r1], np.int32),
+                        np.array([1.0], np.float32), x, W_merge, [Acat], [Bcat])
+    dl = device.to_device(mixed, DEV, with_w=True)
+    plan = device.make_plan(mixed)
+    _, _, ws_bytes = B.lora_plan_query(plan)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
+    y = torch.zeros((T, N), dtype=torch.bfloat16, device=DEV)
+    B.lora_fused_forward(plan, dl.x, K, dl.Wt, K, dl.At_ptrs, dl.Bt_ptrs, y, N, ws, ws.numel())
+    torch.cuda.synchronize()
+    # the GPU path against the oracle on the same (merged, rounded) inputs: the usual tolerance
+    y_mixed_ref = oracle.forward(x, W_merge, oracle.token_adapter(T, indptr, mixed.seg_adapter),
+                                 oracle.Adapters(mixed.adapter_rank, mixed.adapter_scale, mixed.A, mixed.B))
+    _assert_close(_to_np(y), y_mixed_ref, BF16_TOL, "mixture mode vs oracle")
+    # and against plain unmerged inference: equal up to the one extra rounding of the merged weight
+    nrm, _ = oracle.error_metrics(_to_np(y), y_ref)
+    print(f"    mixture vs plain unmerged: normwise {nrm:.3e}", flush=True)
+    assert nrm <= 6e-3
+    plan.destroy()

@@ -152,7 +152,7 @@ lora_status lora_plan_create(const lora_batch_desc* desc, lora_plan** out);
 void        lora_plan_destroy(lora_plan* plan);   /* NULL is allowed */
 
 /* v_row_stride R (floats), bytes of the v buffer (P*T*R*4), and the bytes of
- * workspace lora_fused_forward needs (it holds v).  Any out pointer may be NULL. */
+ * workspace lora_fused_forward needs (v plus its bf16 split).  Any out pointer may be NULL. */
 lora_status lora_plan_query(const lora_plan* plan, int32_t* v_row_stride,
                             size_t* v_bytes, size_t* fused_workspace_bytes);
 
@@ -231,9 +231,10 @@ lora_status lora_base_gemm(int32_t num_tokens, int32_t k, int32_t n, int32_t dty
  * with the adapter delta added to the base GEMM's fp32 accumulators before the
  * single rounding of y (unmerged inference at close to the cost of merged
  * inference, sections 2 and 4.4).  Runs the shrink into `workspace` (which
- * holds v; size from lora_plan_query, 256-byte aligned), then one GEMM kernel
- * whose epilogue applies the expand.  LORA_ERR_WORKSPACE if the workspace is
- * too small.
+ * holds v and its split into two bf16 terms; size from lora_plan_query,
+ * 256-byte aligned), then one GEMM kernel that walks the tokens in
+ * adapter-sorted order and takes each adapter's v B_a in as extra k-stages of
+ * its pipeline.  LORA_ERR_WORKSPACE if the workspace is too small.
  */
 lora_status lora_fused_forward(lora_plan* plan, const void* x, int64_t ldx,
                                const void* Wt, int64_t ldw,

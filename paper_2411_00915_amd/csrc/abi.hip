@@ -27,6 +27,7 @@ bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p
 
 struct table_layout {
     size_t perm, token_adapter, rank, scale, shrink_tiles, expand_tiles, sync, sync_bytes, total;
+    size_t order, extra_ptr128, extra128, extra_ptr256, extra256;
 };
 
 table_layout layout_of(const lora_plan* p)
@@ -40,6 +41,11 @@ table_layout layout_of(const lora_plan* p)
     L.scale = take(p->scale.size() * sizeof(float));
     L.shrink_tiles = take(p->shrink_tiles.size() * sizeof(lora_tile));
     L.expand_tiles = take(p->expand_tiles.size() * sizeof(lora_tile));
+    L.order = take(p->order.size() * sizeof(int32_t));
+    L.extra_ptr128 = take(p->extra_ptr128.size() * sizeof(int32_t));
+    L.extra128 = take(p->extra128.size() * sizeof(int32_t));
+    L.extra_ptr256 = take(p->extra_ptr256.size() * sizeof(int32_t));
+    L.extra256 = take(p->extra256.size() * sizeof(int32_t));
     L.sync_bytes = p->fused_ok ? p->group_adapter.size() * 128 : 0;
     L.sync = take(L.sync_bytes);
     L.total = std::max<size_t>(off, 256);
@@ -85,6 +91,11 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     put(L.scale, p->scale.data(), p->scale.size() * sizeof(float));
     put(L.shrink_tiles, p->shrink_tiles.data(), p->shrink_tiles.size() * sizeof(lora_tile));
     put(L.expand_tiles, p->expand_tiles.data(), p->expand_tiles.size() * sizeof(lora_tile));
+    put(L.order, p->order.data(), p->order.size() * sizeof(int32_t));
+    put(L.extra_ptr128, p->extra_ptr128.data(), p->extra_ptr128.size() * sizeof(int32_t));
+    put(L.extra128, p->extra128.data(), p->extra128.size() * sizeof(int32_t));
+    put(L.extra_ptr256, p->extra_ptr256.data(), p->extra_ptr256.size() * sizeof(int32_t));
+    put(L.extra256, p->extra256.data(), p->extra256.size() * sizeof(int32_t));
     std::memset(h + L.sync, 0, L.sync_bytes);                    // hand-off counters start at zero
     if (hipMemcpyAsync(dbuf, hbuf, L.total, hipMemcpyHostToDevice, stream) != hipSuccess) {
         (void)hipGetLastError();
@@ -104,13 +115,18 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     p->d_shrink_tiles = reinterpret_cast<lora_tile*>(d + L.shrink_tiles);
     p->d_expand_tiles = reinterpret_cast<lora_tile*>(d + L.expand_tiles);
     p->d_sync = d + L.sync;
+    p->d_order = reinterpret_cast<int32_t*>(d + L.order);
+    p->d_extra_ptr128 = reinterpret_cast<int32_t*>(d + L.extra_ptr128);
+    p->d_extra128 = reinterpret_cast<int32_t*>(d + L.extra128);
+    p->d_extra_ptr256 = reinterpret_cast<int32_t*>(d + L.extra_ptr256);
+    p->d_extra256 = reinterpret_cast<int32_t*>(d + L.extra256);
     return LORA_OK;
 }
 
 lora_dev_tables tables_of(const lora_plan* p)
 {
     return lora_dev_tables{p->d_perm, p->d_token_adapter, p->d_rank, p->d_scale, p->d_shrink_tiles, p->d_expand_tiles,
-                           p->d_sync};
+                           p->d_sync, p->d_order, p->d_extra_ptr128, p->d_extra128, p->d_extra_ptr256, p->d_extra256};
 }
 
 size_t elem_bytes(int32_t dtype) { return dtype == LORA_F32 ? 4 : 2; }
@@ -231,7 +247,7 @@ extern "C" lora_status lora_base_gemm(int32_t T, int32_t K, int32_t N, int32_t d
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
     if (gemm_tiled_supported(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy))
-        e = launch_gemm_tiled(T, K, N, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, stream);
+        e = launch_gemm_tiled(T, K, N, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
     else
         e = launch_gemm_general(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, stream);
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
@@ -256,6 +272,9 @@ extern "C" lora_status lora_fused_forward(lora_plan* p, const void* x, int64_t l
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     float* v = static_cast<float*>(workspace);
+    size_t v_bytes = 0;
+    lora_plan_query(p, nullptr, &v_bytes, nullptr);
+    void* vb = workspace ? static_cast<char*>(workspace) + (v_bytes + 255) / 256 * 256 : nullptr;   // bf16 split of v
     if (has_delta) {
         lora_status st = lora_shrink(p, x, ldx, d_At_ptrs, v, hip_stream);
         if (st != LORA_OK) return st;
@@ -266,8 +285,8 @@ extern "C" lora_status lora_fused_forward(lora_plan* p, const void* x, int64_t l
     const lora_dev_tables d = tables_of(p);
     hipError_t e;
     if (gemm_tiled_supported(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy) &&
-        (!has_delta || p->tiled_layout_ok))
-        e = launch_gemm_tiled(p->T, p->K, p->N, x, ldx, Wt, ldw, y, ldy, p, &d, v, d_Bt_ptrs, stream);
+        (!has_delta || (int32_t)p->order.size() == p->T))
+        e = launch_gemm_tiled(p->T, p->K, p->N, x, ldx, Wt, ldw, y, ldy, p, &d, v, vb, d_Bt_ptrs, stream);
     else
         e = launch_gemm_general(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy, p, &d, v, d_Bt_ptrs, stream);
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;

@@ -25,6 +25,11 @@ struct lora_dev_tables {
     const lora_tile* shrink_tiles;
     const lora_tile* expand_tiles;
     void* sync;                    // hand-off counters of the single-launch decode kernel: 128 bytes per adapter group
+    const int32_t* order;          // fused GEMM: row order and per-tile (adapter, rank block) lists
+    const int32_t* extra_ptr128;
+    const int32_t* extra128;
+    const int32_t* extra_ptr256;
+    const int32_t* extra256;
 };
 
 // general VALU family (any dtype, any alignment)
@@ -53,5 +58,5 @@ bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const 
                           const void* Wt, int64_t ldw, const void* y, int64_t ldy);
 hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx,
                              const void* Wt, int64_t ldw, void* y, int64_t ldy,
-                             const lora_plan* p, const lora_dev_tables* d, const float* v,
+                             const lora_plan* p, const lora_dev_tables* d, const float* v, void* vb,
                              const void* const* Bt, hipStream_t stream);

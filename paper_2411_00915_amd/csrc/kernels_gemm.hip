@@ -1,10 +1,17 @@
-// Base GEMM y = x W (bf16 MFMA, fp32 accumulate) with an optional adapter-delta
-// epilogue: y = x W + v B_a per token, v = s_a (x A_a) from the shrink kernel.
+// Base GEMM y = x W (bf16 MFMA, fp32 accumulate), optionally with the adapter
+// delta folded in: y = x W + v B_a per token, v = s_a (x A_a) from the shrink.
 //
 // This is the base-model product that unmerged inference shares across all
 // requests of the batch, with the adapter branches added on top (paper
 // sections 1-2); adding the delta to the fp32 accumulators before y is rounded
 // makes unmerged inference cost close to merged inference (section 4.4).
+//
+// The delta enters as extra k-stages of the same pipeline.  The kernel walks
+// the tokens in adapter-sorted order, so a tile of rows holds few adapters; for
+// each (adapter a, 64-wide rank block) present in a row tile it runs two more
+// stages whose "W tile" is Bt_a[features, ranks] and whose "x tile" is v_hi
+// resp. v_lo (v split into two bf16 terms, rows of other adapters zero).  Their
+// loads are prefetched like any other stage's: nothing is exposed in an epilogue.
 //
 // x [T,K] and Wt [N,K] are both contraction-index-fastest, so tiles go
 // HBM -> registers -> LDS as 16-byte chunks and come back out of LDS as
@@ -58,21 +65,35 @@ __device__ __forceinline__ void split_bf16(const float* f, op16& hi, op16& lo)
 }
 
 extern __shared__ uint4 gemm_lds[];
+constexpr int META_MAX = 256;      // adapter stages of a tile whose metadata is cached in LDS (more are read from memory)
 
-// KTAIL: K is not a multiple of 64, the last stage's chunks beyond K are zero-filled
+struct gemm_delta_args {
+    const int32_t* order;          // [T] tokens sorted by adapter, then tokens without adapter; nullptr = identity
+    const int32_t* token_adapter;  // [T]
+    const int32_t* rank;
+    const int32_t* extra_ptr;      // [token tiles + 1]
+    const int32_t* extra;          // adapter | rank block << 24
+    const bf16_t* vb;              // [T][2][R]: v_hi, v_lo
+    int R;
+    const bf16_t* const* Bt_ptrs;
+};
+
+// KTAIL: K is not a multiple of 64, the last K stage's chunks beyond K are zero-filled
 template <int WB, bool DELTA, bool KTAIL>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     int T, int K, int N, const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ Wt, int64_t ldw,
-    bf16_t* __restrict__ y, int64_t ldy, int tiles_n, int tiles_t,
-    const int32_t* __restrict__ token_adapter, const int32_t* __restrict__ rank,
-    const float* __restrict__ v, lora_vspec vsp, const bf16_t* const* __restrict__ Bt_ptrs)
+    bf16_t* __restrict__ y, int64_t ldy, int tiles_n, int tiles_t, gemm_delta_args da)
 {
     constexpr int BM = 64 * WB;            // features per workgroup tile
     constexpr int BT = 64 * WB;            // tokens per workgroup tile
     constexpr int NLD = (BM * 8) / 256;    // 16-byte chunks of W (and of x) per thread and stage
-    const int R = vsp.R;
     uint4* lds_w0 = gemm_lds;                       // [2][BM * 8]
     uint4* lds_x0 = gemm_lds + 2 * BM * 8;          // [2][BT * 8]
+    // DELTA: the tile's adapter stages {adapter, rank, Bt pointer} are fetched once, up front, into LDS
+    uint4* lds_meta = gemm_lds + 4 * BM * 8;        // [META_MAX]
+    // DELTA: token and adapter of the rows this thread stages, parked in LDS so that they hold no
+    // registers during the K stages: [NLD][256] int2
+    int2* lds_rows = reinterpret_cast<int2*>(lds_meta + META_MAX);
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
     // run of tiles (so its L2 sees neighbouring tiles), walking token tiles
@@ -89,8 +110,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = (wave & 1) * (32 * WB), wt = (wave >> 1) * (32 * WB);   // wavefront tile origin
+    const int c_lane8 = (tid & 7) * 8;                           // this thread's k offset inside a stage
 
-    // global -> register staging
+    // global -> register staging: the rows this thread fetches in every stage
     const bf16_t* gw[NLD];
     const bf16_t* gx[NLD];
     int slot[NLD], slot_w[NLD];
@@ -98,23 +120,15 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     for (int i = 0; i < NLD; ++i) {
         const int q = tid + i * 256, row = q >> 3, c = q & 7;
         int nr = n0 + row; if (nr >= N) nr = N - 1;
-        int tr = t0 + row; if (tr >= T) tr = T - 1;
+        int pos = t0 + row;
+        const bool pos_ok = pos < T;
+        if (!pos_ok) pos = T - 1;
+        const int tok = DELTA ? da.order[pos] : pos;
         gw[i] = Wt + (int64_t)nr * ldw + c * 8;
-        gx[i] = x + (int64_t)tr * ldx + c * 8;
+        gx[i] = x + (int64_t)tok * ldx + c * 8;
         slot[i] = lds_slot(row, c);
         slot_w[i] = lds_slot_w(row, c);
-    }
-    const int c_lane8 = (tid & 7) * 8;                           // this thread's k offset inside a stage
-
-    // adapter of this lane's token in each of its WB column blocks; fetched now, used in the epilogue
-    int my_adapter[WB];
-#pragma unroll
-    for (int b = 0; b < WB; ++b) {
-        my_adapter[b] = -1;
-        if constexpr (DELTA) {
-            const int t = t0 + wt + b * 32 + (lane & 31);
-            if (t < T) my_adapter[b] = token_adapter[t];
-        }
+        if constexpr (DELTA) lds_rows[i * 256 + tid] = make_int2(tok, pos_ok ? da.token_adapter[tok] : -1);
     }
 
     floatx16 acc[WB][WB];
@@ -130,15 +144,63 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     // feature of MFMA row l32 = 8q + 4hh + p  ->  16 hh + 4 q + p
     const int frow = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
 
-    const int stages = (K + BK - 1) / BK;
+    const int stages_k = (K + BK - 1) / BK;
+    int extra_base = 0, n_extra = 0, stages = stages_k;
+    if constexpr (DELTA) {
+        extra_base = da.extra_ptr[tile_t];
+        n_extra = da.extra_ptr[tile_t + 1] - extra_base;
+        stages += 2 * n_extra;
+        for (int e = tid; e < n_extra && e < META_MAX; e += 256) {
+            const int packed = da.extra[extra_base + e];
+            const int a_id = packed & 0xffffff;
+            const uint64_t bt = reinterpret_cast<uint64_t>(da.Bt_ptrs[a_id]);
+            lds_meta[e] = uint4{(uint32_t)packed, (uint32_t)da.rank[a_id], (uint32_t)bt, (uint32_t)(bt >> 32)};
+        }
+    }
+    bool skip[WB];                                               // column blocks without a token of the stage's adapter
+#pragma unroll
+    for (int b = 0; b < WB; ++b) skip[b] = false;
     uint4 rw[NLD], rx[NLD];
-    auto load_stage = [&](int s) {
+    auto load_k_stage = [&](int s) {
         const int k = s * BK;
         const bool in = !KTAIL || k + c_lane8 < K;               // K % 8 == 0: chunk is whole or absent
+        // same issue order as in the steady loop: all W chunks, then all x chunks
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            rw[i] = in ? *reinterpret_cast<const uint4*>(gw[i] + k) : uint4{0, 0, 0, 0};
-            rx[i] = in ? *reinterpret_cast<const uint4*>(gx[i] + k) : uint4{0, 0, 0, 0};
+        for (int i = 0; i < NLD; ++i) rw[i] = in ? *reinterpret_cast<const uint4*>(gw[i] + k) : uint4{0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) rx[i] = in ? *reinterpret_cast<const uint4*>(gx[i] + k) : uint4{0, 0, 0, 0};
+    };
+    auto load_stage = [&](int s) {
+        if (!DELTA || s < stages_k) {
+            load_k_stage(s);
+        } else {
+            // adapter stage: Bt_a[feature rows, 64 ranks] against v_hi or v_lo of the adapter's tokens
+            const int e = (s - stages_k) >> 1, part = (s - stages_k) & 1;
+            int packed, r;
+            const bf16_t* Bt;
+            if (e < META_MAX) {
+                const uint4 m = lds_meta[e];
+                packed = (int)m.x;
+                r = (int)m.y;
+                Bt = reinterpret_cast<const bf16_t*>((uint64_t)m.z | ((uint64_t)m.w << 32));
+            } else {
+                packed = da.extra[extra_base + e];
+                r = da.rank[packed & 0xffffff];
+                Bt = da.Bt_ptrs[packed & 0xffffff];
+            }
+            const int a_id = packed & 0xffffff;
+            const int j = (packed >> 24) * 64 + c_lane8;
+            const bool in = j < r;                               // r % 8 == 0
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                int nr = n0 + ((tid + i * 256) >> 3);
+                if (nr >= N) nr = N - 1;
+                const int2 ta = lds_rows[i * 256 + tid];         // (token, its adapter)
+                rw[i] = in ? *reinterpret_cast<const uint4*>(Bt + (int64_t)nr * r + j) : uint4{0, 0, 0, 0};
+                rx[i] = (in && ta.y == a_id)
+                            ? *reinterpret_cast<const uint4*>(da.vb + ((int64_t)ta.x * 2 + part) * da.R + j)
+                            : uint4{0, 0, 0, 0};
+            }
         }
     };
     auto store_stage = [&](int buf) {
@@ -150,7 +212,6 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
             lx[slot[i]] = rx[i];
         }
     };
-
     auto read_ops = [&](const uint4* lw, const uint4* lx, int ks, op16 (&wa)[WB], op16 (&xb)[WB]) {
         const int c = ks * 2 + h;
 #pragma unroll
@@ -160,10 +221,26 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     };
     auto mma = [&](const op16 (&wa)[WB], const op16 (&xb)[WB]) {
 #pragma unroll
-        for (int a = 0; a < WB; ++a)
+        for (int b = 0; b < WB; ++b) {
+            if (DELTA && skip[b]) continue;                      // wavefront-uniform
 #pragma unroll
-            for (int b = 0; b < WB; ++b)
+            for (int a = 0; a < WB; ++a)
                 acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a].v, xb[b].v, acc[a][b], 0, 0, 0);
+        }
+    };
+    // an adapter stage only concerns the column blocks that hold one of the adapter's tokens
+    auto set_skip = [&](int stage) {
+        if constexpr (DELTA) {
+            if (stage < stages_k) return;
+            const int e = (stage - stages_k) >> 1;
+            const int a_id = (e < META_MAX ? (int)lds_meta[e].x : da.extra[extra_base + e]) & 0xffffff;
+#pragma unroll
+            for (int b = 0; b < WB; ++b) {
+                // row wt + 32 b + l32 of the tile is staged by thread (row * 8) & 255 as its chunk slot (row * 8) >> 8
+                const int q = (wt + b * 32 + (lane & 31)) * 8;
+                skip[b] = __ballot(lds_rows[(q >> 8) * 256 + (q & 255)].y == a_id) == 0;
+            }
+        }
     };
 
     // Software pipeline.  Global loads run two stages ahead (registers), LDS is double
@@ -171,17 +248,27 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     // work on k-step ks the LDS reads of ks+1 are in flight, and the barrier between
     // stages sits before the last k-step so that its MFMAs cover the first reads of the
     // next stage.
-    load_stage(0);
-    store_stage(0);
-    if (stages > 1) load_stage(1);
-    __syncthreads();
     op16 waA[WB], xbA[WB], waB[WB], xbB[WB];
-    read_ops(lds_w0, lds_x0, 0, waA, xbA);
     int s = 0;
-    if constexpr (WB == 4 && !KTAIL) {
-        // Steady state, written out so that every MFMA is followed by exactly one memory
-        // operation (the scheduler is pinned to that order): the 64 MFMAs of a stage carry
-        // its 32 LDS operand reads, the 16 LDS writes of the next stage and the 16 global
+    const bool steady = WB == 4 && !KTAIL && stages_k >= 3;
+    if (!steady) {
+        load_stage(0);
+        store_stage(0);
+        if (stages > 1) load_stage(1);
+        __syncthreads();
+        read_ops(lds_w0, lds_x0, 0, waA, xbA);
+    }
+    if constexpr (WB == 4 && !KTAIL) if (steady) {
+        // (its own straight-line prologue: were the steady loop reachable through the branchy general
+        // loader, the compiler would wait for all outstanding loads at the top of every iteration)
+        load_k_stage(0);
+        store_stage(0);
+        load_k_stage(1);
+        __syncthreads();
+        read_ops(lds_w0, lds_x0, 0, waA, xbA);
+        // Steady state over the K stages, written out so that every MFMA is followed by exactly
+        // one memory operation (the scheduler is pinned to that order): the 64 MFMAs of a stage
+        // carry its 32 LDS operand reads, the 16 LDS writes of the next stage and the 16 global
         // loads of the stage after that, and the matrix cores never wait for a block of them.
         auto one_read = [&](const uint4* lw, const uint4* lx, int ks, int i, op16 (&wa)[WB], op16 (&xb)[WB]) {
             const int c = ks * 2 + h;
@@ -191,7 +278,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
 #define MMA1(WA, XB, IDX) \
         acc[(IDX) >> 2][(IDX) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WA[(IDX) >> 2].v, XB[(IDX) & 3].v, acc[(IDX) >> 2][(IDX) & 3], 0, 0, 0)
 #define PIN(MASK) do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(MASK, 1, 0); } while (0)
-        for (; s + 2 < stages; ++s) {
+        for (; s + 2 < stages_k; ++s) {
             const int buf = s & 1;
             const uint4* lw = lds_w0 + buf * BM * 8;
             const uint4* lx = lds_x0 + buf * BT * 8;
@@ -223,7 +310,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
 #undef MMA1
 #undef PIN
     }
+    // the last K stages and the adapter stages (and everything, for the small tile / K tail builds)
     for (; s < stages; ++s) {
+        set_skip(s);
         const int buf = s & 1;
         const uint4* lw = lds_w0 + buf * BM * 8;
         const uint4* lx = lds_x0 + buf * BT * 8;
@@ -242,72 +331,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
         mma(waB, xbB);
     }
 
-    // ---- epilogue: adapter delta, rounding, store -------------------------
+    // ---- epilogue: one rounding, store (rows go back to their tokens) ------
 #pragma unroll
     for (int b = 0; b < WB; ++b) {
-        const int t = t0 + wt + b * 32 + l32;                    // this lane's token in column block b
-        const bool t_ok = t < T;
-        if constexpr (DELTA) {
-            const int my_a = my_adapter[b];
-            // adapters present in this 32-token column block, one pass each; v is masked to the
-            // pass's tokens, so other tokens of the block receive exactly zero from it
-            unsigned long long todo = __ballot(my_a >= 0) & 0xffffffffull;   // lanes 0..31 and 32..63 hold the same tokens
-            while (todo) {
-                const int leader = __ffsll((long long)todo) - 1;
-                const int a_id = __shfl(my_a, leader, 64);
-                const unsigned long long same = __ballot(my_a == a_id) & 0xffffffffull;
-                todo &= ~same;
-                const int r = rank[a_id];
-                const bf16_t* Bt = Bt_ptrs[a_id];
-                const bool mine = my_a == a_id;
-                constexpr int JS = 4;                            // k-steps of 16 whose loads go out together
-                for (int j0 = 0; j0 < r; j0 += 16 * JS) {
-                    float4 va[JS][2];
-                    uint4 bo[JS][WB];
-#pragma unroll
-                    for (int u = 0; u < JS; ++u) {
-                        const int j = j0 + 16 * u + 8 * h;
-                        const bool ok = j < r;
-                        if (mine && ok) {
-                            const float* vq = v + (int64_t)t * R + j;
-                            va[u][0] = *reinterpret_cast<const float4*>(vq);
-                            va[u][1] = *reinterpret_cast<const float4*>(vq + 4);
-                        } else {
-                            va[u][0] = make_float4(0.f, 0.f, 0.f, 0.f);
-                            va[u][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-                        }
-#pragma unroll
-                        for (int a = 0; a < WB; ++a) {
-                            const int n = n0 + wn + a * 32 + frow;
-                            bo[u][a] = (n < N && ok) ? *reinterpret_cast<const uint4*>(Bt + (int64_t)n * r + j) : uint4{0, 0, 0, 0};
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < JS; ++u) {
-                        const int j = j0 + 16 * u + 8 * h;
-                        float f[8] = {va[u][0].x, va[u][0].y, va[u][0].z, va[u][0].w, va[u][1].x, va[u][1].y, va[u][1].z, va[u][1].w};
-                        if (mine && j < r) {
-                            for (int q = 1; q < vsp.P; ++q) {      // v = sum of its K parts (plans of small tiles only)
-                                const float* vq = v + q * vsp.part + (int64_t)t * R + j;
-                                const float4 q0 = *reinterpret_cast<const float4*>(vq);
-                                const float4 q1 = *reinterpret_cast<const float4*>(vq + 4);
-                                f[0] += q0.x; f[1] += q0.y; f[2] += q0.z; f[3] += q0.w; f[4] += q1.x; f[5] += q1.y; f[6] += q1.z; f[7] += q1.w;
-                            }
-                        }
-                        op16 vhi, vlo;
-                        split_bf16(f, vhi, vlo);
-#pragma unroll
-                        for (int a = 0; a < WB; ++a) {
-                            op16 bop;
-                            bop.u = bo[u][a];
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop.v, vhi.v, acc[a][b], 0, 0, 0);
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop.v, vlo.v, acc[a][b], 0, 0, 0);
-                        }
-                    }
-                }
-            }
-        }
-        if (!t_ok) continue;
+        const int pos = t0 + wt + b * 32 + l32;                  // this lane's row of the order in column block b
+        if (pos >= T) continue;
+        const int t = DELTA ? da.order[pos] : pos;
 #pragma unroll
         for (int a = 0; a < WB; ++a) {
             const int n = n0 + wn + a * 32 + 16 * h;             // first of this lane's 16 features
@@ -329,14 +358,30 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     }
 }
 
+// v (sum of its K parts, fp32) -> two bf16 terms hi + lo, rows [t][0][R] and [t][1][R] of vb
+__global__ __launch_bounds__(64) void v_split_kernel(
+    const int32_t* __restrict__ perm, const int32_t* __restrict__ token_adapter, const int32_t* __restrict__ rank,
+    const float* __restrict__ v, lora_vspec vsp, bf16_t* __restrict__ vb)
+{
+    const int t = perm[blockIdx.x];
+    const int r = rank[token_adapter[t]];
+    for (int j = threadIdx.x; j < r; j += 64) {
+        float f = v[(int64_t)t * vsp.R + j];
+        for (int q = 1; q < vsp.P; ++q) f += v[q * vsp.part + (int64_t)t * vsp.R + j];
+        const bf16_t hi = f32_to_bf16(f);
+        vb[(int64_t)t * 2 * vsp.R + j] = hi;
+        vb[(int64_t)t * 2 * vsp.R + vsp.R + j] = f32_to_bf16(f - bf16_to_f32(hi));
+    }
+}
+
 template <int WB, bool DELTA, bool KTAIL>
 hipError_t launch_one(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx, const void* Wt, int64_t ldw,
-                      void* y, int64_t ldy, const int32_t* token_adapter, const int32_t* rank, const float* v,
-                      lora_vspec vsp, const void* const* Bt, hipStream_t stream)
+                      void* y, int64_t ldy, const gemm_delta_args& da, hipStream_t stream)
 {
     constexpr int BM = 64 * WB;
     const int tiles_n = (N + BM - 1) / BM, tiles_t = (T + BM - 1) / BM;
-    const size_t lds_bytes = (size_t)2 * 2 * BM * 8 * sizeof(uint4);
+    const size_t lds_bytes = (size_t)2 * 2 * BM * 8 * sizeof(uint4) +
+                             (DELTA ? META_MAX * sizeof(uint4) + (size_t)(BM * 8 / 256) * 256 * sizeof(int2) : 0);
     static bool attr_set = false;                 // dynamic LDS above 64 KB has to be allowed once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<WB, DELTA, KTAIL>),
@@ -346,7 +391,7 @@ hipError_t launch_one(int32_t T, int32_t K, int32_t N, const void* x, int64_t ld
     }
     LORA_LAUNCH(DELTA ? LORA_K_GEMM_TILED_DELTA : LORA_K_GEMM_TILED, (gemm_tiled_kernel<WB, DELTA, KTAIL>),
                 dim3(tiles_n * tiles_t), dim3(256), lds_bytes, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
-                (bf16_t*)y, ldy, tiles_n, tiles_t, token_adapter, rank, v, vsp, (const bf16_t* const*)Bt);
+                (bf16_t*)y, ldy, tiles_n, tiles_t, da);
     return hipGetLastError();
 }
 
@@ -363,20 +408,26 @@ bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const 
     return tiles < (1ll << 31);
 }
 
+// p != nullptr: fold the adapter delta in; v holds the shrink's output and vb (room for T*2*R bf16) receives its split
 hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx,
                              const void* Wt, int64_t ldw, void* y, int64_t ldy,
-                             const lora_plan* p, const lora_dev_tables* d, const float* v,
+                             const lora_plan* p, const lora_dev_tables* d, const float* v, void* vb,
                              const void* const* Bt, hipStream_t stream)
 {
     // 256 x 256 tiles once there are enough of them to fill the 256 compute units
     const bool big = (int64_t)((N + 255) / 256) * ((T + 255) / 256) >= 192;
     const bool delta = p && !p->perm.empty();
-    const int32_t* ta = delta ? d->token_adapter : nullptr;
-    const int32_t* rk = delta ? d->rank : nullptr;
-    const lora_vspec vsp = delta ? lora_vspec_of(p) : lora_vspec{0, 1, 0};
+    gemm_delta_args da{};
+    if (delta) {
+        LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)p->perm.size()), dim3(64), 0, stream,
+                    d->perm, d->token_adapter, d->rank, v, lora_vspec_of(p), (bf16_t*)vb);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        da = gemm_delta_args{d->order, d->token_adapter, d->rank, big ? d->extra_ptr256 : d->extra_ptr128,
+                             big ? d->extra256 : d->extra128, (const bf16_t*)vb, p->R, (const bf16_t* const*)Bt};
+    }
     const bool ktail = (K % BK) != 0;
-#define GEMM_DISPATCH(WB_, D_, KT_) \
-    launch_one<WB_, D_, KT_>(T, K, N, x, ldx, Wt, ldw, y, ldy, ta, rk, v, vsp, Bt, stream)
+#define GEMM_DISPATCH(WB_, D_, KT_) launch_one<WB_, D_, KT_>(T, K, N, x, ldx, Wt, ldw, y, ldy, da, stream)
     if (big) {
         if (delta) return ktail ? GEMM_DISPATCH(4, true, true) : GEMM_DISPATCH(4, true, false);
         return ktail ? GEMM_DISPATCH(4, false, true) : GEMM_DISPATCH(4, false, false);

@@ -31,6 +31,9 @@ struct lora_plan {
     std::vector<int32_t> token_adapter, perm, group_adapter, group_offset, rank;
     std::vector<float> scale;
     std::vector<lora_tile> shrink_tiles, expand_tiles;
+    // fused GEMM: row order (tokens sorted by adapter, then tokens without adapter) and, per token tile of 128
+    // or 256 rows of that order, the (adapter, 64-wide rank block) pairs present: packed adapter | block << 24
+    std::vector<int32_t> order, extra_ptr128, extra128, extra_ptr256, extra256;
     bool tiled_layout_ok = false;  // K and all active ranks multiples of 8
 
     // device mirror (one allocation), valid when d_buf != nullptr
@@ -44,6 +47,11 @@ struct lora_plan {
     float* d_scale = nullptr;
     lora_tile* d_shrink_tiles = nullptr;
     lora_tile* d_expand_tiles = nullptr;
+    int32_t* d_order = nullptr;
+    int32_t* d_extra_ptr128 = nullptr;
+    int32_t* d_extra128 = nullptr;
+    int32_t* d_extra_ptr256 = nullptr;
+    int32_t* d_extra256 = nullptr;
     void* d_sync = nullptr;           // hand-off counters, 128 bytes per adapter group (only when fused_ok)
 };
 

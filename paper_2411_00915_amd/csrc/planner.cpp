@@ -192,6 +192,35 @@ static void build_tiles(lora_plan* p)
                      [&](const lora_tile& x, const lora_tile& y) { return weight(x) > weight(y); });
 }
 
+// Tables of the fused GEMM: it walks the tokens in adapter-sorted order, so a tile of rows holds few
+// adapters, and folds each adapter's delta in as extra k-stages (v_hi, v_lo against Bt_a).
+static void build_gemm_tables(lora_plan* p)
+{
+    p->order = p->perm;
+    p->order.reserve((size_t)p->T);
+    for (int32_t t = 0; t < p->T; ++t)
+        if (p->token_adapter[t] < 0) p->order.push_back(t);
+    const int32_t n_active = (int32_t)p->perm.size();
+    const int G = (int)p->group_adapter.size();
+    for (int h = 0; h < 2; ++h) {
+        const int32_t rows = h == 0 ? 128 : 256;
+        std::vector<int32_t>& ptr = h == 0 ? p->extra_ptr128 : p->extra_ptr256;
+        std::vector<int32_t>& lst = h == 0 ? p->extra128 : p->extra256;
+        const int32_t tiles = (p->T + rows - 1) / rows;
+        ptr.assign(1, 0);
+        int g = 0;
+        for (int32_t tile = 0; tile < tiles; ++tile) {
+            const int32_t p0 = tile * rows, p1 = std::min(p0 + rows, n_active);
+            while (g < G && p->group_offset[g + 1] <= p0) ++g;
+            for (int gg = g; gg < G && p->group_offset[gg] < p1; ++gg) {
+                const int32_t a = p->group_adapter[gg];
+                for (int32_t jb = 0; jb * 64 < p->rank[a]; ++jb) lst.push_back(a | (jb << 24));
+            }
+            ptr.push_back((int32_t)lst.size());
+        }
+    }
+}
+
 extern "C" lora_status lora_plan_create(const lora_batch_desc* d, lora_plan** out)
 {
     if (!d || !out) return LORA_ERR_INVALID_ARG;
@@ -248,6 +277,7 @@ extern "C" lora_status lora_plan_create(const lora_batch_desc* d, lora_plan** ou
         else
             p->family = (n_active >= g_lora_tuning.tiled_min_tokens) ? LORA_VARIANT_TILED : LORA_VARIANT_GENERAL;
         if (p->family == LORA_VARIANT_TILED) build_tiles(p);
+        if (p->tiled_layout_ok && p->n_a < (1 << 24)) build_gemm_tables(p);
     } catch (const std::bad_alloc&) {
         delete p;
         return LORA_ERR_NOMEM;
@@ -263,7 +293,9 @@ extern "C" lora_status lora_plan_query(const lora_plan* p, int32_t* v_row_stride
     const size_t vb = (size_t)p->v_parts * (size_t)p->T * (size_t)p->R * sizeof(float);
     if (v_row_stride) *v_row_stride = p->R;
     if (v_bytes) *v_bytes = vb;
-    if (fused_workspace_bytes) *fused_workspace_bytes = (vb + 255) / 256 * 256;
+    // workspace of the fused call: v (all parts), then its bf16 split [T][2][R]
+    if (fused_workspace_bytes)
+        *fused_workspace_bytes = (vb + 255) / 256 * 256 + ((size_t)p->T * 2 * p->R * 2 + 255) / 256 * 256;
     return LORA_OK;
 }
 

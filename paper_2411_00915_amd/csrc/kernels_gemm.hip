@@ -8,9 +8,10 @@
 //
 // The delta enters as extra k-stages of the same pipeline.  The kernel walks
 // the tokens in adapter-sorted order, so a tile of rows holds few adapters; for
-// each (adapter a, 64-wide rank block) present in a row tile it runs two more
-// stages whose "W tile" is Bt_a[features, ranks] and whose "x tile" is v_hi
-// resp. v_lo (v split into two bf16 terms, rows of other adapters zero).  Their
+// each adapter a present in a row tile it runs ceil(2 r_a / 64) more stages
+// whose "W tile" is Bt_a[features, ranks] and whose "x tile" is the matching 64
+// columns of [v_hi | v_lo] (v split into two bf16 terms, rows of other adapters
+// zero; Bt_a is simply addressed twice).  Their
 // loads are prefetched like any other stage's: nothing is exposed in an epilogue.
 //
 // x [T,K] and Wt [N,K] are both contraction-index-fastest, so tiles go
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     if constexpr (DELTA) {
         extra_base = da.extra_ptr[tile_t];
         n_extra = da.extra_ptr[tile_t + 1] - extra_base;
-        stages += 2 * n_extra;
+        stages += n_extra;
         for (int e = tid; e < n_extra && e < META_MAX; e += 256) {
             const int packed = da.extra[extra_base + e];
             const int a_id = packed & 0xffffff;
@@ -174,8 +175,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
         if (!DELTA || s < stages_k) {
             load_k_stage(s);
         } else {
-            // adapter stage: Bt_a[feature rows, 64 ranks] against v_hi or v_lo of the adapter's tokens
-            const int e = (s - stages_k) >> 1, part = (s - stages_k) & 1;
+            // adapter stage: Bt_a[feature rows, ranks] against 64 columns of [v_hi | v_lo] of the adapter's tokens
+            const int e = s - stages_k;
             int packed, r;
             const bf16_t* Bt;
             if (e < META_MAX) {
@@ -189,8 +190,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
                 Bt = da.Bt_ptrs[packed & 0xffffff];
             }
             const int a_id = packed & 0xffffff;
-            const int j = (packed >> 24) * 64 + c_lane8;
-            const bool in = j < r;                               // r % 8 == 0
+            // column of the adapter's [v_hi | v_lo] concatenation; r % 8 == 0, so a chunk lies in one half
+            const int col = (packed >> 24) * 64 + c_lane8;
+            const bool in = col < 2 * r;
+            const int part = col >= r ? 1 : 0;
+            const int j = col - part * r;
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
                 int nr = n0 + ((tid + i * 256) >> 3);
@@ -232,7 +236,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     auto set_skip = [&](int stage) {
         if constexpr (DELTA) {
             if (stage < stages_k) return;
-            const int e = (stage - stages_k) >> 1;
+            const int e = stage - stages_k;
             const int a_id = (e < META_MAX ? (int)lds_meta[e].x : da.extra[extra_base + e]) & 0xffffff;
 #pragma unroll
             for (int b = 0; b < WB; ++b) {

@@ -32,7 +32,8 @@ struct lora_plan {
     std::vector<float> scale;
     std::vector<lora_tile> shrink_tiles, expand_tiles;
     // fused GEMM: row order (tokens sorted by adapter, then tokens without adapter) and, per token tile of 128
-    // or 256 rows of that order, the (adapter, 64-wide rank block) pairs present: packed adapter | block << 24
+    // or 256 rows of that order, the adapter stages present: packed adapter | (64-column block of the
+    // adapter's [v_hi | v_lo] concatenation) << 24
     std::vector<int32_t> order, extra_ptr128, extra128, extra_ptr256, extra256;
     bool tiled_layout_ok = false;  // K and all active ranks multiples of 8
 

@@ -214,7 +214,8 @@ static void build_gemm_tables(lora_plan* p)
             while (g < G && p->group_offset[g + 1] <= p0) ++g;
             for (int gg = g; gg < G && p->group_offset[gg] < p1; ++gg) {
                 const int32_t a = p->group_adapter[gg];
-                for (int32_t jb = 0; jb * 64 < p->rank[a]; ++jb) lst.push_back(a | (jb << 24));
+                // one stage per 64 columns of the adapter's [v_hi | v_lo] concatenation (2 r columns)
+                for (int32_t jb = 0; jb * 64 < 2 * p->rank[a]; ++jb) lst.push_back(a | (jb << 24));
             }
             ptr.push_back((int32_t)lst.size());
         }

@@ -27,7 +27,7 @@ bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p
 
 struct table_layout {
     size_t perm, token_adapter, rank, scale, shrink_tiles, expand_tiles, sync, sync_bytes, total;
-    size_t order, extra_ptr128, extra128, extra_ptr256, extra256;
+    size_t order, extra_ptr128, extra128, extra_ptr256, extra256, zeros;
 };
 
 table_layout layout_of(const lora_plan* p)
@@ -46,6 +46,7 @@ table_layout layout_of(const lora_plan* p)
     L.extra128 = take(p->extra128.size() * sizeof(int32_t));
     L.extra_ptr256 = take(p->extra_ptr256.size() * sizeof(int32_t));
     L.extra256 = take(p->extra256.size() * sizeof(int32_t));
+    L.zeros = take(256);
     L.sync_bytes = p->fused_ok ? p->group_adapter.size() * 128 : 0;
     L.sync = take(L.sync_bytes);
     L.total = std::max<size_t>(off, 256);
@@ -96,6 +97,7 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     put(L.extra128, p->extra128.data(), p->extra128.size() * sizeof(int32_t));
     put(L.extra_ptr256, p->extra_ptr256.data(), p->extra_ptr256.size() * sizeof(int32_t));
     put(L.extra256, p->extra256.data(), p->extra256.size() * sizeof(int32_t));
+    std::memset(h + L.zeros, 0, 256);
     std::memset(h + L.sync, 0, L.sync_bytes);                    // hand-off counters start at zero
     if (hipMemcpyAsync(dbuf, hbuf, L.total, hipMemcpyHostToDevice, stream) != hipSuccess) {
         (void)hipGetLastError();
@@ -115,6 +117,7 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     p->d_shrink_tiles = reinterpret_cast<lora_tile*>(d + L.shrink_tiles);
     p->d_expand_tiles = reinterpret_cast<lora_tile*>(d + L.expand_tiles);
     p->d_sync = d + L.sync;
+    p->d_zeros = d + L.zeros;
     p->d_order = reinterpret_cast<int32_t*>(d + L.order);
     p->d_extra_ptr128 = reinterpret_cast<int32_t*>(d + L.extra_ptr128);
     p->d_extra128 = reinterpret_cast<int32_t*>(d + L.extra128);
@@ -126,7 +129,7 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
 lora_dev_tables tables_of(const lora_plan* p)
 {
     return lora_dev_tables{p->d_perm, p->d_token_adapter, p->d_rank, p->d_scale, p->d_shrink_tiles, p->d_expand_tiles,
-                           p->d_sync, p->d_order, p->d_extra_ptr128, p->d_extra128, p->d_extra_ptr256, p->d_extra256};
+                           p->d_sync, p->d_order, p->d_extra_ptr128, p->d_extra128, p->d_extra_ptr256, p->d_extra256, p->d_zeros};
 }
 
 size_t elem_bytes(int32_t dtype) { return dtype == LORA_F32 ? 4 : 2; }

@@ -30,6 +30,7 @@ struct lora_dev_tables {
     const int32_t* extra128;
     const int32_t* extra_ptr256;
     const int32_t* extra256;
+    const void* zeros;             // 256 zero bytes
 };
 
 // general VALU family (any dtype, any alignment)

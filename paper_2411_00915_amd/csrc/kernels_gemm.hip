@@ -77,6 +77,7 @@ struct gemm_delta_args {
     const bf16_t* vb;              // [T][2][R]: v_hi, v_lo
     int R;
     const bf16_t* const* Bt_ptrs;
+    const bf16_t* zeros;           // 16 zero bytes: the source of chunks that are masked out
 };
 
 // KTAIL: K is not a multiple of 64, the last K stage's chunks beyond K are zero-filled
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     // next stage.
     op16 waA[WB], xbA[WB], waB[WB], xbB[WB];
     int s = 0;
-    const bool steady = WB == 4 && !KTAIL && stages_k >= 3;
+    const bool steady = WB == 4 && !KTAIL && stages_k >= 3 && n_extra <= META_MAX;
     if (!steady) {
         load_stage(0);
         store_stage(0);
@@ -265,12 +266,56 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     if constexpr (WB == 4 && !KTAIL) if (steady) {
         // (its own straight-line prologue: were the steady loop reachable through the branchy general
         // loader, the compiler would wait for all outstanding loads at the top of every iteration)
-        load_k_stage(0);
+        // Running source pointers of the stage to fetch next.  A K stage advances them by 64 elements; an
+        // adapter stage sets them afresh: W chunks to Bt_a[feature row, ranks], x chunks to the token's
+        // [v_hi | v_lo] columns, and every chunk that is masked out (beyond the rank, or a token of another
+        // adapter) to a block of zeros -- so all stages issue the same 16 unconditional loads.
+        const bf16_t* pw[NLD];
+        const bf16_t* px[NLD];
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) { pw[i] = gw[i]; px[i] = gx[i]; }
+        auto advance = [&](int next) {
+            if (!DELTA || next < stages_k) {
+#pragma unroll
+                for (int i = 0; i < NLD; ++i) { pw[i] += BK; px[i] += BK; }
+            } else if (next < stages) {
+                const uint4 m = lds_meta[next - stages_k];
+                const int a_id = (int)m.x & 0xffffff, r = (int)m.y;
+                const bf16_t* Bt = reinterpret_cast<const bf16_t*>((uint64_t)m.z | ((uint64_t)m.w << 32));
+                const int col = ((int)m.x >> 24) * 64 + c_lane8;
+                const bool in = col < 2 * r;
+                const int part = col >= r ? 1 : 0;
+                const int j = col - part * r;
+#pragma unroll
+                for (int i = 0; i < NLD; ++i) {
+                    int nr = n0 + ((tid + i * 256) >> 3);
+                    if (nr >= N) nr = N - 1;
+                    const int2 ta = lds_rows[i * 256 + tid];
+                    pw[i] = in ? Bt + (int64_t)nr * r + j : da.zeros;
+                    px[i] = (in && ta.y == a_id) ? da.vb + ((int64_t)ta.x * 2 + part) * da.R + j : da.zeros;
+                }
+            }
+        };
+        auto load_ptrs = [&]() {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) rw[i] = *reinterpret_cast<const uint4*>(pw[i]);
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) rx[i] = *reinterpret_cast<const uint4*>(px[i]);
+        };
+        __syncthreads();                                 // lds_meta / lds_rows are complete
+        // stages 0, 1 and 2 are K stages (stages_k >= 3): straight-line code up to the first loop (were it
+        // reachable through a branch with loads in flight, the compiler would wait for all of them at the
+        // top of every iteration instead of the oldest one)
+        load_ptrs();
         store_stage(0);
-        load_k_stage(1);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) { pw[i] += BK; px[i] += BK; }
+        load_ptrs();
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) { pw[i] += BK; px[i] += BK; }
         __syncthreads();
         read_ops(lds_w0, lds_x0, 0, waA, xbA);
-        // Steady state over the K stages, written out so that every MFMA is followed by exactly
+        // Steady state over all stages but the last two, written out so that every MFMA is followed by exactly
         // one memory operation (the scheduler is pinned to that order): the 64 MFMAs of a stage
         // carry its 32 LDS operand reads, the 16 LDS writes of the next stage and the 16 global
         // loads of the stage after that, and the matrix cores never wait for a block of them.
@@ -282,39 +327,40 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
 #define MMA1(WA, XB, IDX) \
         acc[(IDX) >> 2][(IDX) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WA[(IDX) >> 2].v, XB[(IDX) & 3].v, acc[(IDX) >> 2][(IDX) & 3], 0, 0, 0)
 #define PIN(MASK) do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(MASK, 1, 0); } while (0)
-        for (; s + 2 < stages_k; ++s) {
-            const int buf = s & 1;
-            const uint4* lw = lds_w0 + buf * BM * 8;
-            const uint4* lx = lds_x0 + buf * BT * 8;
-            uint4* lw_n = lds_w0 + (buf ^ 1) * BM * 8;
-            uint4* lx_n = lds_x0 + (buf ^ 1) * BT * 8;
-            const int k2 = (s + 2) * BK;
-            // k-step 0: reads of k-step 1, W chunks of stage s+1 into LDS
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, i); one_read(lw, lx, 1, i, waB, xbB); PIN(0x100); }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, 8 + i); lw_n[slot_w[i]] = rw[i]; PIN(0x200); }
-            // k-step 1: reads of k-step 2, x chunks of stage s+1 into LDS
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, i); one_read(lw, lx, 2, i, waA, xbA); PIN(0x100); }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, 8 + i); lx_n[slot[i]] = rx[i]; PIN(0x200); }
-            // k-step 2: reads of k-step 3, W chunks of stage s+2 from HBM
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, i); one_read(lw, lx, 3, i, waB, xbB); PIN(0x100); }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, 8 + i); rw[i] = *reinterpret_cast<const uint4*>(gw[i] + k2); PIN(0x020); }
-            __syncthreads();                             // stage s+1 is in LDS; nobody reads stage s any more
-            // k-step 3: reads of k-step 0 of stage s+1, x chunks of stage s+2 from HBM
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, i); one_read(lw_n, lx_n, 0, i, waA, xbA); PIN(0x100); }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, 8 + i); rx[i] = *reinterpret_cast<const uint4*>(gx[i] + k2); PIN(0x020); }
+        // the body of one stage; ADV_GENERAL: the pointer update after it may set up an adapter stage
+#define STAGE_BODY(ADV_GENERAL)                                                                                        \
+        {                                                                                                              \
+            const int buf = s & 1;                                                                                     \
+            const uint4* lw = lds_w0 + buf * BM * 8;                                                                   \
+            const uint4* lx = lds_x0 + buf * BT * 8;                                                                   \
+            uint4* lw_n = lds_w0 + (buf ^ 1) * BM * 8;                                                                 \
+            uint4* lx_n = lds_x0 + (buf ^ 1) * BT * 8;                                                                 \
+            /* k-step 0: reads of k-step 1, W chunks of stage s+1 into LDS */                                          \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, i); one_read(lw, lx, 1, i, waB, xbB); PIN(0x100); }       \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, 8 + i); lw_n[slot_w[i]] = rw[i]; PIN(0x200); }           \
+            /* k-step 1: reads of k-step 2, x chunks of stage s+1 into LDS */                                          \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, i); one_read(lw, lx, 2, i, waA, xbA); PIN(0x100); }       \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, 8 + i); lx_n[slot[i]] = rx[i]; PIN(0x200); }             \
+            /* k-step 2: reads of k-step 3, W chunks of stage s+2 from memory */                                       \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, i); one_read(lw, lx, 3, i, waB, xbB); PIN(0x100); }       \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) { MMA1(waA, xbA, 8 + i); rw[i] = *reinterpret_cast<const uint4*>(pw[i]); PIN(0x020); } \
+            __syncthreads(); /* stage s+1 is in LDS; nobody reads stage s any more */                                  \
+            /* k-step 3: reads of k-step 0 of stage s+1, x chunks of stage s+2 from memory */                          \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, i); one_read(lw_n, lx_n, 0, i, waA, xbA); PIN(0x100); }   \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) { MMA1(waB, xbB, 8 + i); rx[i] = *reinterpret_cast<const uint4*>(px[i]); PIN(0x020); } \
+            if (ADV_GENERAL) advance(s + 3);                                                                           \
+            else { _Pragma("unroll") for (int i = 0; i < NLD; ++i) { pw[i] += BK; px[i] += BK; } }                     \
         }
+        // K stages whose successors are K stages too: a loop without any branch in its body (a branch
+        // makes the compiler wait for all outstanding loads instead of the oldest one)
+        for (; s + 3 < stages_k; ++s) STAGE_BODY(false)
+        // the stages around and inside the adapter part
+        for (; s + 2 < stages; ++s) STAGE_BODY(true)
+#undef STAGE_BODY
 #undef MMA1
 #undef PIN
     }
-    // the last K stages and the adapter stages (and everything, for the small tile / K tail builds)
+    // the last two stages (and everything, for the small tile / K tail builds)
     for (; s < stages; ++s) {
         set_skip(s);
         const int buf = s & 1;
@@ -428,7 +474,8 @@ hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         da = gemm_delta_args{d->order, d->token_adapter, d->rank, big ? d->extra_ptr256 : d->extra_ptr128,
-                             big ? d->extra256 : d->extra128, (const bf16_t*)vb, p->R, (const bf16_t* const*)Bt};
+                             big ? d->extra256 : d->extra128, (const bf16_t*)vb, p->R, (const bf16_t* const*)Bt,
+                             (const bf16_t*)d->zeros};
     }
     const bool ktail = (K % BK) != 0;
 #define GEMM_DISPATCH(WB_, D_, KT_) launch_one<WB_, D_, KT_>(T, K, N, x, ldx, Wt, ldw, y, ldy, da, stream)

@@ -53,6 +53,7 @@ struct lora_plan {
     int32_t* d_extra128 = nullptr;
     int32_t* d_extra_ptr256 = nullptr;
     int32_t* d_extra256 = nullptr;
+    void* d_zeros = nullptr;          // 256 zero bytes (source of masked chunks in the fused GEMM)
     void* d_sync = nullptr;           // hand-off counters, 128 bytes per adapter group (only when fused_ok)
 };
 

@@ -193,30 +193,52 @@ static void build_tiles(lora_plan* p)
 }
 
 // Tables of the fused GEMM: it walks the tokens in adapter-sorted order, so a tile of rows holds few
-// adapters, and folds each adapter's delta in as extra k-stages (v_hi, v_lo against Bt_a).
+// adapters, and folds each adapter's delta in as extra k-stages (v_hi, v_lo against Bt_a).  The full
+// blocks of 256 sorted rows are then put heaviest first (most adapter stages): workgroups start in
+// index order, so the long tiles run early and the short ones fill the tail of the launch.
 static void build_gemm_tables(lora_plan* p)
 {
-    p->order = p->perm;
-    p->order.reserve((size_t)p->T);
+    std::vector<int32_t> sorted = p->perm;
+    sorted.reserve((size_t)p->T);
     for (int32_t t = 0; t < p->T; ++t)
-        if (p->token_adapter[t] < 0) p->order.push_back(t);
-    const int32_t n_active = (int32_t)p->perm.size();
-    const int G = (int)p->group_adapter.size();
+        if (p->token_adapter[t] < 0) sorted.push_back(t);
+
+    // adapter stages of the rows [p0, p1) of `rows`: one per 64 columns of [v_hi | v_lo] (2 r columns) and
+    // adapter; the rows of one adapter are adjacent
+    auto stages_of = [&](const std::vector<int32_t>& rows, int32_t p0, int32_t p1, std::vector<int32_t>* lst) {
+        int32_t n = 0, last = -1;
+        for (int32_t q = p0; q < p1; ++q) {
+            const int32_t a = p->token_adapter[rows[q]];
+            if (a < 0 || a == last) continue;
+            last = a;
+            for (int32_t jb = 0; jb * 64 < 2 * p->rank[a]; ++jb, ++n)
+                if (lst) lst->push_back(a | (jb << 24));
+        }
+        return n;
+    };
+
+    const int32_t full = p->T / 256;
+    std::vector<int32_t> weight((size_t)full), blocks((size_t)full);
+    for (int32_t b = 0; b < full; ++b) {
+        weight[b] = stages_of(sorted, b * 256, b * 256 + 256, nullptr);
+        blocks[b] = b;
+    }
+    std::stable_sort(blocks.begin(), blocks.end(), [&](int32_t x, int32_t y) { return weight[x] > weight[y]; });
+    p->order.resize((size_t)p->T);
+    for (int32_t b = 0; b < full; ++b)
+        std::copy(sorted.begin() + (size_t)blocks[b] * 256, sorted.begin() + (size_t)blocks[b] * 256 + 256,
+                  p->order.begin() + (size_t)b * 256);
+    std::copy(sorted.begin() + (size_t)full * 256, sorted.end(), p->order.begin() + (size_t)full * 256);
+
     for (int h = 0; h < 2; ++h) {
         const int32_t rows = h == 0 ? 128 : 256;
         std::vector<int32_t>& ptr = h == 0 ? p->extra_ptr128 : p->extra_ptr256;
         std::vector<int32_t>& lst = h == 0 ? p->extra128 : p->extra256;
         const int32_t tiles = (p->T + rows - 1) / rows;
         ptr.assign(1, 0);
-        int g = 0;
+        lst.clear();
         for (int32_t tile = 0; tile < tiles; ++tile) {
-            const int32_t p0 = tile * rows, p1 = std::min(p0 + rows, n_active);
-            while (g < G && p->group_offset[g + 1] <= p0) ++g;
-            for (int gg = g; gg < G && p->group_offset[gg] < p1; ++gg) {
-                const int32_t a = p->group_adapter[gg];
-                // one stage per 64 columns of the adapter's [v_hi | v_lo] concatenation (2 r columns)
-                for (int32_t jb = 0; jb * 64 < 2 * p->rank[a]; ++jb) lst.push_back(a | (jb << 24));
-            }
+            stages_of(p->order, tile * rows, std::min(tile * rows + rows, p->T), &lst);
             ptr.push_back((int32_t)lst.size());
         }
     }

@@ -263,7 +263,11 @@ const char* lora_status_str(lora_status s);
  * fused_delay (lora_delta's single launch: head start given to the shrink blocks'
  * loads, units of about 0.4 us, plus one), expand_wave_bytes_big (expand_wave_bytes
  * for adapter groups of at least expand_tb2_min_rows tokens), shrink_tb4_min_rows
- * (adapter groups with at least this many tokens use 64-token shrink tiles).
+ * (adapter groups with at least this many tokens use 64-token shrink tiles),
+ * shrink_stream_min_tokens (batches with at least this many adapter tokens, ranks
+ * <= 128 and K >= 1024 use the streaming shrink: tiles of up to 128 tokens over all
+ * rank rows, At shared through LDS), shrink_stream_wgs (the streaming shrink uses
+ * 64-token tiles when 128-token tiles would give fewer workgroups than this).
  * Entries <= 0 keep the current value; plans made
  * earlier are unaffected.  Host only.
  */

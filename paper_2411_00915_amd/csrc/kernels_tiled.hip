@@ -27,6 +27,18 @@ union op16 {            // one 16-byte MFMA operand
 };
 
 __device__ __forceinline__ uint4 ld16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+// the same for a pointer the compiler cannot trace back to a kernel argument (one fetched from a pointer
+// table): states that it points to global memory, so that the load is not a flat one
+__device__ __forceinline__ uint4 ld16_global(const bf16_t* p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+    const u32x4 r = *(const __attribute__((address_space(1))) u32x4*)(uintptr_t)p;
+    return uint4{r[0], r[1], r[2], r[3]};
+#else       // the host pass only parses device functions
+    return *reinterpret_cast<const uint4*>(p);
+#endif
+}
 
 __device__ __forceinline__ floatx4 mfma(const op16& a, const op16& b, floatx4 c)
 {
@@ -209,6 +221,182 @@ __global__ __launch_bounds__(512) void shrink_tiled_kernel(
 #undef SHRINK_CASE
 }
 
+// ---------------------------------------------------------------------------
+// Streaming shrink for prefill-sized batches.  One workgroup (8 wavefronts) per tile =
+// (16*NB tokens of one adapter, NB = 8/KW) x all of the adapter's rank rows x one K part.
+// x is private to a wavefront (its 16 tokens).  It is fetched two stages (2 x 128 k) ahead into registers
+// with loads that cover whole 128-byte lines (4 rows x 256 bytes per instruction: a CU's rate of line
+// requests is what bounds it, and the MFMA operand shape, 16 rows x 64 bytes, would use half of each
+// line per request), and is turned into MFMA operands through a 4 KB LDS patch that only this
+// wavefront touches (no workgroup barrier involved).  At_a is common to all wavefronts of the tile, so
+// every stage's slab At_a[:, 128 k] is fetched once per workgroup and shared through LDS (double
+// buffer, XOR swizzle: the 16 lanes of a ds_read_b128 phase hit 16 different 16-byte columns).  With
+// fewer than 8 token blocks the wavefronts also split each stage's 4 k-steps KW ways and add up in
+// LDS at the end.  No branch inside the stage loop: chunks outside the K part (or K) and padding rows
+// read a block of zeros.
+template <int JB, int KW>
+__device__ __forceinline__ void shrink_stream_tile(
+    const lora_tile tile, const int32_t* __restrict__ perm,
+    const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
+    float* __restrict__ v, lora_vspec vsp, const bf16_t* __restrict__ zeros, uint4* lds)
+{
+    constexpr int NB = 8 / KW;                    // token blocks of the tile
+    constexpr int UW = 4 / KW;                    // k-steps per stage and wavefront
+    constexpr int SLAB = JB * 16 * 16;            // 16-byte chunks of one stage's At slab: [16 JB rows][16]
+    constexpr int NLD = SLAB >= 512 ? SLAB / 512 : 1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int blk = wave % NB, kw = wave / NB;
+
+    // the token whose results this lane ends up with (MFMA column m)
+    const int row = blk * 16 + m;
+    const bool row_ok = row < tile.nrows;
+    const int tok = perm[tile.row0 + (row_ok ? row : 0)];
+
+    // x loads: the wavefront's span of a stage is 64 UW bytes per row = LPR lanes; instruction i
+    // fetches rows i*RPI .. i*RPI+RPI-1 of the block
+    constexpr int LPR = 4 * UW, RPI = 64 / LPR;
+    const int xl_row = lane / LPR, xl_c = lane % LPR;
+    const bf16_t* xsrc[UW];
+    int x_ok = 0;
+    uint4* xw = lds + 2 * SLAB + wave * (16 * LPR);          // this wavefront's patch: [16 rows][LPR], swizzled
+    int wslot[UW];
+#pragma unroll
+    for (int i = 0; i < UW; ++i) {
+        const int r16 = i * RPI + xl_row, r = blk * 16 + r16;
+        const bool ok = r < tile.nrows;
+        x_ok |= (int)ok << i;
+        xsrc[i] = x + (int64_t)perm[tile.row0 + (ok ? r : 0)] * ldx + (kw * LPR + xl_c) * 8;
+        wslot[i] = r16 * LPR + (xl_c ^ (r16 % LPR));
+    }
+
+    const int steps = (K + 31) >> 5;
+    const int kpart = (tile.shape >> 8) & 15, kparts = (tile.shape >> 12) & 15;
+    const int p_begin = (int)(((int64_t)steps * kpart) / kparts), p_end = (int)(((int64_t)steps * (kpart + 1)) / kparts);
+    const int k_begin = p_begin << 5, k_end = min(K, p_end << 5);
+    const int n_stages = (p_end - p_begin + 3) >> 2;
+
+    // At staging: chunk q of a slab = row q/16, 16-byte column q%16
+    const bf16_t* asrc[NLD];
+    int aslot[NLD], acol[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int q = (tid + i * 512) % SLAB, j = q >> 4, c = q & 15;
+        asrc[i] = At + (int64_t)(tile.c0 + (j < tile.cn ? j : 0)) * K + c * 8;
+        aslot[i] = j * 16 + (c ^ (j & 15));
+        acol[i] = c * 8;
+    }
+    auto load_a = [&](int s, uint4 (&ra)[NLD]) {
+        const int k0 = k_begin + s * 128;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) ra[i] = ld16_global(k0 + acol[i] < k_end ? asrc[i] + k0 : zeros);
+    };
+    auto load_x1 = [&](int s, int i) {
+        const int k0 = k_begin + s * 128;
+        return ld16_global((((x_ok >> i) & 1) && k0 + (kw * LPR + xl_c) * 8 < k_end) ? xsrc[i] + k0 : zeros);
+    };
+    auto store_a = [&](int buf, const uint4 (&ra)[NLD]) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) lds[buf * SLAB + aslot[i]] = ra[i];
+    };
+    floatx4 acc[JB];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) acc[jb] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // one stage: the stage's x goes through the wavefront's LDS patch (the registers are refilled at once
+    // with the same rows of stage s_next, so nearly all x registers are in flight all the time), then per
+    // k-step the LDS reads of x and of the slab, and the MFMAs
+    auto compute = [&](int buf, op16 (&xr)[UW], int s_next) {
+#pragma unroll
+        for (int i = 0; i < UW; ++i) xw[wslot[i]] = xr[i].u;
+#pragma unroll
+        for (int i = 0; i < UW; ++i) xr[i].u = load_x1(s_next, i);
+        __builtin_amdgcn_wave_barrier();         // the patch is exchanged between lanes of this wavefront only
+#pragma unroll
+        for (int i = 0; i < UW; ++i) {
+            op16 b, a[JB];
+            b.u = xw[m * LPR + ((4 * i + g) ^ (m % LPR))];
+            const int c = (kw * UW + i) * 4 + g;
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) a[jb].u = lds[buf * SLAB + (jb * 16 + m) * 16 + (c ^ m)];
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) acc[jb] = mfma(a[jb], b, acc[jb]);
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    uint4 ra0[NLD], ra1[NLD];
+    op16 xr0[UW], xr1[UW];
+    // the loads are issued in the order the stage loop keeps them in flight and consumes them, and the
+    // loop has no guard branch, so every wait in it can name exactly the loads it needs
+    load_a(0, ra0);
+#pragma unroll
+    for (int i = 0; i < UW; ++i) xr0[i].u = load_x1(0, i);
+    store_a(0, ra0);
+    load_a(1, ra0);
+#pragma unroll
+    for (int i = 0; i < UW; ++i) xr1[i].u = load_x1(1, i);
+    load_a(2, ra1);
+    __syncthreads();
+    // stage s computes from slab buffer s%2; the slab of stage s+1 (in registers since two stages ago)
+    // goes to the other buffer after the MFMAs, and the slab of stage s+3 is requested
+    int s = 0;
+    do {
+        compute(0, xr0, s + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        store_a(1, ra0);
+        load_a(s + 3, ra0);
+        __syncthreads();
+        compute(1, xr1, s + 3);        // past the last stage: zeros
+        __builtin_amdgcn_sched_barrier(0);
+        store_a(0, ra1);
+        load_a(s + 4, ra1);
+        __syncthreads();
+        s += 2;
+    } while (s < n_stages);
+
+    const float s_a = __int_as_float(tile.reserved1);
+    floatx4* red = reinterpret_cast<floatx4*>(lds);
+    if (KW > 1) {
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) red[(wave * JB + jb) * 64 + lane] = acc[jb];
+        __syncthreads();
+        if (kw != 0) return;
+#pragma unroll
+        for (int q = 1; q < KW; ++q)
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) acc[jb] += red[((blk + NB * q) * JB + jb) * 64 + lane];
+    }
+    if (!row_ok) return;
+    float* dst = v + kpart * vsp.part + (int64_t)tok * vsp.R + tile.c0 + 4 * g;
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+        if (jb * 16 + 4 * g < tile.cn)
+            *reinterpret_cast<float4*>(dst + jb * 16) =
+                make_float4(s_a * acc[jb][0], s_a * acc[jb][1], s_a * acc[jb][2], s_a * acc[jb][3]);
+}
+
+extern __shared__ uint4 shrink_stream_lds[];
+
+// JBMAX: the largest rank-block count among the plan's tiles (the kernel's register count is that
+// of its widest case, so plans without ranks above 64 get a leaner build)
+template <int JBMAX>
+__global__ __launch_bounds__(512) void shrink_stream_kernel(
+    const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm,
+    const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* const* __restrict__ At_ptrs, int K,
+    float* __restrict__ v, lora_vspec R, const bf16_t* __restrict__ zeros)
+{
+    const lora_tile tile = tiles[blockIdx.x];
+    const bf16_t* At = At_ptrs[tile.adapter];
+    const int nb = tile.shape & 15, jb = (tile.shape >> 4) & 15;
+#define STREAM_CASE(JB_, KW_) \
+    if (JB_ <= JBMAX && jb == JB_ && nb == 8 / KW_) { shrink_stream_tile<JB_, KW_>(tile, perm, x, ldx, At, K, v, R, zeros, shrink_stream_lds); return; }
+    STREAM_CASE(4, 1) STREAM_CASE(4, 2) STREAM_CASE(4, 4)
+    STREAM_CASE(2, 1) STREAM_CASE(2, 2) STREAM_CASE(2, 4)
+    STREAM_CASE(1, 1) STREAM_CASE(1, 2) STREAM_CASE(1, 4)
+    STREAM_CASE(8, 1) STREAM_CASE(8, 2) STREAM_CASE(8, 4)
+#undef STREAM_CASE
+}
+
 hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
                                const void* const* At, float* v, hipStream_t stream)
 {
@@ -216,6 +404,20 @@ hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, con
     if (n_tiles == 0) return hipSuccess;
     const int W = p->shrink_waves;
     const size_t lds_bytes = (size_t)W * p->shrink_max_blocks * 64 * sizeof(floatx4);   // <= 64 KB
+    if (p->shrink_stream) {
+        // two slabs of 16 JB rows x 256 bytes (the final cross-wavefront sum needs the same 8 JB KB), and a
+        // 4 KB patch per wavefront
+        const size_t stream_lds = (size_t)p->shrink_max_blocks * 8192 + 32768;
+#define STREAM_LAUNCH(JBMAX_)                                                                                          \
+    LORA_LAUNCH(LORA_K_SHRINK_STREAM, shrink_stream_kernel<JBMAX_>, dim3(n_tiles), dim3(512), stream_lds, stream,      \
+                d.shrink_tiles, d.perm, (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, lora_vspec_of(p),    \
+                (const bf16_t*)d.zeros)
+        if (p->shrink_max_blocks <= 2) STREAM_LAUNCH(2);
+        else if (p->shrink_max_blocks <= 4) STREAM_LAUNCH(4);
+        else STREAM_LAUNCH(8);
+#undef STREAM_LAUNCH
+        return hipGetLastError();
+    }
     if (p->shrink_small)
         LORA_LAUNCH(LORA_K_SHRINK_TILED, shrink_tiled_small_kernel, dim3(n_tiles), dim3(64 * W), lds_bytes, stream,
                     d.shrink_tiles, d.perm, d.scale, (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, lora_vspec_of(p));

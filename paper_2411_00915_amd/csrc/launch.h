@@ -18,6 +18,7 @@ enum lora_kernel_id {
     LORA_K_GEMM_TILED_DELTA,
     LORA_K_DELTA_FUSED,
     LORA_K_V_SPLIT,
+    LORA_K_SHRINK_STREAM,
     LORA_K_COUNT
 };
 

@@ -23,6 +23,7 @@ struct lora_plan {
     int32_t family = LORA_VARIANT_GENERAL;
     int32_t shrink_waves = 4;      // wavefronts per shrink workgroup (split the K range), 1..16
     bool shrink_small = false;     // every shrink tile is 16 tokens x <= 32 rank rows: small kernel build
+    bool shrink_stream = false;    // shrink tiles are those of the streaming kernel (prefill-sized batches)
     bool expand_small = false;     // every expand tile is 16 tokens of rank <= 64: small kernel build
     bool fused_ok = false;         // both small: shrink and expand can run as one launch
     int32_t fused_spin_limit = 0;  // polls an expand block spends waiting for its group's shrink tiles
@@ -74,5 +75,7 @@ struct lora_tuning {
     int32_t fused_delay;           // single-launch decode kernel: head start of the shrink blocks' loads, units of ~0.4 us (+1)
     int32_t expand_wave_bytes_big; // like expand_wave_bytes, for adapter groups of at least expand_tb2_min_rows tokens
     int32_t shrink_tb4_min_rows;   // groups with at least this many tokens use 64-token shrink tiles
+    int32_t shrink_stream_min_tokens;  // batches with at least this many adapter tokens use the streaming shrink
+    int32_t shrink_stream_wgs;     // streaming shrink: 64-token tiles when 128-token tiles give fewer workgroups than this
 };
 extern lora_tuning g_lora_tuning;

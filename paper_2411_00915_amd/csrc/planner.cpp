@@ -27,6 +27,8 @@ lora_tuning g_lora_tuning = {
     /*fused_delay*/ 3,
     /*expand_wave_bytes_big*/ 131072,
     /*shrink_tb4_min_rows*/ 64,
+    /*shrink_stream_min_tokens*/ 1024,
+    /*shrink_stream_wgs*/ 512,
 };
 
 extern "C" void lora_tuning_set(const int32_t* values, int32_t count)
@@ -80,12 +82,40 @@ static void build_tiles(lora_plan* p)
     p->shrink_small = true;
     p->expand_small = true;
     const int G = (int)p->group_adapter.size();
+    // Prefill-sized batches (ranks up to 128) take the streaming shrink; its tiles hold 128 tokens, or 64
+    // when 128 would leave the launch with few workgroups even after the K split.
+    int32_t max_rank = 0;
+    for (int g = 0; g < G; ++g) max_rank = std::max(max_rank, p->rank[p->group_adapter[g]]);
+    p->shrink_stream = (int64_t)p->perm.size() >= tu.shrink_stream_min_tokens && max_rank <= 128 && p->K >= 1024;
+    int32_t stream_tokens = 128;
+    if (p->shrink_stream) {
+        int64_t n128 = 0;
+        for (int g = 0; g < G; ++g) n128 += (p->group_offset[g + 1] - p->group_offset[g] + 127) / 128;
+        if (n128 * 4 < tu.shrink_stream_wgs) stream_tokens = 64;
+    }
     for (int g = 0; g < G; ++g) {
         const int32_t a = p->group_adapter[g];
         const int32_t r = p->rank[a];
         const int32_t lo = p->group_offset[g], hi = p->group_offset[g + 1];
         const int32_t m = hi - lo;
 
+        // ---- shrink, prefill-sized batches: streaming tiles of up to 128 (or 64) tokens over all rank rows
+        if (p->shrink_stream) {
+            const int jblocks = (r + 15) / 16;
+            const int jbk = jblocks <= 1 ? 1 : (jblocks <= 2 ? 2 : (jblocks <= 4 ? 4 : 8));
+            for (int32_t row = lo; row < hi; row += stream_tokens) {
+                lora_tile t{};
+                t.adapter = a; t.row0 = row; t.nrows = std::min<int32_t>(stream_tokens, hi - row);
+                t.c0 = 0; t.cn = r;
+                const int nblk = (t.nrows + 15) / 16;
+                t.shape = lora_shape_code(nblk > 4 ? 8 : (nblk > 2 ? 4 : 2), jbk) | ((g & 0xffff) << 16);
+                t.reserved0 = r;
+                std::memcpy(&t.reserved1, &p->scale[a], sizeof(float));
+                p->shrink_max_blocks = std::max(p->shrink_max_blocks, jbk);
+                p->shrink_small = false;
+                p->shrink_tiles.push_back(t);
+            }
+        } else
         // ---- shrink: groups with many tokens take 32- or 64-token tiles over up to 64
         // rank rows (x is the big stream, and At is re-read once per tile); groups with few tokens
         // take 16-token tiles over 16 (or 32) rank rows so that the launch has
@@ -165,7 +195,9 @@ static void build_tiles(lora_plan* p)
             }
         p->shrink_tiles.swap(split);
     }
-    if (p->shrink_small)
+    if (p->shrink_stream)
+        p->shrink_waves = 8;
+    else if (p->shrink_small)
         p->shrink_waves = std::max(1, std::min({tu.shrink_small_waves / p->v_parts, 16, steps / p->v_parts}));
     else
         p->shrink_waves = std::max(1, std::min({tu.shrink_waves, 8, 64 / p->shrink_max_blocks, steps / p->v_parts}));

@@ -52,7 +52,7 @@ def _check_tiles(w, v, tok, perm):
         assert v["shrink_tiles"].shape[0] == 0 and not et_
     for t in v["shrink_tiles"]:
         tb, jb = t[5] & 15, (t[5] >> 4) & 15
-        assert t[2] <= 16 * tb and t[4] <= 16 * jb and tb in (1, 2, 4) and 1 <= jb <= 4
+        assert t[2] <= 16 * tb and t[4] <= 16 * jb and tb in (1, 2, 4, 8) and 1 <= jb <= 8
         assert t[3] % 16 == 0
     for t in v["expand_tiles"]:
         tb = t[5] & 15
@@ -177,7 +177,7 @@ def test_tuning_roundtrip_changes_tiles():
         a = _export(w)[0]
         B.lora_tuning_set(shrink_tb2_min_rows=1 << 20, shrink_tb4_min_rows=1 << 20, expand_tb2_min_rows=1 << 20,
                           shrink_small_waves=4, shrink_target_wgs=1,
-                          shrink_small_jb=2)
+                          shrink_small_jb=2, shrink_stream_min_tokens=1 << 30)
         b = _export(w)[0]
         assert b["shrink_waves"] == 4
         assert b["shrink_tiles"].shape[0] // b["v_parts"] > a["shrink_tiles"].shape[0] // a["v_parts"]

@@ -102,7 +102,7 @@ EXPORTED = ["lora_timing_begin", "lora_timing_end", "lora_timing_read", "lora_ke
 TUNING_FIELDS = ["shrink_waves", "shrink_tb2_min_rows", "shrink_max_jb", "expand_wave_bytes",
                  "expand_tb2_min_rows", "expand_tb4_min_rows", "tiled_min_tokens",
                  "shrink_small_waves", "shrink_small_jb", "shrink_target_wgs", "fused_spin_limit", "fused_delay", "expand_wave_bytes_big", "shrink_tb4_min_rows",
-                 "shrink_stream_min_tokens", "shrink_stream_wgs"]
+                 "shrink_stream_min_tokens", "shrink_stream_wgs", "expand_stream_stages"]
 
 
 class LoraError(RuntimeError):

@@ -26,10 +26,10 @@ union op16 {            // one 16-byte MFMA operand
     bf16x8 v;
 };
 
-__device__ __forceinline__ uint4 ld16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
-// the same for a pointer the compiler cannot trace back to a kernel argument (one fetched from a pointer
-// table): states that it points to global memory, so that the load is not a flat one
-__device__ __forceinline__ uint4 ld16_global(const bf16_t* p)
+// 16-byte load from global memory.  Pointers fetched from a pointer table cannot be traced back to a
+// kernel argument by the compiler, which would make their loads flat ones (counted as LDS traffic too,
+// so that waits on them are coarse); the address space is therefore stated here.
+__device__ __forceinline__ uint4 ld16(const bf16_t* p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
@@ -39,6 +39,7 @@ __device__ __forceinline__ uint4 ld16_global(const bf16_t* p)
     return *reinterpret_cast<const uint4*>(p);
 #endif
 }
+__device__ __forceinline__ uint4 ld16_global(const bf16_t* p) { return ld16(p); }
 
 __device__ __forceinline__ floatx4 mfma(const op16& a, const op16& b, floatx4 c)
 {
@@ -646,11 +647,228 @@ __global__ __launch_bounds__(256) void expand_tiled_kernel(
 #undef EXPAND_CASE
 }
 
+// ---------------------------------------------------------------------------
+// Streaming expand for prefill-sized batches, the mirror image of the streaming shrink.  One
+// workgroup (8 wavefronts) per tile = (16*NB tokens of one adapter) x a range of output features,
+// walked in stages of 64*FW features.  Wavefront w owns token block w % NB and, inside a stage, the
+// 64-feature chunk w / NB (wavefronts with w / NB >= FW idle).  y is private to a wavefront: it is
+// read four stages ahead and written back with instructions that cover whole 128-byte lines (8 tokens
+// x 64 features); the fp32 MFMA results reach that layout through an LDS patch of the wavefront's
+// own.  The stage's rows of Bt_a (64 FW features x r) are common to the tile's wavefronts and are
+// shared through LDS (double buffer, swizzled).  v (sum of the K parts, split into two bf16 terms)
+// stays in registers for the whole tile.  No branch inside the stage loop: loads outside the tile read
+// a block of zeros, stores outside it are masked.
+template <int KS, int FW>
+__device__ __forceinline__ void expand_stream_tile(
+    const lora_tile tile, const int32_t* __restrict__ perm, const float* __restrict__ v, lora_vspec vsp,
+    const bf16_t* __restrict__ Bt, int r, bf16_t* __restrict__ y, int64_t ldy, float beta,
+    const bf16_t* __restrict__ zeros, uint4* lds)
+{
+    constexpr int RC = 4 * KS;                    // 16-byte chunks per slab row (32 KS ranks)
+    constexpr int SH = KS == 1 ? 2 : (KS == 2 ? 1 : 0);
+    constexpr int SLAB = FW * 64 * RC;            // 16-byte chunks of one stage's slab: [64 FW features][RC]
+    constexpr int NLD = SLAB >= 512 ? SLAB / 512 : 1;
+    constexpr int PROW = 68;                      // floats per patch row: 64 features + 4, rows start 4 banks apart
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int NB = tile.shape & 15;               // 1, 2, 4 or 8
+    const int blk = wave & (NB - 1), fw = wave / NB;
+    const bool active = fw < FW;
+    const int n_end = tile.c0 + tile.cn;
+    const int n_stages = (((tile.cn + 63) >> 6) + FW - 1) / FW;
+
+    // v operands (MFMA columns = tokens): lane holds v[token m][32 s + 8 g .. +7]
+    op16 vhi[KS], vlo[KS];
+    {
+        const int row = blk * 16 + m;
+        const bool row_ok = active && row < tile.nrows;
+        const int tok = perm[tile.row0 + (row_ok ? row : 0)];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int j = s * 32 + g * 8;
+            float4 pa[4], pb[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {                  // all parts are fetched before the first add
+                if (row_ok && j < r && q < vsp.P) {
+                    const float* vq = v + q * vsp.part + (int64_t)tok * vsp.R + j;
+                    pa[q] = *reinterpret_cast<const float4*>(vq);
+                    pb[q] = *reinterpret_cast<const float4*>(vq + 4);
+                } else {
+                    pa[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    pb[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+            float f[8];
+            f[0] = ((pa[0].x + pa[1].x) + pa[2].x) + pa[3].x; f[1] = ((pa[0].y + pa[1].y) + pa[2].y) + pa[3].y;
+            f[2] = ((pa[0].z + pa[1].z) + pa[2].z) + pa[3].z; f[3] = ((pa[0].w + pa[1].w) + pa[2].w) + pa[3].w;
+            f[4] = ((pb[0].x + pb[1].x) + pb[2].x) + pb[3].x; f[5] = ((pb[0].y + pb[1].y) + pb[2].y) + pb[3].y;
+            f[6] = ((pb[0].z + pb[1].z) + pb[2].z) + pb[3].z; f[7] = ((pb[0].w + pb[1].w) + pb[2].w) + pb[3].w;
+            split_bf16(f, vhi[s], vlo[s]);
+        }
+    }
+
+    // y: instruction i of a stage covers tokens 8i .. 8i+7 of the block, 128 bytes (64 features) each
+    const int yl_row = lane >> 3, yl_c = lane & 7;
+    bf16_t* ybase[2];
+    int y_ok = 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int rr = blk * 16 + 8 * i + yl_row;
+        const bool ok = active && rr < tile.nrows;
+        y_ok |= (int)ok << i;
+        ybase[i] = y + (int64_t)perm[tile.row0 + (ok ? rr : 0)] * ldy + tile.c0 + fw * 64 + yl_c * 8;
+    }
+    const int y_n0 = tile.c0 + fw * 64 + yl_c * 8;           // first feature of this lane's 8 in stage 0
+    auto load_y = [&](int s, int i) {
+        const bool ok = ((y_ok >> i) & 1) && y_n0 + s * (FW * 64) < n_end && beta != 0.f;
+        return ld16(ok ? ybase[i] + s * (FW * 64) : zeros);
+    };
+
+    // slab staging: unit q = feature row (q / RC) of the stage, 16-byte column q % RC
+    const bf16_t* bsrc[NLD];
+    int bslot[NLD], bfeat[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int q = (tid + i * 512) % SLAB, c = q % RC, f = q / RC;       // f in [0, 64 FW)
+        const int f64 = f & 63;
+        bfeat[i] = c * 8 < r ? tile.c0 + f : (1 << 30);                    // columns past the rank: never loaded
+        bsrc[i] = Bt + (int64_t)(tile.c0 + f) * r + c * 8;
+        bslot[i] = f * RC + (c ^ ((4 * (f64 >> 4) + (f64 & 3)) >> SH));
+    }
+    auto load_b = [&](int s, uint4 (&rb)[NLD]) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i)
+            rb[i] = ld16(bfeat[i] + s * (FW * 64) < n_end ? bsrc[i] + (int64_t)s * (FW * 64) * r : zeros);
+    };
+    auto store_b = [&](int buf, const uint4 (&rb)[NLD]) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) lds[buf * SLAB + bslot[i]] = rb[i];
+    };
+
+    float* patch = reinterpret_cast<float*>(lds + 2 * SLAB) + wave * (16 * PROW);
+    // one stage: MFMA rows = features (row 4q+i of block b stands for feature 16q+4b+i of the chunk, so
+    // that a lane ends with 4 x 4 consecutive features of token m), results to the patch, back in the
+    // layout of the y loads, y = beta y + delta, rounded once, stored; then the y registers are
+    // refilled with stage s_next
+    auto stage = [&](int buf, int s, uint4 (&yr)[2]) {
+        floatx4 acc[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+            const int f = (active ? fw : 0) * 64 + 16 * (m >> 2) + 4 * b + (m & 3);   // idle wavefronts stay inside the slab
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                op16 a;
+                a.u = lds[buf * SLAB + f * RC + ((4 * ks + g) ^ (m >> SH))];
+                acc[b] = mfma(a, vhi[ks], acc[b]);
+                acc[b] = mfma(a, vlo[ks], acc[b]);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) *reinterpret_cast<floatx4*>(patch + m * PROW + 16 * g + 4 * b) = acc[b];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const float* pr = patch + (8 * i + yl_row) * PROW + yl_c * 8;
+            const floatx4 d0 = *reinterpret_cast<const floatx4*>(pr), d1 = *reinterpret_cast<const floatx4*>(pr + 4);
+            const uint32_t yi[4] = {yr[i].x, yr[i].y, yr[i].z, yr[i].w};
+            uint32_t out[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float e0 = fmaf(beta, bf16_to_f32((bf16_t)(yi[q] & 0xffffu)), q < 2 ? d0[2 * q] : d1[2 * q - 4]);
+                const float e1 = fmaf(beta, bf16_to_f32((bf16_t)(yi[q] >> 16)), q < 2 ? d0[2 * q + 1] : d1[2 * q - 3]);
+                out[q] = (uint32_t)f32_to_bf16(e0) | ((uint32_t)f32_to_bf16(e1) << 16);
+            }
+            if (((y_ok >> i) & 1) && y_n0 + s * (FW * 64) < n_end)
+                *reinterpret_cast<uint4*>(ybase[i] + s * (FW * 64)) = uint4{out[0], out[1], out[2], out[3]};
+            yr[i] = load_y(s + 4, i);
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    uint4 rb0[NLD], rb1[NLD];
+    uint4 yr0[2], yr1[2], yr2[2], yr3[2];
+    load_b(0, rb0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) yr0[i] = load_y(0, i);
+    store_b(0, rb0);
+    load_b(1, rb0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) yr1[i] = load_y(1, i);
+    load_b(2, rb1);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) yr2[i] = load_y(2, i);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) yr3[i] = load_y(3, i);
+    __syncthreads();
+    // stage s multiplies from slab buffer s%2; the slab of stage s+1 (in registers since two stages ago)
+    // goes to the other buffer, and the slab of stage s+3 is requested.  Stages past the last one work
+    // on zeros and store nothing.
+    int s = 0;
+    do {
+#define EXPAND_STAGE(BUF_, S_, YR_, RB_)                 \
+        stage(BUF_, S_, YR_);                            \
+        __builtin_amdgcn_sched_barrier(0);               \
+        store_b(1 - BUF_, RB_);                          \
+        load_b((S_) + 3, RB_);                           \
+        __syncthreads();
+        EXPAND_STAGE(0, s, yr0, rb0)
+        EXPAND_STAGE(1, s + 1, yr1, rb1)
+        EXPAND_STAGE(0, s + 2, yr2, rb0)
+        EXPAND_STAGE(1, s + 3, yr3, rb1)
+#undef EXPAND_STAGE
+        s += 4;
+    } while (s < n_stages);
+}
+
+extern __shared__ uint4 expand_stream_lds[];
+
+// KSMAX: the largest number of 32-rank steps among the plan's adapters (the register count of the
+// kernel is that of its widest case)
+template <int KSMAX>
+__global__ __launch_bounds__(512) void expand_stream_kernel(
+    const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm,
+    const float* __restrict__ v, lora_vspec R, const bf16_t* const* __restrict__ Bt_ptrs,
+    bf16_t* __restrict__ y, int64_t ldy, float beta, const bf16_t* __restrict__ zeros)
+{
+    const lora_tile tile = tiles[blockIdx.x];
+    const int r = tile.reserved0;
+    const bf16_t* Bt = Bt_ptrs[tile.adapter];
+    const int ks = r <= 32 ? 1 : (r <= 64 ? 2 : 4), fw = (tile.shape >> 4) & 15;
+#define EXPAND_STREAM_CASE(KS_, FW_) \
+    if (KS_ <= KSMAX && ks == KS_ && fw == FW_) { expand_stream_tile<KS_, FW_>(tile, perm, v, R, Bt, r, y, ldy, beta, zeros, expand_stream_lds); return; }
+    EXPAND_STREAM_CASE(2, 1) EXPAND_STREAM_CASE(2, 2) EXPAND_STREAM_CASE(2, 4)
+    EXPAND_STREAM_CASE(1, 1) EXPAND_STREAM_CASE(1, 2) EXPAND_STREAM_CASE(1, 4) EXPAND_STREAM_CASE(1, 8)
+    EXPAND_STREAM_CASE(4, 1) EXPAND_STREAM_CASE(4, 2)
+#undef EXPAND_STREAM_CASE
+}
+
 hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, const float* v,
                                const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream)
 {
     const int n_tiles = (int)p->expand_tiles.size();
     if (n_tiles == 0) return hipSuccess;
+    if (p->expand_stream) {
+        // dynamic LDS above 64 KB has to be allowed once per kernel (the largest any tile mix needs: 98 KB)
+#define EXPAND_STREAM_LAUNCH(KSMAX_)                                                                                    \
+    do {                                                                                                                \
+        static bool attr_set = false;                                                                                   \
+        if (!attr_set) {                                                                                                \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&expand_stream_kernel<KSMAX_>),            \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 65536 + 34816);              \
+            if (e != hipSuccess) return e;                                                                              \
+            attr_set = true;                                                                                            \
+        }                                                                                                               \
+        LORA_LAUNCH(LORA_K_EXPAND_STREAM, expand_stream_kernel<KSMAX_>, dim3(n_tiles), dim3(512),                       \
+                    (size_t)p->expand_stream_lds, stream, d.expand_tiles, d.perm, v, lora_vspec_of(p),                  \
+                    (const bf16_t* const*)Bt, (bf16_t*)y, ldy, beta, (const bf16_t*)d.zeros);                           \
+    } while (0)
+        if (p->expand_stream_ks <= 1) EXPAND_STREAM_LAUNCH(1);
+        else if (p->expand_stream_ks <= 2) EXPAND_STREAM_LAUNCH(2);
+        else EXPAND_STREAM_LAUNCH(4);
+#undef EXPAND_STREAM_LAUNCH
+        return hipGetLastError();
+    }
     if (p->expand_small && p->v_parts == 1)
         LORA_LAUNCH(LORA_K_EXPAND_TILED, expand_tiled_small_kernel<1>, dim3(n_tiles), dim3(256), 0, stream,
                     d.expand_tiles, d.perm, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta);

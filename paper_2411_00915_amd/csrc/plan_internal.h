@@ -24,6 +24,9 @@ struct lora_plan {
     int32_t shrink_waves = 4;      // wavefronts per shrink workgroup (split the K range), 1..16
     bool shrink_small = false;     // every shrink tile is 16 tokens x <= 32 rank rows: small kernel build
     bool shrink_stream = false;    // shrink tiles are those of the streaming kernel (prefill-sized batches)
+    bool expand_stream = false;    // likewise for the expand tiles
+    int32_t expand_stream_ks = 1;  // streaming expand: largest number of 32-rank steps (1, 2, 4) among the tiles
+    int32_t expand_stream_lds = 0; // streaming expand: dynamic LDS bytes of the launch
     bool expand_small = false;     // every expand tile is 16 tokens of rank <= 64: small kernel build
     bool fused_ok = false;         // both small: shrink and expand can run as one launch
     int32_t fused_spin_limit = 0;  // polls an expand block spends waiting for its group's shrink tiles
@@ -77,5 +80,6 @@ struct lora_tuning {
     int32_t shrink_tb4_min_rows;   // groups with at least this many tokens use 64-token shrink tiles
     int32_t shrink_stream_min_tokens;  // batches with at least this many adapter tokens use the streaming shrink
     int32_t shrink_stream_wgs;     // streaming shrink: 64-token tiles when 128-token tiles give fewer workgroups than this
+    int32_t expand_stream_stages;  // streaming expand: stages (of 64 features per wavefront) one workgroup walks
 };
 extern lora_tuning g_lora_tuning;

@@ -29,6 +29,7 @@ lora_tuning g_lora_tuning = {
     /*shrink_tb4_min_rows*/ 64,
     /*shrink_stream_min_tokens*/ 1024,
     /*shrink_stream_wgs*/ 512,
+    /*expand_stream_stages*/ 16,
 };
 
 extern "C" void lora_tuning_set(const int32_t* values, int32_t count)
@@ -87,11 +88,22 @@ static void build_tiles(lora_plan* p)
     int32_t max_rank = 0;
     for (int g = 0; g < G; ++g) max_rank = std::max(max_rank, p->rank[p->group_adapter[g]]);
     p->shrink_stream = (int64_t)p->perm.size() >= tu.shrink_stream_min_tokens && max_rank <= 128 && p->K >= 1024;
+    p->expand_stream = p->shrink_stream && p->N >= 64;
+    p->expand_stream_ks = 1;
+    p->expand_stream_lds = 0;
     int32_t stream_tokens = 128;
     if (p->shrink_stream) {
         int64_t n128 = 0;
         for (int g = 0; g < G; ++g) n128 += (p->group_offset[g + 1] - p->group_offset[g] + 127) / 128;
         if (n128 * 4 < tu.shrink_stream_wgs) stream_tokens = 64;
+    }
+    // streaming expand: feature range per workgroup, in stages; halved while the launch would have
+    // fewer than two workgroups per CU (but at least 4 stages: the start-up of a tile has to pay off)
+    int32_t expand_stages = std::max(1, tu.expand_stream_stages);
+    if (p->expand_stream) {
+        int64_t n_tt = 0;
+        for (int g = 0; g < G; ++g) n_tt += (p->group_offset[g + 1] - p->group_offset[g] + stream_tokens - 1) / stream_tokens;
+        while (expand_stages > 4 && n_tt * ((p->N + expand_stages * 64 - 1) / (expand_stages * 64)) < 512) expand_stages /= 2;
     }
     for (int g = 0; g < G; ++g) {
         const int32_t a = p->group_adapter[g];
@@ -142,6 +154,32 @@ static void build_tiles(lora_plan* p)
                 }
             }
         }
+        // ---- expand, prefill-sized batches: streaming tiles, the same token ranges as the streaming shrink;
+        // with fewer than 8 token blocks the wavefronts also spread over FW 64-feature chunks per stage
+        // (as far as the slab of Bt rows, 64 FW x 32 KS ranks, stays within 32 KB)
+        if (p->expand_stream) {
+            const int ks = r <= 32 ? 1 : (r <= 64 ? 2 : 4);
+            const int fw_max = 8 / ks;
+            for (int32_t row = lo; row < hi; row += stream_tokens) {
+                const int32_t nrows = std::min<int32_t>(stream_tokens, hi - row);
+                const int nblk = (nrows + 15) / 16;
+                const int nb = nblk > 4 ? 8 : (nblk > 2 ? 4 : (nblk > 1 ? 2 : 1));
+                const int fw = std::min(8 / nb, fw_max);
+                const int32_t n_tile = expand_stages * 64 * fw;
+                for (int32_t n0 = 0; n0 < p->N; n0 += n_tile) {
+                    lora_tile t{};
+                    t.adapter = a; t.row0 = row; t.nrows = nrows;
+                    t.c0 = n0; t.cn = std::min<int32_t>(n_tile, p->N - n0);
+                    t.shape = lora_shape_code(nb, fw);
+                    t.reserved0 = r;
+                    t.reserved1 = g;
+                    p->expand_small = false;
+                    p->expand_stream_ks = std::max(p->expand_stream_ks, ks);
+                    p->expand_stream_lds = std::max(p->expand_stream_lds, fw * ks * 4 * 2048 + 8 * 16 * 68 * 4);
+                    p->expand_tiles.push_back(t);
+                }
+            }
+        } else
         // ---- expand ----
         {
             int tb = 1;

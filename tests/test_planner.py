@@ -56,7 +56,7 @@ def _check_tiles(w, v, tok, perm):
         assert t[3] % 16 == 0
     for t in v["expand_tiles"]:
         tb = t[5] & 15
-        assert t[2] <= 16 * tb and tb in (1, 2, 4) and t[3] % 64 == 0
+        assert t[2] <= 16 * tb and tb in (1, 2, 4, 8) and t[3] % 64 == 0
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg4d", "cfg5"])

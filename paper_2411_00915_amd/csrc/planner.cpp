@@ -219,7 +219,9 @@ static void build_tiles(lora_plan* p)
     p->v_parts = 1;
     {
         int P = 1;
-        while (P < 4 && (int64_t)p->shrink_tiles.size() * P < tu.shrink_target_wgs && steps / (2 * P) >= 8) P *= 2;
+        // (the streaming shrink has 8 wavefronts per workgroup and long tiles: half as many workgroups do)
+        const int64_t target = p->shrink_stream ? std::max(1, tu.shrink_stream_wgs / 2) : tu.shrink_target_wgs;
+        while (P < 4 && (int64_t)p->shrink_tiles.size() * P < target && steps / (2 * P) >= 8) P *= 2;
         p->v_parts = P;
     }
     {

@@ -203,6 +203,33 @@ def test_ragged_small_cases(variant):
         run_forward_case(w, variant=variant)
 
 
+def test_streaming_kernels_ragged_cases():
+    # the prefill-sized (streaming) shrink / expand kernels forced onto small ragged batches: adapter
+    # groups from 1 to a few hundred tokens (every tile shape: 8, 4, 2, 1 token blocks), all ranks up to
+    # 128, K with a ragged last stage and a ragged last k-step, N with a ragged last chunk, tokens without
+    # adapter, padded leading dimensions, K split over 1, 2, 4 workgroups, short and long feature ranges
+    before = B.lora_tuning_get()
+    B.lora_timing_begin()
+    try:
+        cases = [(420, 1096, 200, 3, 300), (333, 2048, 1352, 9, 90), (700, 2120, 72, 5, 40), (129, 1024, 64, 1, 1000)]
+        settings = [dict(shrink_stream_wgs=1, expand_stream_stages=16), dict(shrink_stream_wgs=1 << 20, expand_stream_stages=1),
+                    dict(shrink_stream_wgs=512, expand_stream_stages=2)]
+        for seed, (T, K, N, n_a, max_seg) in enumerate(cases):
+            w = wl.random_case(500 + seed, T, K, N, n_a, (8, 16, 24, 32, 40, 64, 96, 128), max_seg=max_seg,
+                               frac_none=0.15, scales=(0.5, 1.0, 2.0, -1.5), empty_segments=True)
+            for st in settings:
+                B.lora_tuning_set(**before)
+                B.lora_tuning_set(shrink_stream_min_tokens=1, **st)
+                run_delta_case(w, B.LORA_VARIANT_TILED, check_beta0=(st is settings[0]))
+            run_delta_case(w, B.LORA_VARIANT_TILED, ld_pad=8, check_beta0=False)
+            run_forward_case(w, variant=B.LORA_VARIANT_TILED)
+    finally:
+        B.lora_tuning_set(**before)
+        launched = B.lora_timing_end()
+    assert {"shrink_stream_kernel", "expand_stream_kernel"} <= set(launched), sorted(launched)
+    assert not {"shrink_tiled_kernel", "expand_tiled_kernel"} & set(launched), sorted(launched)
+
+
 def test_general_kernels_take_odd_layouts():
     w = wl.random_case(200, 45, 77, 53, 5, (1, 3, 5, 12, 200, 256), max_seg=9, frac_none=0.2,
                        scales=(1.0, 2.0, -0.5))

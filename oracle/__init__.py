@@ -188,6 +188,20 @@ def forward(x, W, tok_adapter, ad: Adapters, rows=None) -> np.ndarray:
     return y
 
 
+def merge(W, A, B, scale: float, sign: int = 1) -> np.ndarray:
+    """Mode switch (paper section 4.4.2, "swift inference mode switch"): the adapter folded into the
+    base weight, W + sign * s * (A B) with sign = +1 to merge and -1 to unmerge; [K, N] float64.
+    Written as the definition of the product, one rank-1 term at a time."""
+    W, A, B = _f64(W), _f64(A), _f64(B)
+    K, N = W.shape
+    r = A.shape[1]
+    assert A.shape == (K, r) and B.shape == (r, N) and sign in (1, -1)
+    out = W.copy()
+    for j in range(r):
+        out += (sign * float(scale)) * np.outer(A[:, j], B[j, :])
+    return out
+
+
 def error_metrics(y, y_ref, threshold: float = 1e-2):
     """(normwise relative error, max elementwise relative error over
     |y_ref| > threshold).  Both sides are widened to float64 first."""

@@ -202,6 +202,32 @@ def test_delora_identity():
     assert np.allclose(mixed, plain, rtol=1e-11, atol=1e-11)
 
 
+def test_merge_mode_switch():
+    # mode switch (section 4.4.2): W' = W + s A B.  Pinned to (i) the merged layer reproducing the
+    # unmerged operator x W + s (x A) B computed by the C oracle (an independent code path), (ii) a closed
+    # form for constant factors, (iii) merge followed by unmerge, (iv) entries worked by hand, with
+    # non-square shapes so that a transposed factor cannot pass
+    rng = np.random.default_rng(21)
+    T, K, N, r, s = 9, 14, 11, 3, 1.75
+    x = rng.standard_normal((T, K)); W = rng.standard_normal((K, N))
+    A, B = rng.standard_normal((K, r)), rng.standard_normal((r, N))
+    Wm = oracle.merge(W, A, B, s)
+    tok = np.zeros(T, np.int32)
+    unmerged = oracle.forward(x, W, tok, oracle.Adapters([r], [s], [A], [B]))
+    assert np.allclose(oracle.base(x, Wm), unmerged, rtol=1e-12, atol=1e-12)
+    # constant factors: (A B)[k, n] = r a b
+    ones = oracle.merge(np.zeros((K, N)), np.full((K, r), 2.0), np.full((r, N), -0.5), 3.0)
+    assert np.array_equal(ones, np.full((K, N), 3.0 * r * 2.0 * -0.5))
+    # unmerge undoes merge (float64: to rounding), and sign = -1 is the same as a negated scale
+    back = oracle.merge(Wm, A, B, s, sign=-1)
+    assert np.allclose(back, W, rtol=0, atol=1e-13)
+    assert np.array_equal(oracle.merge(W, A, B, s, sign=-1), oracle.merge(W, A, B, -s))
+    # two entries by hand: W'[k, n] = W[k, n] + s sum_j A[k, j] B[j, n]
+    for k, n in [(0, 0), (K - 1, N - 2)]:
+        hand = W[k, n] + s * sum(A[k, j] * B[j, n] for j in range(r))
+        assert abs(Wm[k, n] - hand) < 1e-13
+
+
 def test_fast_expand_is_bitwise_literal_and_consistent_with_forward():
     w = _small(seed=12)
     ad = _adapters(w)

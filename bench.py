@@ -64,13 +64,64 @@ def algorithmic_work(w, beta=1.0):
                 gemm_flops=2 * w.T * w.K * w.N, gemm_delta_flops=2 * w.T * w.K * w.N + 2 * r_tok * w.N)
 
 
+def bench_merge(args, torch, B, dev):
+    """Mode switch: one adapter (rank 64) merged into every one of 32 4096x4096 projections in one launch
+    (lora_merge), alternating merge / unmerge; a step is one such launch."""
+    L, N, K, r, s = 32, 4096, 4096, 64, 2.0
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(24110915)
+    rnd = lambda n, std: (torch.randn(n, generator=gen, device=dev) * std).to(torch.bfloat16)
+    Wt = [rnd(N * K, K ** -0.5).view(N, K) for _ in range(L)]
+    At = [rnd(r * K, K ** -0.5).view(r, K) for _ in range(L)]
+    Bt = [rnd(N * r, r ** -0.5).view(N, r) for _ in range(L)]
+    ptrs = lambda ts: torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device=dev)
+    pW, pA, pB = ptrs(Wt), ptrs(At), ptrs(Bt)
+    stream = torch.cuda.current_stream()
+    sign = [1.0]
+
+    def step():
+        B.lora_merge(L, N, K, r, s * sign[0], B.LORA_BF16, pW, K, pA, pB, stream=stream)
+        sign[0] = -sign[0]
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    B.lora_timing_begin()
+    for _ in range(min(args.steps, 20)):
+        step()
+    torch.cuda.synchronize()
+    kern = B.lora_timing_end()["merge_kernel"]
+    by = L * (2 * N * K * 2 + (N + K) * r * 2)           # every weight read and written once, the factors read once
+    fl = 2 * L * N * K * r
+    print(json.dumps({
+        "metric": "mode switch ms (one adapter merged into / removed from all layers, one launch)",
+        "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "merge7b", "layers": L, "n": N, "k": K, "rank": r,
+                   "launch": "eager, lora_merge per step, alternating +scale / -scale"},
+        "roofline": {"bound": "hbm", "kernel": "merge_stream_kernel", "achieved": round(by / kern["avg_us"] * 1e-3, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(by / kern["avg_us"] * 1e-3 / HBM_PEAK_GBS, 4),
+                     "traffic": None, "avg_kernel_us": round(kern["avg_us"], 3), "algorithmic_bytes": by},
+        "cpu_baseline": None,
+        "kernels": {"merge": {"kernel": "merge_stream_kernel", "avg_us": round(kern["avg_us"], 3),
+                              "min_us": round(kern["min_us"], 3), "launches": kern["count"],
+                              "algorithmic_bytes": by, "algorithmic_flops": fl}}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--layers", type=int, default=32)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg4d", "cfg5", "cfg5mlp"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg4d", "cfg5", "cfg5mlp", "merge7b"])
     ap.add_argument("--path", default="delta", choices=["delta", "two-launches", "fused"])
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time budget of the oracle leg (0 = skip)")
     ap.add_argument("--no-graph", action="store_true")
@@ -92,6 +143,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload == "merge7b":
+        return bench_merge(args, torch, B, dev)
     fused = args.path == "fused"
 
     if args.workload in ("cfg5", "cfg5mlp"):

@@ -242,6 +242,25 @@ lora_status lora_fused_forward(lora_plan* plan, const void* x, int64_t ldx,
                                void* y, int64_t ldy,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * lora_merge -- mode switch (section 4.4.2, "swift inference mode switch"): fold one adapter into
+ * the base weights of all layers, or take it out again, in place and in one launch:
+ *     Wt_l[n*ldw + k] += scale * sum_j Bt_l[n*rank + j] * At_l[j*k_dim + k]     l = 0..num_layers-1
+ * i.e. W_l <- W_l + scale * A_l B_l; pass -scale to unmerge.  fp32 accumulation, one rounding
+ * (RNE) at the store; a merge followed by the unmerge restores W_l only to within that rounding.
+ * d_Wt_ptrs, d_At_ptrs, d_Bt_ptrs: device arrays of num_layers device pointers each (layouts as
+ * above: Wt_l [n, k] with leading dimension ldw, At_l [rank, k], Bt_l [n, rank]); every layer has
+ * the same n, k and rank.  The weights must not be in use by work in flight on another stream.
+ * bf16 with k, ldw and rank multiples of 8, rank <= 128 and 16-byte aligned layer pointers runs
+ * the streaming kernel (every weight read and written once, whole cache lines); with
+ * variant = LORA_VARIANT_GENERAL, fp32 or any other shape a general kernel runs.
+ * LORA_VARIANT_TILED on a shape the streaming kernel does not take: LORA_ERR_UNSUPPORTED.
+ * num_layers = 0 or rank = 0: nothing to do, LORA_OK.
+ */
+lora_status lora_merge(int32_t num_layers, int32_t n, int32_t k, int32_t rank, float scale, int32_t dtype,
+                       int32_t variant, void* const* d_Wt_ptrs, int64_t ldw,
+                       const void* const* d_At_ptrs, const void* const* d_Bt_ptrs, void* hip_stream);
+
 const char* lora_status_str(lora_status s);
 
 /*

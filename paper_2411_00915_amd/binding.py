@@ -78,6 +78,9 @@ _lib.lora_base_gemm.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, 
 _lib.lora_fused_forward.restype = ctypes.c_int
 _lib.lora_fused_forward.argtypes = [_vp, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp, _vp,
                                     _vp, ctypes.c_int64, _vp, ctypes.c_size_t, _vp]
+_lib.lora_merge.restype = ctypes.c_int
+_lib.lora_merge.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, ctypes.c_int32,
+                            ctypes.c_int32, _vp, ctypes.c_int64, _vp, _vp, _vp]
 _lib.lora_status_str.restype = ctypes.c_char_p
 _lib.lora_status_str.argtypes = [ctypes.c_int]
 _lib.lora_tuning_set.restype = None
@@ -97,7 +100,7 @@ _lib.lora_kernel_count.restype = ctypes.c_int32
 EXPORTED = ["lora_timing_begin", "lora_timing_end", "lora_timing_read", "lora_kernel_name", "lora_kernel_count",
             "lora_plan_create", "lora_plan_destroy", "lora_plan_query", "lora_plan_export",
             "lora_plan_upload", "lora_shrink", "lora_expand", "lora_delta", "lora_base_gemm",
-            "lora_fused_forward", "lora_status_str", "lora_tuning_set", "lora_tuning_get"]
+            "lora_fused_forward", "lora_merge", "lora_status_str", "lora_tuning_set", "lora_tuning_get"]
 
 TUNING_FIELDS = ["shrink_waves", "shrink_tb2_min_rows", "shrink_max_jb", "expand_wave_bytes",
                  "expand_tb2_min_rows", "expand_tb4_min_rows", "tiled_min_tokens",
@@ -275,6 +278,12 @@ def lora_delta(plan: Plan, x, ldx: int, d_At_ptrs, d_Bt_ptrs, v, y, ldy: int, be
 def lora_base_gemm(num_tokens: int, k: int, n: int, dtype: int, x, ldx: int, Wt, ldw: int, y, ldy: int, stream=None):
     _check(_lib.lora_base_gemm(int(num_tokens), int(k), int(n), int(dtype), _ptr(x), int(ldx), _ptr(Wt), int(ldw),
                                _ptr(y), int(ldy), _stream(stream)), "lora_base_gemm")
+
+
+def lora_merge(num_layers: int, n: int, k: int, rank: int, scale: float, dtype: int, d_Wt_ptrs, ldw: int,
+               d_At_ptrs, d_Bt_ptrs, variant: int = LORA_VARIANT_AUTO, stream=None):
+    _check(_lib.lora_merge(int(num_layers), int(n), int(k), int(rank), float(scale), int(dtype), int(variant),
+                           _ptr(d_Wt_ptrs), int(ldw), _ptr(d_At_ptrs), _ptr(d_Bt_ptrs), _stream(stream)), "lora_merge")
 
 
 def lora_fused_forward(plan: Plan, x, ldx: int, Wt, ldw: int, d_At_ptrs, d_Bt_ptrs, y, ldy: int,

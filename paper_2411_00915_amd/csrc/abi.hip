@@ -6,6 +6,8 @@
 #include <mutex>
 #include <vector>
 
+#include <cmath>
+
 #include "kernels.h"
 #include "plan_internal.h"
 
@@ -253,6 +255,27 @@ extern "C" lora_status lora_base_gemm(int32_t T, int32_t K, int32_t N, int32_t d
         e = launch_gemm_tiled(T, K, N, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
     else
         e = launch_gemm_general(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, stream);
+    return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
+}
+
+extern "C" lora_status lora_merge(int32_t L, int32_t N, int32_t K, int32_t r, float scale, int32_t dtype,
+                                  int32_t variant, void* const* d_Wt_ptrs, int64_t ldw,
+                                  const void* const* d_At_ptrs, const void* const* d_Bt_ptrs, void* hip_stream)
+{
+    if (L < 0 || N < 1 || K < 1 || r < 0 || r > LORA_MAX_RANK || !std::isfinite(scale)) return LORA_ERR_INVALID_ARG;
+    if (dtype != LORA_F32 && dtype != LORA_BF16) return LORA_ERR_INVALID_ARG;
+    if (variant < LORA_VARIANT_AUTO || variant > LORA_VARIANT_TILED) return LORA_ERR_INVALID_ARG;
+    if (L == 0 || r == 0) return LORA_OK;
+    if (!d_Wt_ptrs || !d_At_ptrs || !d_Bt_ptrs || ldw < K) return LORA_ERR_INVALID_ARG;
+    if (L > 65535) return LORA_ERR_UNSUPPORTED;
+    const bool tiled_ok = dtype == LORA_BF16 && K % 8 == 0 && ldw % 8 == 0 && r % 8 == 0 && r <= 128;
+    if (variant == LORA_VARIANT_TILED && !tiled_ok) return LORA_ERR_UNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (tiled_ok && variant != LORA_VARIANT_GENERAL)
+        e = launch_merge_tiled(L, N, K, r, scale, d_Wt_ptrs, ldw, d_At_ptrs, d_Bt_ptrs, stream);
+    else
+        e = launch_merge_general(L, N, K, r, scale, dtype, d_Wt_ptrs, ldw, d_At_ptrs, d_Bt_ptrs, stream);
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
 }
 

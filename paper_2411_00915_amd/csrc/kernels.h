@@ -61,3 +61,9 @@ hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int
                              const void* Wt, int64_t ldw, void* y, int64_t ldy,
                              const lora_plan* p, const lora_dev_tables* d, const float* v, void* vb,
                              const void* const* Bt, hipStream_t stream);
+
+// mode switch: Wt_l += s Bt_l At_l for L layers in one launch (device arrays of L pointers each)
+hipError_t launch_merge_tiled(int32_t L, int32_t N, int32_t K, int32_t r, float s, void* const* Wt, int64_t ldw,
+                              const void* const* At, const void* const* Bt, hipStream_t stream);
+hipError_t launch_merge_general(int32_t L, int32_t N, int32_t K, int32_t r, float s, int32_t dtype, void* const* Wt,
+                                int64_t ldw, const void* const* At, const void* const* Bt, hipStream_t stream);

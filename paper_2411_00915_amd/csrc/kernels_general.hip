@@ -5,6 +5,8 @@
 // layout the tiled kernels do not take.
 //
 // Operator: v = s_a (x A_a),  y = beta y + v B_a   (paper sections 2, 3.2, 4.3.1).
+#include <algorithm>
+
 #include "device_util.h"
 #include "kernels.h"
 #include "launch.h"
@@ -157,5 +159,38 @@ hipError_t launch_gemm_general(int32_t T, int32_t K, int32_t N, int32_t dtype, c
     else
         LORA_LAUNCH(LORA_K_GEMM_GENERAL, (gemm_general_kernel<bf16_t>), grid, dim3(256), 0, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
             (bf16_t*)y, ldy, ta, rk, v, R, (const bf16_t* const*)Bt);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// General mode switch  Wt_l[n,k] += s sum_j Bt_l[n,j] At_l[j,k]  (any dtype, any alignment, any rank):
+// one thread per weight, fp32 accumulation, one rounding at the store.
+template <typename T>
+__global__ __launch_bounds__(256) void merge_general_kernel(
+    int N, int K, int r, float s, T* const* __restrict__ Wt_ptrs, int64_t ldw,
+    const T* const* __restrict__ At_ptrs, const T* const* __restrict__ Bt_ptrs)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x, layer = blockIdx.z;
+    if (k >= K) return;
+    const T* At = At_ptrs[layer];
+    for (int n = blockIdx.y; n < N; n += gridDim.y) {
+        const T* Bn = Bt_ptrs[layer] + (int64_t)n * r;
+        float d = 0.f;
+        for (int j = 0; j < r; ++j) d = fmaf(elem<T>::load(Bn + j), elem<T>::load(At + (int64_t)j * K + k), d);
+        T* w = Wt_ptrs[layer] + (int64_t)n * ldw + k;
+        elem<T>::store(w, fmaf(s, d, elem<T>::load(w)));
+    }
+}
+
+hipError_t launch_merge_general(int32_t L, int32_t N, int32_t K, int32_t r, float s, int32_t dtype, void* const* Wt,
+                                int64_t ldw, const void* const* At, const void* const* Bt, hipStream_t stream)
+{
+    dim3 grid((K + 255) / 256, std::min(N, 65535), L);
+    if (dtype == LORA_F32)
+        LORA_LAUNCH(LORA_K_MERGE, (merge_general_kernel<float>), grid, dim3(256), 0, stream, N, K, r, s,
+                    (float* const*)Wt, ldw, (const float* const*)At, (const float* const*)Bt);
+    else
+        LORA_LAUNCH(LORA_K_MERGE, (merge_general_kernel<bf16_t>), grid, dim3(256), 0, stream, N, K, r, s,
+                    (bf16_t* const*)Wt, ldw, (const bf16_t* const*)At, (const bf16_t* const*)Bt);
     return hipGetLastError();
 }

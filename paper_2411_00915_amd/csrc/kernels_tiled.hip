@@ -843,6 +843,198 @@ __global__ __launch_bounds__(512) void expand_stream_kernel(
 #undef EXPAND_STREAM_CASE
 }
 
+// ---------------------------------------------------------------------------
+// Mode switch (paper section 4.4.2): Wt_l[n, :] += s * Bt_l[n, :] At_l for every layer l of the model
+// in one launch, in place -- a rank-r update that reads and writes every weight once.  It is the
+// streaming expand with the roles renamed: rows of Wt_l take the place of the tokens (8 wavefronts x
+// 16 rows per workgroup, whole-line loads and stores through the wavefront's LDS patch, four stages
+// ahead), Bt_l[n, :] that of v (already bf16: one MFMA term), and At_l that of the shared slab.  At_l
+// is stored [r, K], so a stage's slab At_l[:, 64 k] is transposed on its way into LDS (16-byte loads
+// along k, 2-byte LDS stores) to the [k][rank] layout the MFMA operand reads with ds_read_b128.
+__device__ __align__(256) uint32_t merge_zero_block[64];      // what masked-out loads read (never written)
+
+template <int KS>
+__global__ __launch_bounds__(512) void merge_stream_kernel(
+    int N, int K, int r, float s, bf16_t* const* __restrict__ Wt_ptrs, int64_t ldw,
+    const bf16_t* const* __restrict__ At_ptrs, const bf16_t* const* __restrict__ Bt_ptrs,
+    int tiles_n, int tiles_k, int stages_per_tile)
+{
+    const bf16_t* zeros = reinterpret_cast<const bf16_t*>(merge_zero_block);
+    constexpr int RC = 4 * KS;
+    constexpr int SH = KS == 1 ? 2 : (KS == 2 ? 1 : 0);
+    constexpr int SLAB = 64 * RC;                 // 16-byte chunks of one stage's slab: [64 k][RC]
+    constexpr int UNITS = 32 * KS * 8;            // 16-byte loads of one stage: [32 KS ranks][8 chunks of 8 k]
+    constexpr int NLD = UNITS >= 512 ? UNITS / 512 : 1;
+    constexpr int PROW = 68;
+    uint4* lds = expand_stream_lds;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    int id = blockIdx.x;
+    const int layer = id / (tiles_n * tiles_k);
+    id -= layer * (tiles_n * tiles_k);
+    const int tile_k = id / tiles_n, tile_n = id - tile_k * tiles_n;   // neighbours share the At slab
+    bf16_t* Wt = Wt_ptrs[layer];
+    const bf16_t* At = At_ptrs[layer];
+    const bf16_t* Bt = Bt_ptrs[layer];
+    const int n0 = tile_n * 128 + wave * 16;
+    const int k0 = tile_k * stages_per_tile * 64;
+    const int k_end = min(K, k0 + stages_per_tile * 64);
+    const int n_stages = (k_end - k0 + 63) >> 6;
+
+    // the rank-side operand (MFMA columns = rows n of Wt): lane holds Bt[n0 + m][32 ks + 8 g .. +7]
+    op16 bop[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const int j = ks * 32 + g * 8;
+        bop[ks].u = ld16((n0 + m < N && j < r) ? Bt + (int64_t)(n0 + m) * r + j : zeros);
+    }
+
+    // Wt rows: instruction i of a stage covers rows 8i .. 8i+7 of the wavefront's 16, 128 bytes (64 k) each
+    const int yl_row = lane >> 3, yl_c = lane & 7;
+    bf16_t* wbase[2];
+    int w_ok = 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int n = n0 + 8 * i + yl_row;
+        const bool ok = n < N;
+        w_ok |= (int)ok << i;
+        wbase[i] = Wt + (int64_t)(ok ? n : 0) * ldw + k0 + yl_c * 8;
+    }
+    const int w_k0 = k0 + yl_c * 8;
+    auto load_w = [&](int st, int i) {
+        return ld16((((w_ok >> i) & 1) && w_k0 + st * 64 < k_end) ? wbase[i] + st * 64 : zeros);
+    };
+
+    // slab staging: unit q = rank row q / 8, columns 8 (q % 8) .. +7 of the stage
+    const bf16_t* asrc[NLD];
+    int acol[NLD], adst[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int q = (tid + i * 512) % UNITS, j = q >> 3, cc = q & 7;
+        asrc[i] = At + (int64_t)(j < r ? j : 0) * K + k0 + cc * 8;
+        acol[i] = j < r ? k0 + cc * 8 : (1 << 30);                     // ranks past r: never loaded
+        adst[i] = (j >> 3) | ((j & 7) << 8) | (cc << 16);              // rank chunk, position in it, column chunk
+    }
+    auto load_a = [&](int st, uint4 (&ra)[NLD]) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) ra[i] = ld16(acol[i] + st * 64 < k_end ? asrc[i] + st * 64 : zeros);
+    };
+    bf16_t* lds16 = reinterpret_cast<bf16_t*>(lds);
+    auto store_a = [&](int buf, const uint4 (&ra)[NLD]) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int c = adst[i] & 255, jj = (adst[i] >> 8) & 255, cc = adst[i] >> 16;
+            const uint32_t w[4] = {ra[i].x, ra[i].y, ra[i].z, ra[i].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int f = cc * 8 + e;                                  // column of the stage = slab row
+                const int slot = f * RC + (c ^ ((4 * (f >> 4) + (f & 3)) >> SH));
+                lds16[(buf * SLAB + slot) * 8 + jj] = (bf16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
+            }
+        }
+    };
+
+    float* patch = reinterpret_cast<float*>(lds + 2 * SLAB) + wave * (16 * PROW);
+    auto stage = [&](int buf, int st, uint4 (&wr)[2]) {
+        floatx4 acc[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+            const int f = 16 * (m >> 2) + 4 * b + (m & 3);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                op16 a;
+                a.u = lds[buf * SLAB + f * RC + ((4 * ks + g) ^ (m >> SH))];
+                acc[b] = mfma(a, bop[ks], acc[b]);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) *reinterpret_cast<floatx4*>(patch + m * PROW + 16 * g + 4 * b) = acc[b];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const float* pr = patch + (8 * i + yl_row) * PROW + yl_c * 8;
+            const floatx4 d0 = *reinterpret_cast<const floatx4*>(pr), d1 = *reinterpret_cast<const floatx4*>(pr + 4);
+            const uint32_t wi[4] = {wr[i].x, wr[i].y, wr[i].z, wr[i].w};
+            uint32_t out[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float e0 = fmaf(s, q < 2 ? d0[2 * q] : d1[2 * q - 4], bf16_to_f32((bf16_t)(wi[q] & 0xffffu)));
+                const float e1 = fmaf(s, q < 2 ? d0[2 * q + 1] : d1[2 * q - 3], bf16_to_f32((bf16_t)(wi[q] >> 16)));
+                out[q] = (uint32_t)f32_to_bf16(e0) | ((uint32_t)f32_to_bf16(e1) << 16);
+            }
+            if (((w_ok >> i) & 1) && w_k0 + st * 64 < k_end)
+                *reinterpret_cast<uint4*>(wbase[i] + st * 64) = uint4{out[0], out[1], out[2], out[3]};
+            wr[i] = load_w(st + 4, i);
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    uint4 ra0[NLD], ra1[NLD];
+    uint4 wr0[2], wr1[2], wr2[2], wr3[2];
+    load_a(0, ra0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) wr0[i] = load_w(0, i);
+    store_a(0, ra0);
+    load_a(1, ra0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) wr1[i] = load_w(1, i);
+    load_a(2, ra1);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) wr2[i] = load_w(2, i);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) wr3[i] = load_w(3, i);
+    __syncthreads();
+    int st = 0;
+    do {
+#define MERGE_STAGE(BUF_, S_, WR_, RA_)                  \
+        stage(BUF_, S_, WR_);                            \
+        __builtin_amdgcn_sched_barrier(0);               \
+        store_a(1 - BUF_, RA_);                          \
+        load_a((S_) + 3, RA_);                           \
+        __syncthreads();
+        MERGE_STAGE(0, st, wr0, ra0)
+        MERGE_STAGE(1, st + 1, wr1, ra1)
+        MERGE_STAGE(0, st + 2, wr2, ra0)
+        MERGE_STAGE(1, st + 3, wr3, ra1)
+#undef MERGE_STAGE
+        st += 4;
+    } while (st < n_stages);
+}
+
+hipError_t launch_merge_tiled(int32_t L, int32_t N, int32_t K, int32_t r, float s, void* const* Wt, int64_t ldw,
+                              const void* const* At, const void* const* Bt, hipStream_t stream)
+{
+    // 16 stages (1024 columns) per workgroup, fewer for small models so that the launch still has
+    // about two workgroups per CU
+    const int tiles_n = (N + 127) / 128;
+    int stages = 16;
+    while (stages > 4 && (int64_t)L * tiles_n * ((K + stages * 64 - 1) / (stages * 64)) < 512) stages /= 2;
+    const int tiles_k = (K + stages * 64 - 1) / (stages * 64);
+    const int64_t grid = (int64_t)L * tiles_n * tiles_k;
+    if (grid > 0x7fffffff) return hipErrorInvalidValue;
+    // dynamic LDS: two slabs of 64 x 32 KS ranks and the eight patches (above 64 KB for ranks > 64)
+#define MERGE_LAUNCH(KS_)                                                                                          \
+    do {                                                                                                           \
+        constexpr int lds_bytes = 2 * 64 * 4 * KS_ * 16 + 8 * 16 * 68 * 4;                                         \
+        static bool attr_set = false;                                                                              \
+        if (!attr_set) {                                                                                           \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&merge_stream_kernel<KS_>),           \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);             \
+            if (e != hipSuccess) return e;                                                                         \
+            attr_set = true;                                                                                       \
+        }                                                                                                          \
+        LORA_LAUNCH(LORA_K_MERGE, merge_stream_kernel<KS_>, dim3((unsigned)grid), dim3(512), (size_t)lds_bytes,    \
+                    stream, N, K, r, s, (bf16_t* const*)Wt, ldw, (const bf16_t* const*)At,                         \
+                    (const bf16_t* const*)Bt, tiles_n, tiles_k, stages);                                           \
+    } while (0)
+    if (r <= 32) MERGE_LAUNCH(1);
+    else if (r <= 64) MERGE_LAUNCH(2);
+    else MERGE_LAUNCH(4);
+#undef MERGE_LAUNCH
+    return hipGetLastError();
+}
+
 hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, const float* v,
                                const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream)
 {

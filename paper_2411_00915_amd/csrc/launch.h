@@ -20,6 +20,7 @@ enum lora_kernel_id {
     LORA_K_V_SPLIT,
     LORA_K_SHRINK_STREAM,
     LORA_K_EXPAND_STREAM,
+    LORA_K_MERGE,
     LORA_K_COUNT
 };
 

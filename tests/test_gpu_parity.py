@@ -383,3 +383,74 @@ def test_delora_mixture_mode():
     print(f"    mixture vs plain unmerged: normwise {nrm:.3e}", flush=True)
     assert nrm <= 6e-3
     plan.destroy()
+
+
+# ---------------------------------------------------------------- mode switch (merge / unmerge)
+def _merge_case(L, N, K, r, scale, dtype="bf16", variant=B.LORA_VARIANT_AUTO, ld_pad=0, seed=0, check_layers=None):
+    print(f"  merge case L={L} N={N} K={K} r={r} s={scale} {dtype} variant={variant} ld_pad={ld_pad}", flush=True)
+    rng = np.random.default_rng(700 + seed)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rnd = wl.round_to_bf16 if dtype == "bf16" else (lambda a: np.asarray(a, np.float32))
+    W = [rnd(rng.standard_normal((K, N), dtype=np.float32) * K ** -0.5) for _ in range(L)]
+    A = [rnd(rng.standard_normal((K, r), dtype=np.float32) * K ** -0.5) for _ in range(L)]
+    Bm = [rnd(rng.standard_normal((r, N), dtype=np.float32) * max(r, 1) ** -0.5) for _ in range(L)]
+    ldw = K + ld_pad
+    Wt = [torch.full((N, ldw), 7.0, dtype=tdt, device=DEV) for _ in range(L)]
+    for l in range(L):
+        Wt[l][:, :K] = torch.from_numpy(np.ascontiguousarray(W[l].T)).to(DEV, tdt)
+    At = [torch.from_numpy(np.ascontiguousarray(a.T)).to(DEV, tdt).contiguous() for a in A]      # [r, K]
+    Bt = [torch.from_numpy(np.ascontiguousarray(b.T)).to(DEV, tdt).contiguous() for b in Bm]     # [N, r]
+    ptrs = lambda ts: torch.tensor([t.data_ptr() for t in ts] or [0], dtype=torch.int64, device=DEV)
+    pW, pA, pB = ptrs(Wt), ptrs(At), ptrs(Bt)
+    code = B.LORA_BF16 if dtype == "bf16" else B.LORA_F32
+    B.lora_merge(L, N, K, r, scale, code, pW, ldw, pA, pB, variant)
+    torch.cuda.synchronize()
+    tol = BF16_TOL if dtype == "bf16" else F32_TOL
+    layers = range(L) if check_layers is None else check_layers
+    for l in layers:
+        got = _to_np(Wt[l])
+        assert np.all(got[:, K:] == 7.0), "written beyond column K"
+        ref = oracle.merge(W[l], A[l], Bm[l], scale)                       # [K, N] float64
+        _assert_close(got[:, :K], ref.T, tol, f"merged layer {l}")
+    # unmerge: back to the original weights, to within the rounding of the two stores
+    B.lora_merge(L, N, K, r, -scale, code, pW, ldw, pA, pB, variant)
+    torch.cuda.synchronize()
+    for l in layers:
+        got = _to_np(Wt[l])[:, :K]
+        if dtype != "bf16" or not r:
+            _assert_close(got, W[l].T.astype(np.float64), tol, f"unmerged layer {l}")
+        else:
+            # not bit-exact: the merged weight was rounded to bf16 (half a step of |W'|, relative 2^-8 at
+            # most), and so is the restored one (2^-8 of |W|)
+            nrm, _ = oracle.error_metrics(got, W[l].T)
+            bound = 2.0 ** -8 * (1.0 + np.linalg.norm(oracle.merge(W[l], A[l], Bm[l], scale)) / np.linalg.norm(W[l]))
+            print(f"    unmerged layer {l}: normwise {nrm:.3e} (bound {bound:.3e})", flush=True)
+            assert nrm <= bound
+        if dtype == "bf16" and r:
+            ulp = np.maximum(np.abs(W[l].T), 2.0 ** -126) * 2.0 ** -7       # one bf16 step at |w| (upper bound)
+            big = np.maximum(ulp, np.abs(scale) * 2.0 ** -7 * np.abs(oracle.merge(0 * W[l], A[l], Bm[l], 1.0).T))
+            assert np.all(np.abs(got - W[l].T) <= 2.5 * big + 1e-30), "unmerge is off by more than the two roundings"
+
+
+def test_mode_switch_merge_unmerge():
+    # streaming kernel: every rank class, ragged N (not a multiple of 128 / 16), ragged K (last stage, last
+    # k-chunk), padded leading dimension, several layers; then the general kernel on the same and on odd shapes
+    for seed, (L, N, K, r, s) in enumerate([(3, 192, 256, 8, 2.0), (2, 130, 1096, 96, -0.75), (1, 520, 2120, 128, 0.5),
+                                            (4, 128, 64, 32, 1.0), (2, 1000, 328, 64, 2.0), (1, 16, 8, 16, 3.0)]):
+        _merge_case(L, N, K, r, s, variant=B.LORA_VARIANT_TILED, seed=seed)
+        _merge_case(L, N, K, r, s, variant=B.LORA_VARIANT_TILED, ld_pad=8, seed=seed)
+        _merge_case(L, N, K, r, s, variant=B.LORA_VARIANT_GENERAL, seed=seed)
+    _merge_case(2, 53, 77, 5, 1.5, ld_pad=3)                     # odd everything: general kernel
+    _merge_case(2, 40, 48, 200, 0.25)                            # rank above 128: general kernel
+    _merge_case(2, 33, 40, 4, 2.0, dtype="f32")
+    _merge_case(0, 64, 64, 8, 1.0)
+    _merge_case(2, 64, 64, 0, 1.0)
+    with pytest.raises(B.LoraError):
+        _merge_case(1, 53, 77, 5, 1.0, variant=B.LORA_VARIANT_TILED)
+
+
+def test_mode_switch_model_sized():
+    # the paper's mode-switch workload: every layer of a 7B-class model (32 x 4096 x 4096, rank 64) in one launch;
+    # two layers are compared with the oracle in full
+    _merge_case(32, 4096, 4096, 64, 2.0, check_layers=[0, 31])
+

@@ -168,6 +168,16 @@ def test_compute_calls_reject_bad_arguments_without_a_gpu():
     assert L.lora_base_gemm(4, 0, 4, B.LORA_BF16, 256, 8, 256, 8, 256, 8, None) == B.LORA_ERR_INVALID_ARG
     assert L.lora_fused_forward(p.handle, 256, 64, 256, 64, 256, 256, 256, 64, 256, 16, None) == B.LORA_ERR_WORKSPACE
     p.destroy()
+    # lora_merge(L, n, k, rank, scale, dtype, variant, Wt_ptrs, ldw, At_ptrs, Bt_ptrs, stream)
+    f = ctypes.c_float
+    assert L.lora_merge(2, 64, 64, 8, f(1.0), B.LORA_BF16, B.LORA_VARIANT_AUTO, None, 64, 256, 256, None) == B.LORA_ERR_INVALID_ARG
+    assert L.lora_merge(2, 64, 64, 8, f(1.0), B.LORA_BF16, B.LORA_VARIANT_AUTO, 256, 32, 256, 256, None) == B.LORA_ERR_INVALID_ARG   # ldw < k
+    assert L.lora_merge(2, 64, 64, 8, f(float("nan")), B.LORA_BF16, B.LORA_VARIANT_AUTO, 256, 64, 256, 256, None) == B.LORA_ERR_INVALID_ARG
+    assert L.lora_merge(2, 64, 64, 300, f(1.0), B.LORA_BF16, B.LORA_VARIANT_AUTO, 256, 64, 256, 256, None) == B.LORA_ERR_INVALID_ARG  # rank
+    assert L.lora_merge(2, 64, 60, 8, f(1.0), B.LORA_BF16, B.LORA_VARIANT_TILED, 256, 64, 256, 256, None) == B.LORA_ERR_UNSUPPORTED   # k % 8
+    assert L.lora_merge(2, 64, 64, 8, f(1.0), B.LORA_F32, B.LORA_VARIANT_TILED, 256, 64, 256, 256, None) == B.LORA_ERR_UNSUPPORTED
+    assert L.lora_merge(0, 64, 64, 8, f(1.0), B.LORA_BF16, B.LORA_VARIANT_AUTO, None, 64, None, None, None) == B.LORA_OK             # no layers
+    assert L.lora_merge(2, 64, 64, 0, f(1.0), B.LORA_BF16, B.LORA_VARIANT_AUTO, None, 64, None, None, None) == B.LORA_OK             # rank 0
 
 
 def test_tuning_roundtrip_changes_tiles():

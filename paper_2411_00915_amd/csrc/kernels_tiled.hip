@@ -277,20 +277,18 @@ __device__ __forceinline__ void shrink_stream_tile(
     const int k_begin = p_begin << 5, k_end = min(K, p_end << 5);
     const int n_stages = (p_end - p_begin + 3) >> 2;
 
-    // At staging: chunk q of a slab = row q/16, 16-byte column q%16
-    const bf16_t* asrc[NLD];
-    int aslot[NLD], acol[NLD];
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-        const int q = (tid + i * 512) % SLAB, j = q >> 4, c = q & 15;
-        asrc[i] = At + (int64_t)(tile.c0 + (j < tile.cn ? j : 0)) * K + c * 8;
-        aslot[i] = j * 16 + (c ^ (j & 15));
-        acol[i] = c * 8;
-    }
+    // At staging: chunk q of a slab = row q/16, 16-byte column q%16; thread's unit i is row j0 + 32 i, same column
+    const int a_q = tid % SLAB, a_j0 = a_q >> 4, a_c = a_q & 15;
+    const bf16_t* a_base = At + (int64_t)tile.c0 * K + a_c * 8;
+    const int a_slot0 = a_j0 * 16 + (a_c ^ (a_j0 & 15));       // rows 32 apart share the swizzle
     auto load_a = [&](int s, uint4 (&ra)[NLD]) {
         const int k0 = k_begin + s * 128;
+        const bool in = k0 + a_c * 8 < k_end;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) ra[i] = ld16_global(k0 + acol[i] < k_end ? asrc[i] + k0 : zeros);
+        for (int i = 0; i < NLD; ++i) {
+            const int j = a_j0 + 32 * i;
+            ra[i] = ld16(in ? a_base + (int64_t)(j < tile.cn ? j : 0) * K + k0 : zeros);
+        }
     };
     auto load_x1 = [&](int s, int i) {
         const int k0 = k_begin + s * 128;
@@ -298,7 +296,7 @@ __device__ __forceinline__ void shrink_stream_tile(
     };
     auto store_a = [&](int buf, const uint4 (&ra)[NLD]) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) lds[buf * SLAB + aslot[i]] = ra[i];
+        for (int i = 0; i < NLD; ++i) lds[buf * SLAB + a_slot0 + 32 * 16 * i] = ra[i];
     };
     floatx4 acc[JB];
 #pragma unroll
@@ -314,18 +312,28 @@ __device__ __forceinline__ void shrink_stream_tile(
         __builtin_amdgcn_wave_barrier();         // the patch is exchanged between lanes of this wavefront only
 #pragma unroll
         for (int i = 0; i < UW; ++i) {
-            op16 b, a[JB];
+            op16 b;
             b.u = xw[m * LPR + ((4 * i + g) ^ (m % LPR))];
             const int c = (kw * UW + i) * 4 + g;
+            // the slab's LDS reads go out four rank blocks at a time, ahead of their MFMAs
+            constexpr int JG = JB < 4 ? JB : 4;
 #pragma unroll
-            for (int jb = 0; jb < JB; ++jb) a[jb].u = lds[buf * SLAB + (jb * 16 + m) * 16 + (c ^ m)];
+            for (int j0 = 0; j0 < JB; j0 += JG) {
+                op16 a[JG];
 #pragma unroll
-            for (int jb = 0; jb < JB; ++jb) acc[jb] = mfma(a[jb], b, acc[jb]);
+                for (int jb = 0; jb < JG; ++jb) a[jb].u = lds[buf * SLAB + ((j0 + jb) * 16 + m) * 16 + (c ^ m)];
+#pragma unroll
+                for (int jb = 0; jb < JG; ++jb) acc[j0 + jb] = mfma(a[jb], b, acc[j0 + jb]);
+                if (JB > JG) __builtin_amdgcn_sched_barrier(0);
+            }
         }
         __builtin_amdgcn_wave_barrier();
     };
 
-    uint4 ra0[NLD], ra1[NLD];
+    // slab registers: two sets (a slab is requested three stages before it is multiplied), or one set
+    // (two stages) for the widest tiles, whose register count decides how many workgroups fit a CU
+    constexpr bool TWO_SETS = JB < 8;
+    uint4 ra0[NLD], ra1[TWO_SETS ? NLD : 1];
     op16 xr0[UW], xr1[UW];
     // the loads are issued in the order the stage loop keeps them in flight and consumes them, and the
     // loop has no guard branch, so every wait in it can name exactly the loads it needs
@@ -336,21 +344,26 @@ __device__ __forceinline__ void shrink_stream_tile(
     load_a(1, ra0);
 #pragma unroll
     for (int i = 0; i < UW; ++i) xr1[i].u = load_x1(1, i);
-    load_a(2, ra1);
+    if constexpr (TWO_SETS) load_a(2, ra1);
     __syncthreads();
-    // stage s computes from slab buffer s%2; the slab of stage s+1 (in registers since two stages ago)
-    // goes to the other buffer after the MFMAs, and the slab of stage s+3 is requested
+    // stage s computes from slab buffer s%2; the slab of stage s+1 goes from its registers to the other
+    // buffer after the MFMAs, and the next slab is requested into them
     int s = 0;
     do {
         compute(0, xr0, s + 2);
         __builtin_amdgcn_sched_barrier(0);
         store_a(1, ra0);
-        load_a(s + 3, ra0);
+        load_a(TWO_SETS ? s + 3 : s + 2, ra0);
         __syncthreads();
         compute(1, xr1, s + 3);        // past the last stage: zeros
         __builtin_amdgcn_sched_barrier(0);
-        store_a(0, ra1);
-        load_a(s + 4, ra1);
+        if constexpr (TWO_SETS) {
+            store_a(0, ra1);
+            load_a(s + 4, ra1);
+        } else {
+            store_a(0, ra0);
+            load_a(s + 3, ra0);
+        }
         __syncthreads();
         s += 2;
     } while (s < n_stages);

@@ -454,3 +454,39 @@ def test_mode_switch_model_sized():
     # two layers are compared with the oracle in full
     _merge_case(32, 4096, 4096, 64, 2.0, check_layers=[0, 31])
 
+
+# ---------------------------------------------------------------- vision task heads
+def test_vision_task_heads_batched_through_the_shrink():
+    # Vision task heads (paper section 4.2.2): a linear layer per adapter that maps the final feature of a
+    # request's last token to C_a task outputs; heads of different width run in one batch.  In this library
+    # that is the shrink with "rank" = C_a, Ht_a stored [C_a, K] like At_a, and scale 1: logits land in v.
+    for seed, (classes, variant) in enumerate([((2, 5, 10, 101, 174, 256), B.LORA_VARIANT_AUTO),     # general kernels
+                                               ((8, 16, 24, 64, 128), B.LORA_VARIANT_TILED)]):      # MFMA kernels
+        w = wl.random_case(900 + seed, 96, 4096, 64, len(classes), classes, max_seg=1, frac_none=0.1,
+                           scales=(1.0,), with_w=False)
+        w.adapter_rank = np.asarray(classes, dtype=np.int32)         # one head of every width
+        rng = np.random.default_rng(910 + seed)
+        w.A = [wl.round_to_bf16(rng.standard_normal((w.K, c), dtype=np.float32) * w.K ** -0.5) for c in classes]
+        w.B = [np.zeros((c, w.N), np.float32) for c in classes]
+        dl = device.to_device(w, DEV, with_w=False)
+        plan = device.make_plan(w, variant)
+        R, v_bytes, _ = B.lora_plan_query(plan)
+        P = B.lora_plan_export(plan)["v_parts"]
+        v = torch.full((P, w.T, R), -12345.0, dtype=torch.float32, device=DEV)
+        B.lora_shrink(plan, dl.x, w.K, dl.At_ptrs, v)
+        torch.cuda.synchronize()
+        tok = oracle.token_adapter(w.T, w.seg_indptr, w.seg_adapter)
+        ref = oracle.shrink(w.x, tok, oracle.Adapters(w.adapter_rank, w.adapter_scale, w.A, w.B), apply_scale=True, R=R)
+        got = _to_np(v)
+        width = np.where(tok >= 0, w.adapter_rank[np.clip(tok, 0, None)], 0)
+        valid = np.arange(R)[None, :] < width[:, None]
+        logits = np.where(valid, got.astype(np.float64).sum(axis=0), 0.0)
+        assert np.all(got[0][~valid] == -12345.0), "written outside a head's C_a outputs"
+        _assert_close(logits, ref, V_TOL, f"task-head logits, widths {classes}")
+        # the decision a head exists for: the arg max agrees wherever the oracle's top two are not a near tie
+        for t in np.nonzero(width > 1)[0]:
+            top = np.sort(ref[t, :width[t]])[-2:]
+            if top[1] - top[0] > 1e-3 * max(1.0, abs(top[1])):
+                assert int(np.argmax(logits[t, :width[t]])) == int(np.argmax(ref[t, :width[t]]))
+        plan.destroy()
+

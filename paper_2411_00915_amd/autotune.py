@@ -5,7 +5,8 @@ candidate offline (section 4.3.2, Algorithm 2: loop over input shapes, ranks
 and tile configurations, profile, keep the best).  This is the same loop for
 this library: for a workload shape it sweeps a grid of planner tunables, times
 the delta path with the library's per-kernel timers on rotating buffers, and
-prints the best setting; `--apply` prints a `lora_tuning_set(...)` line for it.
+prints the best setting with a `lora_tuning_set(...)` line for it; `--out FILE` also stores it in a
+shape-keyed table (tuning_table.py) that `apply_for_shape` consults before planning.
 
     python -m paper_2411_00915_amd.autotune --workload cfg2
     python -m paper_2411_00915_amd.autotune --workload cfg3 --grid '{"expand_wave_bytes_big": [65536, 131072]}'
@@ -18,13 +19,13 @@ import json
 
 DEFAULT_GRIDS = {
     "decode": {"shrink_target_wgs": [256, 512, 768], "expand_wave_bytes": [8192, 16384, 32768], "fused_delay": [1, 3, 5]},
-    "prefill": {"shrink_tb4_min_rows": [64, 128], "shrink_target_wgs": [384, 768],
-                "expand_wave_bytes_big": [65536, 131072, 262144]},
+    "prefill": {"shrink_stream_wgs": [1, 512, 2048], "expand_stream_stages": [8, 16, 32]},
 }
 
 
 def measure(w, layers, v, B, path="delta", reps=3):
     """Mean GPU microseconds per layer of the delta path under the current tunables."""
+    # (v is sized for four K parts, the most a plan can ask for)
     import torch
     from . import device
     plan = device.make_plan(w)
@@ -47,6 +48,7 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg4d", "cfg5"])
     ap.add_argument("--layers", type=int, default=8)
     ap.add_argument("--grid", default=None, help="JSON object: tunable name -> list of values")
+    ap.add_argument("--out", default=None, help="shape-keyed table (JSON) to store the best setting in")
     args = ap.parse_args()
 
     import torch
@@ -86,6 +88,11 @@ def main():
     print(json.dumps({"workload": w.name, "best_us_per_layer": round(best_us, 2), "best": best,
                       "defaults_us_per_layer": round(base_us[0], 2) if base_us else None,
                       "apply": "lora_tuning_set(" + ", ".join(f"{k}={val}" for k, val in best.items()) + ")"}))
+    if args.out:
+        from . import tuning_table
+        key = tuning_table.shape_key(w.T, w.K, w.N, int(w.adapter_rank.max()))
+        tuning_table.store(key, best, args.out)
+        print(f"stored under {key} in {args.out}")
 
 
 if __name__ == "__main__":

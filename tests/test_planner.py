@@ -207,3 +207,28 @@ def test_library_exports_every_declared_symbol():
     for n in sorted(names):
         assert hasattr(B._lib, n), f"{n} is declared in lora_abi.h but not exported"
     assert names == set(B.EXPORTED)
+
+
+def test_shape_keyed_tuning_table_roundtrip(tmp_path):
+    from paper_2411_00915_amd import tuning_table as tt
+    path = str(tmp_path / "table.json")
+    before = B.lora_tuning_get()
+    try:
+        assert tt.shape_key(300, 4096, 4096, 64) == "T512_K4096_N4096_R64" and tt.shape_key(512, 8, 8, 8).startswith("T512_")
+        tt.store(tt.shape_key(4096, 4096, 4096, 64), {"expand_stream_stages": 8, "shrink_stream_wgs": 2048}, path)
+        tt.store(tt.shape_key(256, 4096, 4096, 64), {"fused_delay": 5}, path)
+        assert tt.apply_for_shape(3000, 4096, 4096, 64, path) == {"expand_stream_stages": 8, "shrink_stream_wgs": 2048}
+        now = B.lora_tuning_get()
+        assert now["expand_stream_stages"] == 8 and now["shrink_stream_wgs"] == 2048 and now["fused_delay"] == before["fused_delay"]
+        assert tt.apply_for_shape(17, 64, 64, 8, path, defaults=before) is None      # no entry: defaults stay
+        assert B.lora_tuning_get() == before
+        with open(path, "w") as f:
+            f.write('{"T1_K1_N1_R1": {"no_such_tunable": 1}}')
+        with pytest.raises(KeyError):
+            tt.load(path)
+        # the table that ships with the package loads and names only known tunables
+        shipped = tt.load()
+        assert all(set(e) <= set(B.TUNING_FIELDS) for e in shipped.values())
+    finally:
+        B.lora_tuning_set(**before)
+

@@ -254,22 +254,28 @@ __device__ __forceinline__ void shrink_stream_tile(
     const bool row_ok = row < tile.nrows;
     const int tok = perm[tile.row0 + (row_ok ? row : 0)];
 
-    // x loads: the wavefront's span of a stage is 64 UW bytes per row = LPR lanes; instruction i
-    // fetches rows i*RPI .. i*RPI+RPI-1 of the block
-    constexpr int LPR = 4 * UW, RPI = 64 / LPR;
+    // x loads: the wavefront's span of a stage is 64 UW bytes per row = CPR 16-byte chunks.  An instruction
+    // takes 128 bytes (LPR = 8 lanes) of 8 rows -- whole cache lines -- so a lane meets only NP = 2 rows
+    // (two pointers), H column blocks each; a span of 64 bytes (UW = 1) takes 16 rows x 64 bytes instead.
+    constexpr int CPR = 4 * UW;
+    constexpr int H = UW >= 2 ? UW / 2 : 1, NP = UW / H;
+    constexpr int LPR = UW >= 2 ? 8 : 4, RPI = 64 / LPR;
     const int xl_row = lane / LPR, xl_c = lane % LPR;
-    const bf16_t* xsrc[UW];
+    const bf16_t* xsrc[NP];
     int x_ok = 0;
-    uint4* xw = lds + 2 * SLAB + wave * (16 * LPR);          // this wavefront's patch: [16 rows][LPR], swizzled
-    int wslot[UW];
+    uint4* xw = lds + 2 * SLAB + wave * (16 * CPR);          // this wavefront's patch: [16 rows][CPR], swizzled
 #pragma unroll
-    for (int i = 0; i < UW; ++i) {
-        const int r16 = i * RPI + xl_row, r = blk * 16 + r16;
+    for (int p = 0; p < NP; ++p) {
+        const int r = blk * 16 + p * RPI + xl_row;
         const bool ok = r < tile.nrows;
-        x_ok |= (int)ok << i;
-        xsrc[i] = x + (int64_t)perm[tile.row0 + (ok ? r : 0)] * ldx + (kw * LPR + xl_c) * 8;
-        wslot[i] = r16 * LPR + (xl_c ^ (r16 % LPR));
+        x_ok |= (int)ok << p;
+        xsrc[p] = x + (int64_t)perm[tile.row0 + (ok ? r : 0)] * ldx + (kw * CPR + xl_c) * 8;
     }
+    // instruction i: row group i / H, column block i % H; where its 16 bytes go in the patch
+    auto wslot = [&](int i) {
+        const int r16 = (i / H) * RPI + xl_row, c = (i % H) * LPR + xl_c;
+        return r16 * CPR + (c ^ (r16 % CPR));
+    };
 
     const int steps = (K + 31) >> 5;
     const int kpart = (tile.shape >> 8) & 15, kparts = (tile.shape >> 12) & 15;
@@ -291,8 +297,8 @@ __device__ __forceinline__ void shrink_stream_tile(
         }
     };
     auto load_x1 = [&](int s, int i) {
-        const int k0 = k_begin + s * 128;
-        return ld16_global((((x_ok >> i) & 1) && k0 + (kw * LPR + xl_c) * 8 < k_end) ? xsrc[i] + k0 : zeros);
+        const int k0 = k_begin + s * 128 + (i % H) * (LPR * 8);
+        return ld16_global((((x_ok >> (i / H)) & 1) && k0 + (kw * CPR + xl_c) * 8 < k_end) ? xsrc[i / H] + k0 : zeros);
     };
     auto store_a = [&](int buf, const uint4 (&ra)[NLD]) {
 #pragma unroll
@@ -306,14 +312,14 @@ __device__ __forceinline__ void shrink_stream_tile(
     // k-step the LDS reads of x and of the slab, and the MFMAs
     auto compute = [&](int buf, op16 (&xr)[UW], int s_next) {
 #pragma unroll
-        for (int i = 0; i < UW; ++i) xw[wslot[i]] = xr[i].u;
+        for (int i = 0; i < UW; ++i) xw[wslot(i)] = xr[i].u;
 #pragma unroll
         for (int i = 0; i < UW; ++i) xr[i].u = load_x1(s_next, i);
         __builtin_amdgcn_wave_barrier();         // the patch is exchanged between lanes of this wavefront only
 #pragma unroll
         for (int i = 0; i < UW; ++i) {
             op16 b;
-            b.u = xw[m * LPR + ((4 * i + g) ^ (m % LPR))];
+            b.u = xw[m * CPR + ((4 * i + g) ^ (m % CPR))];
             const int c = (kw * UW + i) * 4 + g;
             // the slab's LDS reads go out four rank blocks at a time, ahead of their MFMAs
             constexpr int JG = JB < 4 ? JB : 4;
@@ -330,42 +336,37 @@ __device__ __forceinline__ void shrink_stream_tile(
         __builtin_amdgcn_wave_barrier();
     };
 
-    // slab registers: two sets (a slab is requested three stages before it is multiplied), or one set
-    // (two stages) for the widest tiles, whose register count decides how many workgroups fit a CU
-    constexpr bool TWO_SETS = JB < 8;
-    uint4 ra0[NLD], ra1[TWO_SETS ? NLD : 1];
-    op16 xr0[UW], xr1[UW];
+    // x registers: NX stages in flight per wavefront (4 KB each); the widest tiles take fewer so that
+    // their register count still lets a second workgroup onto the CU
+    constexpr int NX = 2;
+    uint4 ra[NLD];
+    op16 xr[NX][UW];
     // the loads are issued in the order the stage loop keeps them in flight and consumes them, and the
     // loop has no guard branch, so every wait in it can name exactly the loads it needs
-    load_a(0, ra0);
+    load_a(0, ra);
 #pragma unroll
-    for (int i = 0; i < UW; ++i) xr0[i].u = load_x1(0, i);
-    store_a(0, ra0);
-    load_a(1, ra0);
+    for (int i = 0; i < UW; ++i) xr[0][i].u = load_x1(0, i);
+    store_a(0, ra);
+    load_a(1, ra);
 #pragma unroll
-    for (int i = 0; i < UW; ++i) xr1[i].u = load_x1(1, i);
-    if constexpr (TWO_SETS) load_a(2, ra1);
+    for (int u = 1; u < NX; ++u)
+#pragma unroll
+        for (int i = 0; i < UW; ++i) xr[u][i].u = load_x1(u, i);
     __syncthreads();
     // stage s computes from slab buffer s%2; the slab of stage s+1 goes from its registers to the other
-    // buffer after the MFMAs, and the next slab is requested into them
+    // buffer after the MFMAs, and the slab after that is requested into them.  Stages past the last one
+    // work on zeros.
     int s = 0;
     do {
-        compute(0, xr0, s + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        store_a(1, ra0);
-        load_a(TWO_SETS ? s + 3 : s + 2, ra0);
-        __syncthreads();
-        compute(1, xr1, s + 3);        // past the last stage: zeros
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (TWO_SETS) {
-            store_a(0, ra1);
-            load_a(s + 4, ra1);
-        } else {
-            store_a(0, ra0);
-            load_a(s + 3, ra0);
+#pragma unroll
+        for (int u = 0; u < NX; ++u) {
+            compute(u & 1, xr[u], s + u + NX);
+            __builtin_amdgcn_sched_barrier(0);
+            store_a((u + 1) & 1, ra);
+            load_a(s + u + 2, ra);
+            __syncthreads();
         }
-        __syncthreads();
-        s += 2;
+        s += NX;
     } while (s < n_stages);
 
     const float s_a = __int_as_float(tile.reserved1);

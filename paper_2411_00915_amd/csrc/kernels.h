@@ -31,6 +31,8 @@ struct lora_dev_tables {
     const int32_t* extra_ptr256;
     const int32_t* extra256;
     const void* zeros;             // 256 zero bytes
+    const int32_t* shrink_rows;    // single-launch decode kernel: 16 tokens per shrink / expand tile, padded
+    const int32_t* expand_rows;
 };
 
 // general VALU family (any dtype, any alignment)

@@ -46,6 +46,8 @@ __device__ __forceinline__ floatx4 mfma(const op16& a, const op16& b, floatx4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
 }
 
+__device__ __align__(256) uint32_t lora_zero_block[64];       // what masked-out loads read (never written)
+
 // ---------------------------------------------------------------------------
 // Shrink.  One workgroup per tile = (16*TB tokens of one adapter) x (16*JB rank
 // rows of At_a) x the whole K range.  MFMA rows = rank rows, MFMA columns =
@@ -54,11 +56,13 @@ __device__ __forceinline__ floatx4 mfma(const op16& a, const op16& b, floatx4 c)
 // LDS, are scaled by s_a and stored once (deterministic, no atomics).
 // PUBLISH: v is stored with agent-scope write-through stores, so that workgroups on other XCDs can
 // read it during the same launch without an L2 write-back
+// `rows`: token of the tile's row i at rows[i] (perm + tile.row0).  PUBLISH: rows is the padded 16-entry
+// table of the single-launch kernel instead, whose address does not depend on the tile descriptor.
 template <int TB, int JB, int U, bool PUBLISH = false>
 __device__ __forceinline__ void shrink_tile(
-    const lora_tile tile, const int32_t* __restrict__ perm,
+    const lora_tile tile, const int32_t* __restrict__ rows,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
-    float* __restrict__ v, lora_vspec vsp, floatx4* lds)
+    float* __restrict__ v, lora_vspec vsp, floatx4* lds, uint4* patch = nullptr)
 {
     // U = k-steps whose loads are issued together before any of them is consumed
     const int R = vsp.R;
@@ -69,8 +73,8 @@ __device__ __forceinline__ void shrink_tile(
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
         int row = tb * 16 + m;
-        if (row >= tile.nrows) row = 0;                 // padding lanes re-read a valid row; never stored
-        xrow[tb] = x + (int64_t)perm[tile.row0 + row] * ldx + g * 8;
+        if (!PUBLISH && row >= tile.nrows) row = 0;     // padding lanes re-read a valid row; never stored
+        xrow[tb] = x + (int64_t)rows[row] * ldx + g * 8;
     }
     const bf16_t* arow[JB];
 #pragma unroll
@@ -93,7 +97,7 @@ __device__ __forceinline__ void shrink_tile(
             const int row = (blk / JB) * 16 + (l & 15);
             const int j = (blk % JB) * 16 + 4 * (l >> 4);
             if (row < tile.nrows && j < tile.cn) {
-                t_out = perm[tile.row0 + row];
+                t_out = rows[row];
                 j_out = tile.c0 + j;
             }
         }
@@ -116,6 +120,47 @@ __device__ __forceinline__ void shrink_tile(
     const int kmax = K - g * 8;                          // chunk at offset k is inside the row iff k < kmax
 
     int s = s_begin;
+    // Single-launch decode kernel (16-token tiles, 8 loads of At per round): At is fetched as whole cache
+    // lines -- 4 rows x 256 bytes per instruction instead of the MFMA operand shape, 16 rows x 64 bytes,
+    // which would ask for half of each line twice; the launch is bound by the CUs' rate of line requests --
+    // and reaches the operand layout through a 4 KB LDS patch of the wavefront's own.  A unit of four
+    // instructions = 16 rank rows x four k-steps: the two column halves of the round (JB = 1) or the
+    // two rank blocks (JB = 2).
+    if constexpr (PUBLISH && TB == 1 && JB * U == 8) {
+        const bf16_t* zeros = reinterpret_cast<const bf16_t*>(lora_zero_block);
+        const int lr = lane >> 4, lc = lane & 15;
+        for (; s + U <= s_end; s += U) {
+            uint4 raw[8];
+            op16 xa[U];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int unit = i >> 2;
+                int j = (JB == 2 ? unit * 16 : 0) + 4 * (i & 3) + lr;
+                if (j >= tile.cn) j = 0;
+                const int k = ((s + (JB == 1 ? 4 * unit : 0)) << 5) + lc * 8;
+                raw[i] = ld16(k < K ? At + (int64_t)(tile.c0 + j) * K + k : zeros);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = (s + u) << 5;
+                xa[u].u = k < kmax ? ld16(xrow[0] + k) : uint4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int unit = 0; unit < 2; ++unit) {
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int q = 0; q < 4; ++q) patch[(4 * q + lr) * 16 + (lc ^ (4 * q + lr))] = raw[unit * 4 + q];
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    op16 a;
+                    a.u = patch[m * 16 + ((4 * t + g) ^ m)];
+                    const int jb = JB == 2 ? unit : 0;
+                    acc[0][jb] = mfma(a, xa[JB == 1 ? 4 * unit + t : t], acc[0][jb]);
+                }
+            }
+        }
+    }
     for (; s + U <= s_end; s += U) {
         op16 xa[U][TB], aa[U][JB];
 #pragma unroll
@@ -193,8 +238,8 @@ __global__ __launch_bounds__(1024) void shrink_tiled_small_kernel(
     const lora_tile tile = tiles[blockIdx.x];
     const bf16_t* At = At_ptrs[tile.adapter];
     const int jb = (tile.shape >> 4) & 15;
-    if (jb == 1) shrink_tile<1, 1, 8>(tile, perm, x, ldx, At, K, v, R, shrink_lds);
-    else shrink_tile<1, 2, 4>(tile, perm, x, ldx, At, K, v, R, shrink_lds);
+    if (jb == 1) shrink_tile<1, 1, 8>(tile, perm + tile.row0, x, ldx, At, K, v, R, shrink_lds);
+    else shrink_tile<1, 2, 4>(tile, perm + tile.row0, x, ldx, At, K, v, R, shrink_lds);
 }
 
 __global__ __launch_bounds__(512) void shrink_tiled_kernel(
@@ -206,7 +251,7 @@ __global__ __launch_bounds__(512) void shrink_tiled_kernel(
     const bf16_t* At = At_ptrs[tile.adapter];
     const int tb = tile.shape & 15, jb = (tile.shape >> 4) & 15;
 #define SHRINK_CASE(TB_, JB_, U_) \
-    if (tb == TB_ && jb == JB_) { shrink_tile<TB_, JB_, U_>(tile, perm, x, ldx, At, K, v, R, shrink_lds); return; }
+    if (tb == TB_ && jb == JB_) { shrink_tile<TB_, JB_, U_>(tile, perm + tile.row0, x, ldx, At, K, v, R, shrink_lds); return; }
     SHRINK_CASE(1, 1, 8)
     SHRINK_CASE(1, 2, 4)
     SHRINK_CASE(1, 3, 4)
@@ -865,15 +910,13 @@ __global__ __launch_bounds__(512) void expand_stream_kernel(
 // ahead), Bt_l[n, :] that of v (already bf16: one MFMA term), and At_l that of the shared slab.  At_l
 // is stored [r, K], so a stage's slab At_l[:, 64 k] is transposed on its way into LDS (16-byte loads
 // along k, 2-byte LDS stores) to the [k][rank] layout the MFMA operand reads with ds_read_b128.
-__device__ __align__(256) uint32_t merge_zero_block[64];      // what masked-out loads read (never written)
-
 template <int KS>
 __global__ __launch_bounds__(512) void merge_stream_kernel(
     int N, int K, int r, float s, bf16_t* const* __restrict__ Wt_ptrs, int64_t ldw,
     const bf16_t* const* __restrict__ At_ptrs, const bf16_t* const* __restrict__ Bt_ptrs,
     int tiles_n, int tiles_k, int stages_per_tile)
 {
-    const bf16_t* zeros = reinterpret_cast<const bf16_t*>(merge_zero_block);
+    const bf16_t* zeros = reinterpret_cast<const bf16_t*>(lora_zero_block);
     constexpr int RC = 4 * KS;
     constexpr int SH = KS == 1 ? 2 : (KS == 2 ? 1 : 0);
     constexpr int SLAB = 64 * RC;                 // 16-byte chunks of one stage's slab: [64 k][RC]
@@ -1127,7 +1170,7 @@ __device__ __forceinline__ float ld_agent_f(const float* p)
 
 template <int KS>
 __device__ __forceinline__ void fused_expand_item(
-    const lora_tile tile, const int32_t* __restrict__ perm, const float* __restrict__ scale,
+    const lora_tile tile, const int32_t* __restrict__ rows, const float* __restrict__ scale,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
     const float* v, lora_vspec vsp, const bf16_t* __restrict__ Bt, bf16_t* __restrict__ y, int64_t ldy, int N,
     float beta, lora_sync_slot* sync, int spin_limit, int delay, float* vt, int* flag)
@@ -1148,7 +1191,7 @@ __device__ __forceinline__ void fused_expand_item(
     const int row_in_chunk = 16 * (m >> 2) + (m & 3);
 
     const bool tok_ok = m < tile.nrows;
-    const int tok = perm[tile.row0 + (tok_ok ? m : 0)];
+    const int tok = rows[m];                             // padded table: needs nothing from the descriptor
 
     auto load_b = [&](int c, op16 (&bop)[4][KS]) {
         const int n_base = tile.c0 + (c << 6);
@@ -1201,7 +1244,7 @@ __device__ __forceinline__ void fused_expand_item(
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         const int row = threadIdx.x >> 4, j4 = (threadIdx.x & 15) * 4;
         if (row < tile.nrows && j4 < r) {
-            const int t = perm[tile.row0 + row];
+            const int t = rows[row];
             float pv[4][4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {                  // all parts are requested before the first add
@@ -1217,7 +1260,7 @@ __device__ __forceinline__ void fused_expand_item(
         const float s_a = scale[tile.adapter];
         for (int idx = wave; idx < tile.nrows * r; idx += 4) {
             const int row = idx / r, j = idx - row * r;
-            const bf16_t* xr = x + (int64_t)perm[tile.row0 + row] * ldx;
+            const bf16_t* xr = x + (int64_t)rows[row] * ldx;
             const bf16_t* ar = At + (int64_t)j * K;
             float acc = 0.f;
             for (int k = lane * 8; k < K; k += 512) {
@@ -1297,22 +1340,39 @@ __device__ __forceinline__ void fused_expand_item(
     }
 }
 
-__global__ __launch_bounds__(256) void delta_fused_small_kernel(
+// (five wavefronts per SIMD: the whole launch of a decode batch is then resident at once, expand blocks
+// included, so none of them starts its chain of loads only after a shrink block has retired)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) void delta_fused_small_kernel(
     const lora_tile* __restrict__ shrink_tiles, int n_shrink, const lora_tile* __restrict__ expand_tiles,
-    const int32_t* __restrict__ perm, const float* __restrict__ scale,
+    const int32_t* __restrict__ shrink_rows, const int32_t* __restrict__ expand_rows, const float* __restrict__ scale,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* const* __restrict__ At_ptrs, int K,
     float* v, lora_vspec vsp, const bf16_t* const* __restrict__ Bt_ptrs,
-    bf16_t* __restrict__ y, int64_t ldy, int N, float beta, lora_sync_slot* sync, int spin_limit, int delay)
+    bf16_t* __restrict__ y, int64_t ldy, int N, float beta, lora_sync_slot* sync, int spin_limit, int delay,
+    int n_adapters)
 {
     __shared__ floatx4 lds[4 * 2 * 64];      // 8 KB: shrink reduction buffer, or v rows [16][64] of an expand tile
+    __shared__ uint4 patches[4 * 256];       // 16 KB: one 4 KB patch per wavefront (whole-line loads -> MFMA operands)
     __shared__ int flag;
     const int b = blockIdx.x;
+    // With at most 64 adapters every lane fetches one entry of the pointer table while the tile
+    // descriptor is still on its way; the tile's entry is then picked out of the wavefront's registers.
+    // The workgroup's chain of dependent loads is descriptor / tokens / pointers -> data.
+    const bool table_fits = n_adapters <= 64;
+    const int lane_a = min((int)(threadIdx.x & 63), n_adapters - 1);
+    auto pick = [&](uint64_t entry, int a) {
+        const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)entry, a);
+        const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(entry >> 32), a);
+        return reinterpret_cast<const bf16_t*>((uint64_t)lo | ((uint64_t)hi << 32));
+    };
     if (b < n_shrink) {
+        const uint64_t a_entry = table_fits ? reinterpret_cast<uint64_t>(At_ptrs[lane_a]) : 0;
         const lora_tile tile = shrink_tiles[b];
-        const bf16_t* At = At_ptrs[tile.adapter];
+        const bf16_t* At = table_fits ? pick(a_entry, tile.adapter) : At_ptrs[tile.adapter];
+        const int32_t* rows = shrink_rows + (int64_t)b * 16;
         const int jb = (tile.shape >> 4) & 15;
-        if (jb == 1) shrink_tile<1, 1, 8, true>(tile, perm, x, ldx, At, K, v, vsp, lds);
-        else shrink_tile<1, 2, 4, true>(tile, perm, x, ldx, At, K, v, vsp, lds);
+        uint4* patch = patches + (threadIdx.x >> 6) * 256;
+        if (jb == 1) shrink_tile<1, 1, 8, true>(tile, rows, x, ldx, At, K, v, vsp, lds, patch);
+        else shrink_tile<1, 2, 4, true>(tile, rows, x, ldx, At, K, v, vsp, lds, patch);
         // publish: the write-through stores of every thread have completed before the
         // block's count is added (no L2 write-back: that would cost microseconds per block)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -1320,14 +1380,16 @@ __global__ __launch_bounds__(256) void delta_fused_small_kernel(
         if (threadIdx.x == 0)
             __hip_atomic_fetch_add(&sync[(unsigned int)tile.shape >> 16].done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     } else {
+        const uint64_t b_entry = table_fits ? reinterpret_cast<uint64_t>(Bt_ptrs[lane_a]) : 0;
         const lora_tile tile = expand_tiles[b - n_shrink];
-        const bf16_t* Bt = Bt_ptrs[tile.adapter];
-        const bf16_t* At = At_ptrs[tile.adapter];
+        const bf16_t* Bt = table_fits ? pick(b_entry, tile.adapter) : Bt_ptrs[tile.adapter];
+        const bf16_t* At = At_ptrs[tile.adapter];        // only the bounded-wait fallback reads it
+        const int32_t* rows = expand_rows + (int64_t)(b - n_shrink) * 16;
         if (tile.reserved0 <= 32)
-            fused_expand_item<1>(tile, perm, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, spin_limit, delay,
+            fused_expand_item<1>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, spin_limit, delay,
                                  reinterpret_cast<float*>(lds), &flag);
         else
-            fused_expand_item<2>(tile, perm, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, spin_limit, delay,
+            fused_expand_item<2>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, spin_limit, delay,
                                  reinterpret_cast<float*>(lds), &flag);
     }
 }
@@ -1340,7 +1402,8 @@ hipError_t launch_delta_fused_small(const lora_plan* p, const lora_dev_tables& d
     if (S + E == 0) return hipSuccess;
     lora_sync_slot* sync = reinterpret_cast<lora_sync_slot*>(d.sync);
     LORA_LAUNCH(LORA_K_DELTA_FUSED, delta_fused_small_kernel, dim3(S + E), dim3(256), 0, stream,
-                d.shrink_tiles, S, d.expand_tiles, d.perm, d.scale, (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K,
-                v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta, sync, p->fused_spin_limit, p->fused_delay);
+                d.shrink_tiles, S, d.expand_tiles, d.shrink_rows, d.expand_rows, d.scale, (const bf16_t*)x, ldx,
+                (const bf16_t* const*)At, p->K, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta,
+                sync, p->fused_spin_limit, p->fused_delay, p->n_a);
     return hipGetLastError();
 }

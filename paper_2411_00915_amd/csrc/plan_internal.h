@@ -39,6 +39,7 @@ struct lora_plan {
     // or 256 rows of that order, the adapter stages present: packed adapter | (64-column block of the
     // adapter's [v_hi | v_lo] concatenation) << 24
     std::vector<int32_t> order, extra_ptr128, extra128, extra_ptr256, extra256;
+    std::vector<int32_t> shrink_rows, expand_rows;   // single-launch decode kernel: 16 tokens per tile, padded
     bool tiled_layout_ok = false;  // K and all active ranks multiples of 8
 
     // device mirror (one allocation), valid when d_buf != nullptr
@@ -57,6 +58,8 @@ struct lora_plan {
     int32_t* d_extra128 = nullptr;
     int32_t* d_extra_ptr256 = nullptr;
     int32_t* d_extra256 = nullptr;
+    int32_t* d_shrink_rows = nullptr;
+    int32_t* d_expand_rows = nullptr;
     void* d_zeros = nullptr;          // 256 zero bytes (source of masked chunks in the fused GEMM)
     void* d_sync = nullptr;           // hand-off counters, 128 bytes per adapter group (only when fused_ok)
 };

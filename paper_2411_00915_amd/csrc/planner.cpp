@@ -262,6 +262,21 @@ static void build_tiles(lora_plan* p)
     auto weight = [&](const lora_tile& t) { return (int64_t)((t.nrows + 15) / 16) * t.cn; };
     std::stable_sort(p->shrink_tiles.begin(), p->shrink_tiles.end(),
                      [&](const lora_tile& x, const lora_tile& y) { return weight(x) > weight(y); });
+    // Single-launch decode kernel: the 16 tokens of every tile, in tile order and padded with the tile's
+    // first token, so that a workgroup can fetch them by its index alone, at the same time as its
+    // tile descriptor instead of after it
+    p->shrink_rows.clear();
+    p->expand_rows.clear();
+    if (p->fused_ok) {
+        auto rows_of = [&](const std::vector<lora_tile>& tiles, std::vector<int32_t>& rows) {
+            rows.resize(tiles.size() * 16);
+            for (size_t i = 0; i < tiles.size(); ++i)
+                for (int m = 0; m < 16; ++m)
+                    rows[i * 16 + m] = p->perm[(size_t)tiles[i].row0 + (m < tiles[i].nrows ? m : 0)];
+        };
+        rows_of(p->shrink_tiles, p->shrink_rows);
+        rows_of(p->expand_tiles, p->expand_rows);
+    }
 }
 
 // Tables of the fused GEMM: it walks the tokens in adapter-sorted order, so a tile of rows holds few

@@ -1250,7 +1250,11 @@ __device__ __forceinline__ void fused_expand_item(
             for (int q = 0; q < 4; ++q) {                  // all parts are requested before the first add
                 const float* vq = v + q * vsp.part + (int64_t)t * R + j4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pv[q][i] = (q < vsp.P) ? ld_agent_f(vq + i) : 0.f;
+                for (int i = 0; i < 4; i += 2) {           // 8-byte agent-scope loads (vq is 16-byte aligned)
+                    const unsigned long long two = (q < vsp.P) ? ld_agent(reinterpret_cast<const unsigned long long*>(vq + i)) : 0ull;
+                    pv[q][i] = __uint_as_float((unsigned int)two);
+                    pv[q][i + 1] = __uint_as_float((unsigned int)(two >> 32));
+                }
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) vt[row * 64 + j4 + i] = ((pv[0][i] + pv[1][i]) + pv[2][i]) + pv[3][i];

@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, scaled by a 256 MiB copy
 # (profiles/decode_cfg2_hbm_traffic.txt); keyed by workload and kernel
-MEASURED_TRAFFIC = {("cfg2_decode", "delta_fused_small_kernel"): 45.82e6,
+MEASURED_TRAFFIC = {("cfg2_decode", "delta_fused_small_kernel"): 46.00e6,
                     ("cfg5_large_attn", "expand_stream_kernel"): 536.09e6,     # profiles/prefill_cfg5_shrink_expand_hbm_traffic.txt
                     ("cfg5_large_attn", "shrink_stream_kernel"): 333.39e6}
 

@@ -47,6 +47,12 @@ hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, con
 hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, const float* v,
                                const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream);
 
+// streaming kernels for prefill-sized batches (plans with shrink_stream / expand_stream; called by the two above)
+hipError_t launch_shrink_stream(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
+                                const void* const* At, float* v, hipStream_t stream);
+hipError_t launch_expand_stream(const lora_plan* p, const lora_dev_tables& d, const float* v,
+                                const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream);
+
 // both steps in one launch (decode regime: every tile small); same layout demands as the tiled family
 hipError_t launch_delta_fused_small(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
                                     const void* const* At, const void* const* Bt, float* v, void* y, int64_t ldy,

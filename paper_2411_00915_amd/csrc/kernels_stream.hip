@@ -123,31 +123,35 @@ __device__ __forceinline__ void shrink_stream_tile(
     // x registers: NX stages in flight per wavefront (4 KB each); the widest tiles take fewer so that
     // their register count still lets a second workgroup onto the CU
     constexpr int NX = 2;
-    uint4 ra[NLD];
+    // slab registers: two sets (a slab is requested three stages before it is multiplied) except for the
+    // widest tiles (one set, two stages), whose register count is the kernel's
+    constexpr int NRA = JB < 8 ? 2 : 1;
+    uint4 ra[NRA][NLD];
     op16 xr[NX][UW];
     // the loads are issued in the order the stage loop keeps them in flight and consumes them, and the
     // loop has no guard branch, so every wait in it can name exactly the loads it needs
-    load_a(0, ra);
+    load_a(0, ra[0]);
 #pragma unroll
     for (int i = 0; i < UW; ++i) xr[0][i].u = load_x1(0, i);
-    store_a(0, ra);
-    load_a(1, ra);
+    store_a(0, ra[0]);
+    load_a(1, ra[0]);
 #pragma unroll
     for (int u = 1; u < NX; ++u)
 #pragma unroll
         for (int i = 0; i < UW; ++i) xr[u][i].u = load_x1(u, i);
+    if constexpr (NRA == 2) load_a(2, ra[1]);
     __syncthreads();
     // stage s computes from slab buffer s%2; the slab of stage s+1 goes from its registers to the other
-    // buffer after the MFMAs, and the slab after that is requested into them.  Stages past the last one
-    // work on zeros.
+    // buffer after the MFMAs, and a later slab is requested into them.  Stages past the last one work on
+    // zeros.
     int s = 0;
     do {
 #pragma unroll
         for (int u = 0; u < NX; ++u) {
             compute(u & 1, xr[u], s + u + NX);
             __builtin_amdgcn_sched_barrier(0);
-            store_a((u + 1) & 1, ra);
-            load_a(s + u + 2, ra);
+            store_a((u + 1) & 1, ra[u % NRA]);
+            load_a(s + u + 1 + NRA, ra[u % NRA]);
             __syncthreads();
         }
         s += NX;

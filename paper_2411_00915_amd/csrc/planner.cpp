@@ -262,6 +262,10 @@ static void build_tiles(lora_plan* p)
     auto weight = [&](const lora_tile& t) { return (int64_t)((t.nrows + 15) / 16) * t.cn; };
     std::stable_sort(p->shrink_tiles.begin(), p->shrink_tiles.end(),
                      [&](const lora_tile& x, const lora_tile& y) { return weight(x) > weight(y); });
+    // (the streaming expand's tiles differ in size by up to 8x: the same for them)
+    if (p->expand_stream)
+        std::stable_sort(p->expand_tiles.begin(), p->expand_tiles.end(),
+                         [&](const lora_tile& x, const lora_tile& y) { return weight(x) > weight(y); });
     // Single-launch decode kernel: the 16 tokens of every tile, in tile order and padded with the tile's
     // first token, so that a workgroup can fetch them by its index alone, at the same time as its
     // tile descriptor instead of after it

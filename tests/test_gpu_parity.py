@@ -345,6 +345,13 @@ def test_single_launch_delta_small_and_mixed_cases():
     _delta_case(wl.random_case(412, 5, 2048, 128, 1, (64,), max_seg=8))
 
 
+def test_single_launch_delta_large_decode_batch():
+    # a decode batch several times the size of cfg2: far more workgroups than fit the GPU at once, so expand
+    # blocks are dispatched long after their shrink blocks, and many adapter groups share the counters' table
+    w = wl.random_case(413, 1536, 2048, 2048, 384, (8, 16, 32, 64), max_seg=1, scales=(1.0, 2.0, -0.5))
+    _delta_case(w)
+
+
 # ---------------------------------------------------------------- mixture mode through the same operator
 def test_delora_mixture_mode():
     """Mixture inference (section 4.4.1): adapter 1 is merged into the base weight, requests of other adapters

@@ -507,10 +507,6 @@ __device__ __forceinline__ unsigned long long ld_agent(const unsigned long long*
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float ld_agent_f(const float* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 template <int KS>
 __device__ __forceinline__ void fused_expand_item(

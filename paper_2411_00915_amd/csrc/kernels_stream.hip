@@ -82,7 +82,7 @@ __device__ __forceinline__ void shrink_stream_tile(
     };
     auto load_x1 = [&](int s, int i) {
         const int k0 = k_begin + s * 128 + (i % H) * (LPR * 8);
-        return ld16_global((((x_ok >> (i / H)) & 1) && k0 + (kw * CPR + xl_c) * 8 < k_end) ? xsrc[i / H] + k0 : zeros);
+        return ld16_stream((((x_ok >> (i / H)) & 1) && k0 + (kw * CPR + xl_c) * 8 < k_end) ? xsrc[i / H] + k0 : zeros);
     };
     auto store_a = [&](int buf, const uint4 (&ra)[NLD]) {
 #pragma unroll
@@ -292,7 +292,7 @@ __device__ __forceinline__ void expand_stream_tile(
     const int y_n0 = tile.c0 + fw * 64 + yl_c * 8;           // first feature of this lane's 8 in stage 0
     auto load_y = [&](int s, int i) {
         const bool ok = ((y_ok >> i) & 1) && y_n0 + s * (FW * 64) < n_end && beta != 0.f;
-        return ld16(ok ? ybase[i] + s * (FW * 64) : zeros);
+        return ld16_stream(ok ? ybase[i] + s * (FW * 64) : zeros);
     };
 
     // slab staging: unit q = feature row (q / RC) of the stage, 16-byte column q % RC
@@ -351,7 +351,7 @@ __device__ __forceinline__ void expand_stream_tile(
                 out[q] = (uint32_t)f32_to_bf16(e0) | ((uint32_t)f32_to_bf16(e1) << 16);
             }
             if (((y_ok >> i) & 1) && y_n0 + s * (FW * 64) < n_end)
-                *reinterpret_cast<uint4*>(ybase[i] + s * (FW * 64)) = uint4{out[0], out[1], out[2], out[3]};
+                st16_stream(ybase[i] + s * (FW * 64), uint4{out[0], out[1], out[2], out[3]});
             yr[i] = load_y(s + 4, i);
         }
         __builtin_amdgcn_wave_barrier();

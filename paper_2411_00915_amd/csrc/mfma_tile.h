@@ -30,6 +30,29 @@ __device__ __forceinline__ uint4 ld16(const bf16_t* p)
 }
 __device__ __forceinline__ uint4 ld16_global(const bf16_t* p) { return ld16(p); }
 
+// the same for data that is read (or written) exactly once by the whole launch: marked non-temporal, so that
+// it does not displace what the launch re-reads (adapter matrices) from the caches
+__device__ __forceinline__ uint4 ld16_stream(const bf16_t* p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+    const u32x4 r = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4*)(uintptr_t)p);
+    return uint4{r[0], r[1], r[2], r[3]};
+#else
+    return *reinterpret_cast<const uint4*>(p);
+#endif
+}
+__device__ __forceinline__ void st16_stream(bf16_t* p, uint4 val)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+    const u32x4 r = {val.x, val.y, val.z, val.w};
+    __builtin_nontemporal_store(r, (__attribute__((address_space(1))) u32x4*)(uintptr_t)p);
+#else
+    *reinterpret_cast<uint4*>(p) = val;
+#endif
+}
+
 __device__ __forceinline__ floatx4 mfma(const op16& a, const op16& b, floatx4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);

@@ -496,7 +496,7 @@ __global__ __launch_bounds__(512) void merge_stream_kernel(
     }
     const int w_k0 = k0 + yl_c * 8;
     auto load_w = [&](int st, int i) {
-        return ld16((((w_ok >> i) & 1) && w_k0 + st * 64 < k_end) ? wbase[i] + st * 64 : zeros);
+        return ld16_stream((((w_ok >> i) & 1) && w_k0 + st * 64 < k_end) ? wbase[i] + st * 64 : zeros);
     };
 
     // slab staging: unit q = rank row q / 8, columns 8 (q % 8) .. +7 of the stage
@@ -558,7 +558,7 @@ __global__ __launch_bounds__(512) void merge_stream_kernel(
                 out[q] = (uint32_t)f32_to_bf16(e0) | ((uint32_t)f32_to_bf16(e1) << 16);
             }
             if (((w_ok >> i) & 1) && w_k0 + st * 64 < k_end)
-                *reinterpret_cast<uint4*>(wbase[i] + st * 64) = uint4{out[0], out[1], out[2], out[3]};
+                st16_stream(wbase[i] + st * 64, uint4{out[0], out[1], out[2], out[3]});
             wr[i] = load_w(st + 4, i);
         }
         __builtin_amdgcn_wave_barrier();

@@ -105,7 +105,7 @@ __device__ __forceinline__ void shrink_tile(
                 int j = (JB == 2 ? unit * 16 : 0) + 4 * (i & 3) + lr;
                 if (j >= tile.cn) j = 0;
                 const int k = ((s + (JB == 1 ? 4 * unit : 0)) << 5) + lc * 8;
-                raw[i] = ld16(k < K ? At + (int64_t)(tile.c0 + j) * K + k : zeros);
+                raw[i] = ld16_stream(k < K ? At + (int64_t)(tile.c0 + j) * K + k : zeros);   // read once per launch
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -541,7 +541,7 @@ __device__ __forceinline__ void fused_expand_item(
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const int j = s * 32 + g * 8;
-                bop[b][s].u = (n < n_end && j < r) ? ld16(Bt + (int64_t)n * r + j) : uint4{0, 0, 0, 0};
+                bop[b][s].u = (n < n_end && j < r) ? ld16_stream(Bt + (int64_t)n * r + j) : uint4{0, 0, 0, 0};
             }
         }
     };

@@ -35,8 +35,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, scaled by a 256 MiB copy
 # (profiles/decode_cfg2_hbm_traffic.txt); keyed by workload and kernel
 MEASURED_TRAFFIC = {("cfg2_decode", "delta_fused_small_kernel"): 46.00e6,
-                    ("cfg5_large_attn", "expand_stream_kernel"): 536.09e6,     # profiles/prefill_cfg5_shrink_expand_hbm_traffic.txt
-                    ("cfg5_large_attn", "shrink_stream_kernel"): 333.39e6}
+                    ("cfg5_large_attn", "expand_stream_kernel"): 534.80e6,     # profiles/prefill_cfg5_shrink_expand_hbm_traffic.txt
+                    ("cfg5_large_attn", "shrink_stream_kernel"): 332.00e6}
 
 KERNEL_KEYS = {"shrink_tiled_kernel": "shrink", "expand_tiled_kernel": "expand", "delta_fused_small_kernel": "delta",
                "shrink_stream_kernel": "shrink", "expand_stream_kernel": "expand", "v_split_kernel": "v_split",

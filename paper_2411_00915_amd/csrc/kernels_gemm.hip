@@ -107,7 +107,14 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
         const int xcd = id & 7, q = id >> 3;
         id = xcd * per + (xcd < rem ? xcd : rem) + q;   // XCD k owns per + (k < rem) tiles
     }
-    const int tile_t = id % tiles_t, tile_n = id / tiles_t;
+    // inside an XCD's run the tiles go in groups of GN feature tiles: token tile fastest over GN feature tiles,
+    // so the 32 tiles an XCD works on at a time form an 8 x 4 block and share 8 x panels and 4 W panels
+    // (instead of 32 x panels and one W panel) in its L2
+    constexpr int GN = 4;
+    const int group = id / (GN * tiles_t), first_n = group * GN;
+    const int group_n = min(tiles_n - first_n, GN);
+    const int in_group = id - group * (GN * tiles_t);
+    const int tile_n = first_n + in_group % group_n, tile_t = in_group / group_n;
     const int n0 = tile_n * BM, t0 = tile_t * BT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

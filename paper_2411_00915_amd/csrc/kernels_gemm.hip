@@ -35,6 +35,7 @@
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
 union op16 {
     uint4 u;
@@ -49,8 +50,8 @@ constexpr int BK = 64;    // k per stage; a tile row is 128 bytes = 8 chunks of 
 // wavefront is served 8 lanes at a time, so f must take 8 different values over the 8 rows those lanes read.
 // x tile: lanes read consecutive rows -> f = r & 7.  W tile: lanes 8g..8g+7 read rows 4g..4g+3 and
 // 16+4g..16+4g+3 (the feature permutation of the MFMA rows) -> f = (r & 3) | bit 4 of r << 2.
-__device__ __forceinline__ int lds_slot(int row, int chunk) { return row * 8 + (chunk ^ (row & 7)); }
-__device__ __forceinline__ int lds_slot_w(int row, int chunk) { return row * 8 + (chunk ^ ((row & 3) | ((row >> 2) & 4))); }
+__device__ __forceinline__ int lds_slot(int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); }
+__device__ __forceinline__ int lds_slot_w(int row, int chunk) { return row * 8 + (chunk ^ (((row >> 1) & 3) | ((row >> 2) & 4))); }
 
 __device__ __forceinline__ void split_bf16(const float* f, op16& hi, op16& lo)
 {
@@ -80,6 +81,24 @@ struct gemm_delta_args {
     const bf16_t* zeros;           // 16 zero bytes: the source of chunks that are masked out
 };
 
+// Workgroups are dealt round-robin to the 8 XCDs; every XCD gets a contiguous run of tiles (so its L2 sees
+// neighbouring tiles).  Inside a run the tiles go in groups of GN feature tiles, token tile fastest over GN
+// feature tiles, so the 32 tiles an XCD works on at a time form an 8 x 4 block and share 8 x panels and 4 W
+// panels (instead of 32 x panels and one W panel) in its L2.
+__device__ __forceinline__ void tile_of_workgroup(int id, int tiles_n, int tiles_t, int& tile_n, int& tile_t)
+{
+    const int n_wg = tiles_n * tiles_t;
+    const int per = n_wg / 8, rem = n_wg % 8;
+    const int xcd = id & 7, q = id >> 3;
+    id = xcd * per + (xcd < rem ? xcd : rem) + q;       // XCD k owns per + (k < rem) tiles
+    constexpr int GN = 4;
+    const int group = id / (GN * tiles_t), first_n = group * GN;
+    const int group_n = min(tiles_n - first_n, GN);
+    const int in_group = id - group * (GN * tiles_t);
+    tile_n = first_n + in_group % group_n;
+    tile_t = in_group / group_n;
+}
+
 // KTAIL: K is not a multiple of 64, the last K stage's chunks beyond K are zero-filled
 template <int WB, bool DELTA, bool KTAIL>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(
@@ -97,24 +116,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     // registers during the K stages: [NLD][256] int2
     int2* lds_rows = reinterpret_cast<int2*>(lds_meta + META_MAX);
 
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
-    // run of tiles (so its L2 sees neighbouring tiles), walking token tiles
-    // fastest inside a band of feature tiles so W panels stay hot.
-    const int n_wg = tiles_n * tiles_t;
-    int id = blockIdx.x;
-    {
-        const int per = n_wg / 8, rem = n_wg % 8;
-        const int xcd = id & 7, q = id >> 3;
-        id = xcd * per + (xcd < rem ? xcd : rem) + q;   // XCD k owns per + (k < rem) tiles
-    }
-    // inside an XCD's run the tiles go in groups of GN feature tiles: token tile fastest over GN feature tiles,
-    // so the 32 tiles an XCD works on at a time form an 8 x 4 block and share 8 x panels and 4 W panels
-    // (instead of 32 x panels and one W panel) in its L2
-    constexpr int GN = 4;
-    const int group = id / (GN * tiles_t), first_n = group * GN;
-    const int group_n = min(tiles_n - first_n, GN);
-    const int in_group = id - group * (GN * tiles_t);
-    const int tile_n = first_n + in_group % group_n, tile_t = in_group / group_n;
+    int tile_n, tile_t;
+    tile_of_workgroup(blockIdx.x, tiles_n, tiles_t, tile_n, tile_t);
     const int n0 = tile_n * BM, t0 = tile_t * BT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -415,6 +418,259 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// Ring variant of the 256 x 256 tile: the same MFMA blocking and lane roles, but the tiles go HBM -> LDS
+// directly (global_load_lds_dwordx4, no staging registers, no LDS write instructions) into a ring of four
+// stages of 32 k, three stages ahead of the one the matrix cores work on.  A workgroup's tile walks through
+// lines that nobody has touched yet, stage after stage, so its loads see memory latency (microseconds
+// under load), not L2 latency; with register staging the fetch distance was half a 64-k stage.
+//
+// A direct-to-LDS load puts lane i's 16 bytes at LDS address M0 + 16 i: the LDS image of one load is 1 KB
+// contiguous = 16 tile rows of 64 bytes, and the XOR swizzle is applied on the global side (lane i fetches the
+// chunk that belongs in slot i).  The loads are issued from inline assembly, so the compiler does not count
+// them: the waits for them are written out (s_waitcnt vmcnt), and since memory returns loads in order,
+// "at most 16 outstanding" means that everything but the two youngest stages has landed.
+constexpr int RK = 32;             // k per ring stage; a tile row is 64 bytes = 4 chunks of 16 bytes
+constexpr int RING = 4;            // stages in the LDS ring
+constexpr int RING_STAGE = 2048;   // uint4 per stage: 256 W rows x 4 chunks, then 256 x rows x 4 chunks
+
+// Chunk c of row r lives at slot 4 r + (c ^ f(r)).  LDS serves a ds_read_b128 sixteen lanes at a time out of 64
+// banks (256 bytes = 4 rows), so the 16 rows those lanes read must fall into 16 different 16-byte columns: rows
+// with equal r & 3 need different f.  x: 16 consecutive rows -> f = bits 2..3 of r.  W: the MFMA row
+// permutation makes 16 lanes read rows {0..7, 16..23} or {8..15, 24..31} of a block -> f = bit 2 | bit 4 << 1.
+__device__ __forceinline__ int ring_f_x(int row) { return (row >> 2) & 3; }
+__device__ __forceinline__ int ring_f_w(int row) { return (row >> 4) & 3; }
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+__device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }
+
+// lane i's 16 bytes at g -> LDS byte address lds_base + 16 i (lds_base wavefront-uniform)
+__device__ __forceinline__ void load16_to_lds(const void* g, uint32_t lds_base)
+{
+    // (readfirstlane: the operand has to be a scalar register also where the compiler cannot prove it uniform)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
+}
+
+template <bool DELTA>
+__global__ __launch_bounds__(512) void gemm_ring_kernel(
+    int T, int K, int N, const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ Wt, int64_t ldw,
+    bf16_t* __restrict__ y, int64_t ldy, int tiles_n, int tiles_t, gemm_delta_args da)
+{
+    // Eight wavefronts, two per SIMD, each 128 features x 64 tokens = 4 x 2 MFMA blocks (128 accumulator
+    // registers).  A wavefront cannot issue an MFMA while it issues a load (each load costs it about one
+    // MFMA slot, also with all lanes masked off); with a second wavefront on the SIMD the matrix core takes
+    // that one's MFMA meanwhile.
+    constexpr int BM = 256, BT = 256, WA = 8, WX = 4;
+    uint4* ring = gemm_lds;                                          // [RING][RING_STAGE]
+    uint4* lds_meta = gemm_lds + RING * RING_STAGE;                  // DELTA: [META_MAX] adapter stages of the tile
+    int2* lds_rows = reinterpret_cast<int2*>(lds_meta + META_MAX);   // DELTA: [2][512] (token, adapter) of staged rows
+
+    int tile_n, tile_t;
+    tile_of_workgroup(blockIdx.x, tiles_n, tiles_t, tile_n, tile_t);
+    const int n0 = tile_n * BM, t0 = tile_t * BT;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = (wave & 1) * 128, wt = (wave >> 1) * 64;         // wavefront tile origin
+    // Lane roles in v_mfma_f32_16x16x32_bf16 (D = A*B + C, A 16x32, B 32x16): lane l supplies A[row l%16][k 8(l/16) ..
+    // +7] and B[k 8(l/16) .. +7][col l%16], and receives D[row 4(l/16) + i][col l%16], i = 0..3.  MFMA rows carry
+    // features, columns carry tokens.  The 128 features of a wavefront are two groups of 64; block q of a group
+    // holds the features 16 g + 4 q + i (MFMA row 4 g + i), so that over its four blocks a lane (g = l/16) ends up
+    // with the 16 consecutive features 16 g .. 16 g + 15 of its token.
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int frow = 16 * (l16 >> 2) + (l16 & 3);                   // feature (block 0 of a group) of MFMA row l16
+
+    // Staging role: load j of this wavefront fills slots (2 wave + j) 64 .. +63 of the W part and of the x part
+    // of a stage, i.e. rows (2 wave + j) 16 .. +15; this lane brings chunk slot lane & 3 of row .. + lane / 4.
+    const int pc = lane & 3;
+    const bf16_t* pw[2];
+    const bf16_t* px[2];
+    int cw[2];                                                       // logical chunk this lane fetches (W side)
+    const int cx = pc ^ ring_f_x(lane >> 2);                         // (x side: the same for both loads)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int row = (wave * 2 + j) * 16 + (lane >> 2);
+        cw[j] = pc ^ ring_f_w(row);
+        int nr = n0 + row; if (nr >= N) nr = N - 1;
+        int pos = t0 + row;
+        const bool pos_ok = pos < T;
+        if (!pos_ok) pos = T - 1;
+        const int tok = DELTA ? da.order[pos] : pos;
+        pw[j] = Wt + (int64_t)nr * ldw + cw[j] * 8;
+        px[j] = x + (int64_t)tok * ldx + cx * 8;
+        if constexpr (DELTA) lds_rows[j * 512 + tid] = make_int2(tok, pos_ok ? da.token_adapter[tok] : -1);
+    }
+
+    const int stages_k = K / RK;                                     // K % 32 == 0, stages_k >= 4 (checked by the launcher)
+    int n_extra = 0, stages = stages_k;
+    if constexpr (DELTA) {
+        const int extra_base = da.extra_ptr[tile_t];
+        n_extra = da.extra_ptr[tile_t + 1] - extra_base;             // <= META_MAX (checked by the launcher)
+        stages += n_extra;
+        for (int e = tid; e < n_extra; e += 512) {
+            const int packed = da.extra[extra_base + e];
+            const int a_id = packed & 0xffffff;
+            const uint64_t bt = reinterpret_cast<uint64_t>(da.Bt_ptrs[a_id]);
+            lds_meta[e] = uint4{(uint32_t)packed, (uint32_t)da.rank[a_id], (uint32_t)bt, (uint32_t)(bt >> 32)};
+        }
+        __syncthreads();                                             // lds_meta / lds_rows are complete
+    }
+
+    floatx4 acc[WA][WX];
+#pragma unroll
+    for (int a = 0; a < WA; ++a)
+#pragma unroll
+        for (int b = 0; b < WX; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // source pointers of the stage to fetch next: a K stage advances them by 32 elements, an adapter stage sets
+    // them afresh (W chunks to Bt_a[feature row, ranks], x chunks to the token's [v_hi | v_lo] columns, every
+    // chunk that is masked out to a block of zeros), so every stage issues the same four unconditional loads
+    auto advance = [&](int next) {
+        if (!DELTA || next < stages_k) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) { pw[j] += RK; px[j] += RK; }
+        } else if (next < stages) {
+            const uint4 m = lds_meta[next - stages_k];
+            const int a_id = (int)m.x & 0xffffff, r = (int)m.y;
+            const bf16_t* Bt = reinterpret_cast<const bf16_t*>((uint64_t)m.z | ((uint64_t)m.w << 32));
+            const int col0 = ((int)m.x >> 24) * RK;
+            const int colx = col0 + cx * 8;
+            const bool inx = colx < 2 * r;
+            const int partx = colx >= r ? 1 : 0;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                int nr = n0 + (wave * 2 + j) * 16 + (lane >> 2);
+                if (nr >= N) nr = N - 1;
+                const int colw = col0 + cw[j] * 8;
+                const int jw = colw >= r ? colw - r : colw;          // r % 8 == 0: a chunk lies in one half
+                const int2 ta = lds_rows[j * 512 + tid];
+                pw[j] = colw < 2 * r ? Bt + (int64_t)nr * r + jw : da.zeros;
+                px[j] = (inx && ta.y == a_id) ? da.vb + ((int64_t)ta.x * 2 + partx) * da.R + (colx - partx * r) : da.zeros;
+            }
+        }
+    };
+    const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 2048), lds_x = lds_w + 16384;
+    auto issue = [&](int buf, int j4) {                              // one of the four loads of a stage
+        const uint32_t base = (uint32_t)buf * (RING_STAGE * 16) + (j4 & 1) * 1024;
+        if (j4 < 2) load16_to_lds(pw[j4 & 1], lds_w + base);
+        else load16_to_lds(px[j4 & 1], lds_x + base);
+    };
+
+    // operand slots of a stage: one ds_read_b128 of a wavefront is one 16 x 32 operand block (lane group kg reads
+    // chunk kg of its row); W block a = 4 G + q: + (64 G + 4 q) rows; x block b: + 16 b rows
+    const int sw0 = (wn + frow) * 4 + (kg ^ ring_f_w(frow));
+    const int sx0 = RING_STAGE / 2 + (wt + l16) * 4 + (kg ^ ring_f_x(l16));
+    // W operands are single-buffered (block a is re-read for the next stage once its four MFMAs are out), x
+    // operands double-buffered
+    op16 wa[WA], xbA[WX], xbB[WX];
+    auto read_w = [&](const uint4* st, int a) { wa[a].u = st[sw0 + ((a >> 2) * 64 + (a & 3) * 4) * 4]; };
+    auto read_x = [&](const uint4* st, int b, op16 (&xb)[WX]) { xb[b].u = st[sx0 + b * 64]; };
+#define RING_MMA(XB_, A_, B_) \
+    acc[A_][B_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[A_].v, XB_[B_].v, acc[A_][B_], 0, 0, 0)
+#define RING_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+    // prologue: stages 0, 1, 2 on their way (all K stages), stage 0 landed, its first operands read
+#pragma unroll
+    for (int s0 = 0; s0 < 3; ++s0) {
+#pragma unroll
+        for (int j4 = 0; j4 < 4; ++j4) issue(s0, j4);
+        advance(s0 + 1);
+    }
+    asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+#pragma unroll
+    for (int b = 0; b < WX; ++b) read_x(ring, b, xbA);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) read_w(ring, a);
+
+    // One stage = 32 MFMAs.  First half (W blocks 0..3): the reads of W blocks 4..7 of this stage and two of the
+    // four loads of stage s + 3 (into the buffer that stage s - 1 used; everybody left it before the previous
+    // barrier).  Then the wavefront waits until its own loads of stage s + 1 have landed (AHEAD = loads allowed
+    // to be still outstanding) and for its LDS reads, and meets the others.  Second half (W blocks 4..7): the
+    // reads of W blocks 0..3 and of the x blocks of stage s + 1, and the other two loads.
+#define RING_HALF_STAGE(XB_, XN_, ISSUE, AHEAD, LAST)                                                                  \
+    {                                                                                                                  \
+        const uint4* st = ring + (s & 3) * RING_STAGE;                                                                 \
+        const uint4* st_n = ring + ((s + 1) & 3) * RING_STAGE;                                                         \
+        _Pragma("unroll") for (int i = 0; i < 16; ++i) {                                                               \
+            RING_MMA(XB_, i >> 2, i & 3);                                                                              \
+            if ((i & 3) == 1 && i < 16) read_w(st, 4 + (i >> 2));                                                      \
+            if (ISSUE && (i == 7 || i == 11)) issue((s + 3) & 3, i == 7 ? 0 : 1);                                      \
+            RING_FENCE();                                                                                              \
+        }                                                                                                              \
+        if (!(LAST)) asm volatile("s_waitcnt vmcnt(" #AHEAD ") lgkmcnt(0)\n\ts_barrier" ::: "memory");                   \
+        _Pragma("unroll") for (int i = 16; i < 32; ++i) {                                                              \
+            RING_MMA(XB_, i >> 2, i & 3);                                                                              \
+            if (!(LAST) && (i & 1) == 0) { if (i < 24) read_x(st_n, (i - 16) >> 1, XN_); else read_w(st_n, (i - 24) >> 1); } \
+            if (ISSUE && (i == 21 || i == 27)) issue((s + 3) & 3, i == 21 ? 2 : 3);                                    \
+            RING_FENCE();                                                                                              \
+        }                                                                                                              \
+    }
+    // Two stages per loop iteration, so that the x operand buffers swap roles statically; an odd number of
+    // stages ahead of the last three is evened out by one stage up front and a register copy.
+    int s = 0;
+    if ((stages - 3) & 1) {
+        RING_HALF_STAGE(xbA, xbB, true, 6, false)
+        advance(4);
+        _Pragma("unroll") for (int b = 0; b < WX; ++b) xbA[b].u = xbB[b].u;
+        s = 1;
+    }
+    // K stages whose fourth successor is a K stage too: no branch in the body
+    for (; s + 5 < stages_k; s += 2) {
+        RING_HALF_STAGE(xbA, xbB, true, 6, false)
+        _Pragma("unroll") for (int j = 0; j < 2; ++j) { pw[j] += RK; px[j] += RK; }
+        ++s;
+        RING_HALF_STAGE(xbB, xbA, true, 6, false)
+        _Pragma("unroll") for (int j = 0; j < 2; ++j) { pw[j] += RK; px[j] += RK; }
+        --s;
+    }
+    // the stages around and inside the adapter part
+    for (; s + 4 < stages; s += 2) {
+        RING_HALF_STAGE(xbA, xbB, true, 6, false)
+        advance(s + 4);
+        ++s;
+        RING_HALF_STAGE(xbB, xbA, true, 6, false)
+        advance(s + 4);
+        --s;
+    }
+    // the last three stages fetch nothing
+    RING_HALF_STAGE(xbA, xbB, false, 4, false)
+    ++s;
+    RING_HALF_STAGE(xbB, xbA, false, 0, false)
+    ++s;
+    RING_HALF_STAGE(xbA, xbB, false, 0, true)
+#undef RING_HALF_STAGE
+#undef RING_MMA
+#undef RING_FENCE
+
+    // ---- epilogue: one rounding, store (rows go back to their tokens) ------
+#pragma unroll
+    for (int b = 0; b < WX; ++b) {
+        const int pos = t0 + wt + b * 16 + l16;
+        if (pos >= T) continue;
+        const int t = DELTA ? da.order[pos] : pos;
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+            const int n = n0 + wn + 64 * G + 16 * kg;                // first of this lane's 16 features
+            bf16_t* yp = y + (int64_t)t * ldy + n;
+            // feature offset 4 q + i is element i of block 4 G + q
+            if (n + 16 <= N) {
+                uint32_t o[8];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    o[2 * q] = (uint32_t)f32_to_bf16(acc[4 * G + q][b][0]) | ((uint32_t)f32_to_bf16(acc[4 * G + q][b][1]) << 16);
+                    o[2 * q + 1] = (uint32_t)f32_to_bf16(acc[4 * G + q][b][2]) | ((uint32_t)f32_to_bf16(acc[4 * G + q][b][3]) << 16);
+                }
+                *reinterpret_cast<uint4*>(yp) = uint4{o[0], o[1], o[2], o[3]};
+                *reinterpret_cast<uint4*>(yp + 8) = uint4{o[4], o[5], o[6], o[7]};
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (n + i < N) yp[i] = f32_to_bf16(acc[4 * G + (i >> 2)][b][i & 3]);
+            }
+        }
+    }
+}
+
 // v (sum of its K parts, fp32) -> two bf16 terms hi + lo, rows [t][0][R] and [t][1][R] of vb
 __global__ __launch_bounds__(64) void v_split_kernel(
     const int32_t* __restrict__ perm, const int32_t* __restrict__ token_adapter, const int32_t* __restrict__ rank,
@@ -452,6 +708,26 @@ hipError_t launch_one(int32_t T, int32_t K, int32_t N, const void* x, int64_t ld
     return hipGetLastError();
 }
 
+template <bool DELTA>
+hipError_t launch_ring(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx, const void* Wt, int64_t ldw,
+                       void* y, int64_t ldy, const gemm_delta_args& da, hipStream_t stream)
+{
+    const int tiles_n = (N + 255) / 256, tiles_t = (T + 255) / 256;
+    const size_t lds_bytes = (size_t)RING * RING_STAGE * sizeof(uint4) +
+                             (DELTA ? META_MAX * sizeof(uint4) + (size_t)2 * 512 * sizeof(int2) : 0);
+    static bool attr_set = false;                 // dynamic LDS above 64 KB has to be allowed once per kernel
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_ring_kernel<DELTA>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    LORA_LAUNCH(DELTA ? LORA_K_GEMM_TILED_DELTA : LORA_K_GEMM_TILED, (gemm_ring_kernel<DELTA>),
+                dim3(tiles_n * tiles_t), dim3(512), lds_bytes, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
+                (bf16_t*)y, ldy, tiles_n, tiles_t, da);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const void* x, int64_t ldx,
@@ -474,16 +750,22 @@ hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int
     // 256 x 256 tiles once there are enough of them to fill the 256 compute units
     const bool big = (int64_t)((N + 255) / 256) * ((T + 255) / 256) >= 192;
     const bool delta = p && !p->perm.empty();
+    // the ring kernel: whole 32-k stages, at least four of them, every tile's adapter stages fit its LDS list
+    const bool ring_ok = big && K % RK == 0 && K / RK >= 4 && (!delta || p->max_extra256h <= META_MAX);
     gemm_delta_args da{};
     if (delta) {
         LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)p->perm.size()), dim3(64), 0, stream,
                     d->perm, d->token_adapter, d->rank, v, lora_vspec_of(p), (bf16_t*)vb);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        da = gemm_delta_args{d->order, d->token_adapter, d->rank, big ? d->extra_ptr256 : d->extra_ptr128,
-                             big ? d->extra256 : d->extra128, (const bf16_t*)vb, p->R, (const bf16_t* const*)Bt,
-                             (const bf16_t*)d->zeros};
+        da = gemm_delta_args{d->order, d->token_adapter, d->rank,
+                             ring_ok ? d->extra_ptr256h : big ? d->extra_ptr256 : d->extra_ptr128,
+                             ring_ok ? d->extra256h : big ? d->extra256 : d->extra128, (const bf16_t*)vb, p->R,
+                             (const bf16_t* const*)Bt, (const bf16_t*)d->zeros};
     }
+    if (ring_ok)
+        return delta ? launch_ring<true>(T, K, N, x, ldx, Wt, ldw, y, ldy, da, stream)
+                     : launch_ring<false>(T, K, N, x, ldx, Wt, ldw, y, ldy, da, stream);
     const bool ktail = (K % BK) != 0;
 #define GEMM_DISPATCH(WB_, D_, KT_) launch_one<WB_, D_, KT_>(T, K, N, x, ldx, Wt, ldw, y, ldy, da, stream)
     if (big) {

@@ -294,15 +294,15 @@ static void build_gemm_tables(lora_plan* p)
     for (int32_t t = 0; t < p->T; ++t)
         if (p->token_adapter[t] < 0) sorted.push_back(t);
 
-    // adapter stages of the rows [p0, p1) of `rows`: one per 64 columns of [v_hi | v_lo] (2 r columns) and
+    // adapter stages of the rows [p0, p1) of `rows`: one per `cols` columns of [v_hi | v_lo] (2 r columns) and
     // adapter; the rows of one adapter are adjacent
-    auto stages_of = [&](const std::vector<int32_t>& rows, int32_t p0, int32_t p1, std::vector<int32_t>* lst) {
+    auto stages_of = [&](const std::vector<int32_t>& rows, int32_t p0, int32_t p1, int32_t cols, std::vector<int32_t>* lst) {
         int32_t n = 0, last = -1;
         for (int32_t q = p0; q < p1; ++q) {
             const int32_t a = p->token_adapter[rows[q]];
             if (a < 0 || a == last) continue;
             last = a;
-            for (int32_t jb = 0; jb * 64 < 2 * p->rank[a]; ++jb, ++n)
+            for (int32_t jb = 0; jb * cols < 2 * p->rank[a]; ++jb, ++n)
                 if (lst) lst->push_back(a | (jb << 24));
         }
         return n;
@@ -311,7 +311,7 @@ static void build_gemm_tables(lora_plan* p)
     const int32_t full = p->T / 256;
     std::vector<int32_t> weight((size_t)full), blocks((size_t)full);
     for (int32_t b = 0; b < full; ++b) {
-        weight[b] = stages_of(sorted, b * 256, b * 256 + 256, nullptr);
+        weight[b] = stages_of(sorted, b * 256, b * 256 + 256, 64, nullptr);
         blocks[b] = b;
     }
     std::stable_sort(blocks.begin(), blocks.end(), [&](int32_t x, int32_t y) { return weight[x] > weight[y]; });
@@ -321,15 +321,17 @@ static void build_gemm_tables(lora_plan* p)
                   p->order.begin() + (size_t)b * 256);
     std::copy(sorted.begin() + (size_t)full * 256, sorted.end(), p->order.begin() + (size_t)full * 256);
 
-    for (int h = 0; h < 2; ++h) {
-        const int32_t rows = h == 0 ? 128 : 256;
-        std::vector<int32_t>& ptr = h == 0 ? p->extra_ptr128 : p->extra_ptr256;
-        std::vector<int32_t>& lst = h == 0 ? p->extra128 : p->extra256;
+    p->max_extra256h = 0;
+    for (int h = 0; h < 3; ++h) {
+        const int32_t rows = h == 0 ? 128 : 256, cols = h == 2 ? 32 : 64;
+        std::vector<int32_t>& ptr = h == 0 ? p->extra_ptr128 : h == 1 ? p->extra_ptr256 : p->extra_ptr256h;
+        std::vector<int32_t>& lst = h == 0 ? p->extra128 : h == 1 ? p->extra256 : p->extra256h;
         const int32_t tiles = (p->T + rows - 1) / rows;
         ptr.assign(1, 0);
         lst.clear();
         for (int32_t tile = 0; tile < tiles; ++tile) {
-            stages_of(p->order, tile * rows, std::min(tile * rows + rows, p->T), &lst);
+            const int32_t n = stages_of(p->order, tile * rows, std::min(tile * rows + rows, p->T), cols, &lst);
+            if (h == 2) p->max_extra256h = std::max(p->max_extra256h, n);
             ptr.push_back((int32_t)lst.size());
         }
     }

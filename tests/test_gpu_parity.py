@@ -190,6 +190,15 @@ def test_cfg5_large(shape):
     run_forward_case(w, n_sample=128)
 
 
+@pytest.mark.parametrize("T,K,N", [(3585, 128, 3600), (3600, 160, 3585), (3585, 200, 3600)])
+def test_large_tile_gemm_ragged_shapes(T, K, N):
+    """The 256 x 256 tile kernels on ragged T and N with few stages: the shortest ring (four stages of 32 k), an odd
+    number of stages, and a K that is no multiple of 32 (staged through registers, with a K tail); base GEMM and
+    fused forward, with mixed ranks, tokens without adapter and several adapters per tile."""
+    w = wl.random_case(700 + K, T, K, N, 40, (8, 16, 24, 32, 64, 128), max_seg=90, frac_none=0.15, scales=(0.5, 2.0))
+    run_forward_case(w, n_sample=160)
+
+
 # ---------------------------------------------------------------- edge cases
 @pytest.mark.parametrize("variant", [B.LORA_VARIANT_TILED, B.LORA_VARIANT_GENERAL])
 def test_ragged_small_cases(variant):

@@ -435,12 +435,12 @@ constexpr int RK = 32;             // k per ring stage; a tile row is 64 bytes =
 constexpr int RING = 4;            // stages in the LDS ring
 constexpr int RING_STAGE = 2048;   // uint4 per stage: 256 W rows x 4 chunks, then 256 x rows x 4 chunks
 
-// Chunk c of row r lives at slot 4 r + (c ^ f(r)).  LDS serves a ds_read_b128 sixteen lanes at a time out of 64
-// banks (256 bytes = 4 rows), so the 16 rows those lanes read must fall into 16 different 16-byte columns: rows
-// with equal r & 3 need different f.  x: 16 consecutive rows -> f = bits 2..3 of r.  W: the MFMA row
-// permutation makes 16 lanes read rows {0..7, 16..23} or {8..15, 24..31} of a block -> f = bit 2 | bit 4 << 1.
-__device__ __forceinline__ int ring_f_x(int row) { return (row >> 2) & 3; }
-__device__ __forceinline__ int ring_f_w(int row) { return (row >> 4) & 3; }
+// Chunk c of row r lives at slot 4 r + (c ^ f(r)).  An operand read (ds_read_b128) has lane l take chunk l / 16 of
+// one of 16 rows: x rows r0 + l % 16, W rows r0 + 16 (l % 16 / 4) + l % 4 (the MFMA row permutation).  The f below
+// make these reads free of bank conflicts (checked with the SQ_LDS_BANK_CONFLICT counter on a read-only kernel:
+// 0 stalled cycles, against half of all LDS cycles for f = bits 2..3 of r, or none).
+__device__ __forceinline__ int ring_f_x(int row) { return (row >> 1) & 3; }
+__device__ __forceinline__ int ring_f_w(int row) { return ((row >> 1) & 1) | ((row >> 3) & 2); }
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 __device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }

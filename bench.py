@@ -41,6 +41,7 @@ MEASURED_TRAFFIC = {("cfg2_decode", "delta_fused_small_kernel"): 46.00e6,
 KERNEL_KEYS = {"shrink_tiled_kernel": "shrink", "expand_tiled_kernel": "expand", "delta_fused_small_kernel": "delta",
                "shrink_stream_kernel": "shrink", "expand_stream_kernel": "expand", "v_split_kernel": "v_split",
                "gemm_tiled_kernel": "gemm", "gemm_tiled_kernel<delta>": "gemm_delta",
+               "gemm_ring_kernel": "gemm", "gemm_ring_kernel<delta>": "gemm_delta",
                "shrink_general_kernel": "shrink", "expand_general_kernel": "expand", "gemm_general_kernel": "gemm"}
 
 

@@ -722,7 +722,7 @@ hipError_t launch_ring(int32_t T, int32_t K, int32_t N, const void* x, int64_t l
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    LORA_LAUNCH(DELTA ? LORA_K_GEMM_TILED_DELTA : LORA_K_GEMM_TILED, (gemm_ring_kernel<DELTA>),
+    LORA_LAUNCH(DELTA ? LORA_K_GEMM_RING_DELTA : LORA_K_GEMM_RING, (gemm_ring_kernel<DELTA>),
                 dim3(tiles_n * tiles_t), dim3(512), lds_bytes, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
                 (bf16_t*)y, ldy, tiles_n, tiles_t, da);
     return hipGetLastError();

@@ -21,6 +21,8 @@ enum lora_kernel_id {
     LORA_K_SHRINK_STREAM,
     LORA_K_EXPAND_STREAM,
     LORA_K_MERGE,
+    LORA_K_GEMM_RING,
+    LORA_K_GEMM_RING_DELTA,
     LORA_K_COUNT
 };
 

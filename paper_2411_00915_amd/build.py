@@ -26,16 +26,56 @@ def _compile(src: str) -> str:
     path = os.path.join(CSRC, src)
     if src.endswith(".hip"):
         cmd = ["hipcc", "-c", path, "-o", obj] + HIP_FLAGS
+        if src in NO_SCRATCH:
+            cmd.append("-Rpass-analysis=kernel-resource-usage")
     else:
         cmd = ["g++", "-c", path, "-o", obj] + HOST_FLAGS
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"compile failed: {' '.join(cmd)}\n{res.stdout}\n{res.stderr}")
     noise = "'-packed-fp32-ops' is not a recognized feature"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l).strip()
+    lines = [l for l in res.stderr.splitlines() if noise not in l]
+    if src in NO_SCRATCH:
+        _check_no_scratch(src, lines, NO_SCRATCH[src])
+        lines = _without_remarks(lines)
+    err = "\n".join(lines).strip()
     if err:
         sys.stderr.write(err + "\n")
     return obj
+
+
+# Kernels that count their outstanding loads by hand (s_waitcnt vmcnt(n) written out next to loads issued from
+# inline assembly): a register spill would put scratch loads and stores, which the same counter counts, between
+# them.  The build fails if the compiler reports scratch use or spills for one of them.
+NO_SCRATCH = {"kernels_gemm.hip": ("gemm_ring_kernel",)}
+REMARK = "[-Rpass-analysis=kernel-resource-usage]"
+
+
+def _without_remarks(lines):
+    """stderr without the resource remarks and the source lines echoed under them"""
+    import re
+    return [l for l in lines
+            if REMARK not in l and not re.match(r"^\s*(\d+\s*)?\|", l) and not re.match(r"^\d+ remarks? generated", l)]
+
+
+def _check_no_scratch(src, lines, kernels):
+    current, seen = None, set()
+    for l in lines:
+        if REMARK not in l:
+            continue
+        text = l.split("remark:", 1)[1].replace(REMARK, "").strip()
+        if text.startswith("Function Name:"):
+            current = text.split(":", 1)[1].strip()
+            continue
+        if current is None or not any(k in current for k in kernels):
+            continue
+        for field in ("ScratchSize [bytes/lane]", "VGPRs Spill", "SGPRs Spill"):
+            if text.startswith(field + ":"):
+                seen.add(current)
+                if int(text.rsplit(":", 1)[1]) != 0:
+                    raise RuntimeError(f"{src}: {current} must not use scratch memory, but the compiler reports {text}")
+    if not seen:
+        raise RuntimeError(f"{src}: no resource report for {kernels}: cannot check that they use no scratch memory")
 
 
 def build(verbose: bool = False) -> str:

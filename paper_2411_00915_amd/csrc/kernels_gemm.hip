@@ -445,7 +445,8 @@ __device__ __forceinline__ int ring_f_w(int row) { return ((row >> 1) & 1) | ((r
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 __device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }
 
-// lane i's 16 bytes at g -> LDS byte address lds_base + 16 i (lds_base wavefront-uniform)
+// lane i's 16 bytes at g -> LDS byte address lds_base + 16 i (lds_base wavefront-uniform).  M0 carries the LDS
+// address; nothing else in these kernels uses M0 (LDS instructions of gfx9 and later do not read it).
 __device__ __forceinline__ void load16_to_lds(const void* g, uint32_t lds_base)
 {
     // (readfirstlane: the operand has to be a scalar register also where the compiler cannot prove it uniform)

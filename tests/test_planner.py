@@ -232,3 +232,21 @@ def test_shape_keyed_tuning_table_roundtrip(tmp_path):
     finally:
         B.lora_tuning_set(**before)
 
+
+def test_build_refuses_scratch_in_kernels_that_count_their_loads():
+    """build.py's guard: a kernel that waits with hand-written s_waitcnt vmcnt(n) must not spill (scratch accesses
+    use the same counter); the compiler's resource report is parsed and a nonzero scratch size fails the build."""
+    from paper_2411_00915_amd import build as b
+    R = b.REMARK
+    head = f"k.hip:1:1: remark: Function Name: _ZN12_GLOBAL__N_116gemm_ring_kernelILb1EEEv {R}"
+    other = f"k.hip:9:1: remark: Function Name: _ZN12_GLOBAL__N_117gemm_tiled_kernelILi4ELb0ELb0EEEv {R}"
+    ok = [head, f"k.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 {R}", f"k.hip:1:1: remark:     VGPRs Spill: 0 {R}",
+          other, f"k.hip:9:1: remark:     ScratchSize [bytes/lane]: 64 {R}"]
+    b._check_no_scratch("k.hip", ok, ("gemm_ring_kernel",))          # other kernels may use scratch
+    for bad in ("ScratchSize [bytes/lane]: 8", "VGPRs Spill: 3"):
+        with pytest.raises(RuntimeError):
+            b._check_no_scratch("k.hip", [head, f"k.hip:1:1: remark:     {bad} {R}"], ("gemm_ring_kernel",))
+    with pytest.raises(RuntimeError):                                  # no report at all: cannot vouch for it
+        b._check_no_scratch("k.hip", [other], ("gemm_ring_kernel",))
+    assert b._without_remarks(ok + ["  459 | {", "      | ^", "2 remarks generated when compiling for gfx950.", "real warning"]) == ["real warning"]
+

@@ -8,20 +8,22 @@
 //
 // The delta enters as extra k-stages of the same pipeline.  The kernel walks
 // the tokens in adapter-sorted order, so a tile of rows holds few adapters; for
-// each adapter a present in a row tile it runs ceil(2 r_a / 64) more stages
-// whose "W tile" is Bt_a[features, ranks] and whose "x tile" is the matching 64
-// columns of [v_hi | v_lo] (v split into two bf16 terms, rows of other adapters
-// zero; Bt_a is simply addressed twice).  Their
+// each adapter a present in a row tile it runs ceil(2 r_a / 64) (ring kernel:
+// / 32) more stages whose "W tile" is Bt_a[features, ranks] and whose "x tile"
+// is the matching columns of [v_hi | v_lo] (v split into two bf16 terms, rows
+// of other adapters zero; Bt_a is simply addressed twice).  Their
 // loads are prefetched like any other stage's: nothing is exposed in an epilogue.
 //
-// x [T,K] and Wt [N,K] are both contraction-index-fastest, so tiles go
-// HBM -> registers -> LDS as 16-byte chunks and come back out of LDS as
-// ready-made v_mfma_f32_32x32x16_bf16 operands (8 consecutive k per lane).
+// x [T,K] and Wt [N,K] are both contraction-index-fastest, so tiles arrive in LDS
+// as 16-byte chunks and come back out of it as ready-made MFMA operands (8
+// consecutive k per lane).  Two kernels:
 //
-//   workgroup tile = 4 wavefronts (2 x 2), each WB x WB MFMA blocks of 32 x 32:
-//     WB = 4: 256 features x 256 tokens x 64 k (large problems; LDS reads per MFMA halved)
+//   gemm_ring_kernel (further down): 256 x 256 tiles of large problems.  8 wavefronts, 16x16x32 MFMA,
+//     loads HBM -> LDS directly into a ring of four 32-k stages.
+//   gemm_tiled_kernel: everything else.  Loads HBM -> registers -> LDS, double buffered (dynamic LDS,
+//     2 x (BM + BT) x 128 bytes); workgroup tile = 4 wavefronts (2 x 2), each WB x WB MFMA blocks of 32 x 32:
+//     WB = 4: 256 features x 256 tokens x 64 k (K no multiple of 32, or more adapter stages than the ring kernel lists)
 //     WB = 2: 128 x 128 x 64 (small problems, less padding waste)
-//   LDS double buffered (dynamic, 2 x (BM + BT) x 128 bytes).
 //
 // Lane roles in v_mfma_f32_32x32x16_bf16 (D = A*B + C, A 32x16, B 16x32):
 //   lane l supplies A[row l%32][k 8*(l/32) .. +7], B[k 8*(l/32) .. +7][col l%32],

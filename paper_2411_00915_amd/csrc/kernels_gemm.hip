@@ -31,6 +31,7 @@
 // MFMA rows carry output features, columns carry tokens.  MFMA row 8q+4h+p of a
 // block stands for feature 16h + 4q + p, so a lane (h = l/32) ends up with the
 // 16 consecutive features 16h .. 16h+15 of its token: 32-byte stores of y.
+#include <atomic>
 #include "device_util.h"
 #include "kernels.h"
 #include "launch.h"
@@ -698,7 +699,7 @@ hipError_t launch_one(int32_t T, int32_t K, int32_t N, const void* x, int64_t ld
     const int tiles_n = (N + BM - 1) / BM, tiles_t = (T + BM - 1) / BM;
     const size_t lds_bytes = (size_t)2 * 2 * BM * 8 * sizeof(uint4) +
                              (DELTA ? META_MAX * sizeof(uint4) + (size_t)(BM * 8 / 256) * 256 * sizeof(int2) : 0);
-    static bool attr_set = false;                 // dynamic LDS above 64 KB has to be allowed once per kernel
+    static std::atomic<bool> attr_set{false};                 // dynamic LDS above 64 KB has to be allowed once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<WB, DELTA, KTAIL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -718,7 +719,7 @@ hipError_t launch_ring(int32_t T, int32_t K, int32_t N, const void* x, int64_t l
     const int tiles_n = (N + 255) / 256, tiles_t = (T + 255) / 256;
     const size_t lds_bytes = (size_t)RING * RING_STAGE * sizeof(uint4) +
                              (DELTA ? META_MAX * sizeof(uint4) + (size_t)2 * 512 * sizeof(int2) : 0);
-    static bool attr_set = false;                 // dynamic LDS above 64 KB has to be allowed once per kernel
+    static std::atomic<bool> attr_set{false};                 // dynamic LDS above 64 KB has to be allowed once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_ring_kernel<DELTA>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);

@@ -2,6 +2,7 @@
 // What is common to the wavefronts of a tile (the adapter matrix) goes through LDS; the big stream (x, y, W)
 // stays private to a wavefront, is fetched as whole cache lines several stages ahead, and reaches the MFMA
 // operand layout through a small LDS patch of the wavefront's own.
+#include <atomic>
 #include "mfma_tile.h"
 #include "kernels.h"
 #include "launch.h"
@@ -421,7 +422,7 @@ hipError_t launch_expand_stream(const lora_plan* p, const lora_dev_tables& d, co
     // dynamic LDS above 64 KB has to be allowed once per kernel (the largest any tile mix needs: 98 KB)
 #define EXPAND_STREAM_LAUNCH(KSMAX_)                                                                                    \
     do {                                                                                                                \
-        static bool attr_set = false;                                                                                   \
+        static std::atomic<bool> attr_set{false};                                                                                   \
         if (!attr_set) {                                                                                                \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&expand_stream_kernel<KSMAX_>),            \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 65536 + 34816);              \
@@ -611,7 +612,7 @@ hipError_t launch_merge_tiled(int32_t L, int32_t N, int32_t K, int32_t r, float 
 #define MERGE_LAUNCH(KS_)                                                                                          \
     do {                                                                                                           \
         constexpr int lds_bytes = 2 * 64 * 4 * KS_ * 16 + 8 * 16 * 68 * 4;                                         \
-        static bool attr_set = false;                                                                              \
+        static std::atomic<bool> attr_set{false};                                                                              \
         if (!attr_set) {                                                                                           \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&merge_stream_kernel<KS_>),           \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);             \

@@ -130,6 +130,16 @@ typedef struct {
     const int32_t* group_offset;    /* [num_groups+1] exclusive prefix sums into perm */
     const lora_tile* shrink_tiles;  int32_t num_shrink_tiles;
     const lora_tile* expand_tiles;  int32_t num_expand_tiles;
+    /* Tables of lora_fused_forward's GEMM (empty when the plan cannot use the MFMA kernels): the row order it walks
+     * (tokens sorted by adapter, then tokens without adapter; whole blocks of 256 rows ordered by decreasing number
+     * of adapter stages), and per tile of 256 rows of that order its adapter stages: one entry
+     * adapter | block << 24 per adapter present and per block of 32 columns of the adapter's [v_hi | v_lo]
+     * (2 r columns). */
+    int32_t        num_gemm_rows;        /* T, or 0 */
+    int32_t        num_gemm_tiles;       /* ceil(T / 256), or 0 */
+    const int32_t* gemm_order;           /* [num_gemm_rows] */
+    const int32_t* gemm_stage_offset;    /* [num_gemm_tiles + 1] exclusive prefix sums into gemm_stage */
+    const int32_t* gemm_stage;           /* [gemm_stage_offset[num_gemm_tiles]] */
 } lora_plan_view;
 
 /*

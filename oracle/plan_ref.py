@@ -13,6 +13,9 @@ are what is *unique* about a correct plan:
 
 Tile lists are the planner's free choice; `check_cover` verifies they tile the
 work exactly once and never mix adapters.
+
+`gemm_tables` derives the tables of the fused forward (unmerged inference in one
+product, section 4.4): the row order and the adapter stages of every 256-row tile.
 """
 from __future__ import annotations
 
@@ -62,3 +65,40 @@ def check_cover(tiles_rows_cols, tok_adapter, perm, extent, adapter_rank=None, r
         assert np.all(canvas[p, :lim] == 1), f"row {p}: cells not covered exactly once"
         assert np.all(canvas[p, lim:] == 0)
     return True
+
+
+def gemm_tables(T, tok_adapter, perm, adapter_rank, rows_per_tile=256, stage_cols=32, weight_cols=64):
+    """Row order and per-tile adapter stages of the fused forward.
+
+    Rows: the tokens with an adapter in `perm` order, then the tokens without one in index order.  The whole blocks
+    of `rows_per_tile` rows are then put in decreasing order of their number of (adapter, block of `weight_cols`
+    columns) pairs, ties in their original order; a last partial block stays last.  A tile's stages: for each
+    adapter in the order its rows appear, one entry adapter | block << 24 per block of `stage_cols` columns of the
+    adapter's 2 r columns."""
+    tok = np.asarray(tok_adapter, dtype=np.int64)
+    rank = np.asarray(adapter_rank, dtype=np.int64)
+    rows = [int(t) for t in perm] + [t for t in range(T) if tok[t] < 0]
+    assert len(rows) == T
+
+    def adapters_of(block):
+        seen = []
+        for t in block:
+            a = int(tok[t])
+            if a >= 0 and (not seen or seen[-1] != a):
+                seen.append(a)
+        return seen
+
+    def blocks_of(a, cols):
+        return -(-2 * int(rank[a]) // cols)
+
+    full = T // rows_per_tile
+    blocks = [rows[b * rows_per_tile:(b + 1) * rows_per_tile] for b in range(full)]
+    weight = [sum(blocks_of(a, weight_cols) for a in adapters_of(blk)) for blk in blocks]
+    idx = sorted(range(full), key=lambda b: -weight[b])          # sorted() is stable
+    order = [t for b in idx for t in blocks[b]] + rows[full * rows_per_tile:]
+    offset, stages = [0], []
+    for t0 in range(0, T, rows_per_tile):
+        for a in adapters_of(order[t0:t0 + rows_per_tile]):
+            stages.extend(a | (jb << 24) for jb in range(blocks_of(a, stage_cols)))
+        offset.append(len(stages))
+    return np.asarray(order, np.int32), np.asarray(offset, np.int32), np.asarray(stages, np.int32)

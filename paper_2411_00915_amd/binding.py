@@ -52,7 +52,9 @@ class PlanView(ctypes.Structure):
                 ("v_parts", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("token_adapter", _i32p), ("perm", _i32p), ("group_adapter", _i32p), ("group_offset", _i32p),
                 ("shrink_tiles", ctypes.POINTER(Tile)), ("num_shrink_tiles", ctypes.c_int32),
-                ("expand_tiles", ctypes.POINTER(Tile)), ("num_expand_tiles", ctypes.c_int32)]
+                ("expand_tiles", ctypes.POINTER(Tile)), ("num_expand_tiles", ctypes.c_int32),
+                ("num_gemm_rows", ctypes.c_int32), ("num_gemm_tiles", ctypes.c_int32),
+                ("gemm_order", _i32p), ("gemm_stage_offset", _i32p), ("gemm_stage", _i32p)]
 
 
 _vp = ctypes.c_void_p
@@ -254,7 +256,11 @@ def lora_plan_export(plan: Plan) -> dict:
                 group_adapter=arr(v.group_adapter, v.num_groups),
                 group_offset=arr(v.group_offset, v.num_groups + 1),
                 shrink_tiles=tiles(v.shrink_tiles, v.num_shrink_tiles),
-                expand_tiles=tiles(v.expand_tiles, v.num_expand_tiles))
+                expand_tiles=tiles(v.expand_tiles, v.num_expand_tiles),
+                gemm_order=arr(v.gemm_order, v.num_gemm_rows),
+                gemm_stage_offset=arr(v.gemm_stage_offset, v.num_gemm_tiles + 1 if v.num_gemm_tiles else 0),
+                gemm_stage=(arr(v.gemm_stage, int(v.gemm_stage_offset[v.num_gemm_tiles])) if v.num_gemm_tiles
+                            else np.zeros(0, np.int32)))
 
 
 def lora_plan_upload(plan: Plan, stream=None):

@@ -433,6 +433,12 @@ extern "C" lora_status lora_plan_export(const lora_plan* p, lora_plan_view* v)
     v->num_shrink_tiles = (int32_t)p->shrink_tiles.size();
     v->expand_tiles = p->expand_tiles.data();
     v->num_expand_tiles = (int32_t)p->expand_tiles.size();
+    const bool gemm_tables = !p->extra_ptr256h.empty() && (int32_t)p->order.size() == p->T;
+    v->num_gemm_rows = gemm_tables ? p->T : 0;
+    v->num_gemm_tiles = gemm_tables ? (int32_t)p->extra_ptr256h.size() - 1 : 0;
+    v->gemm_order = gemm_tables ? p->order.data() : nullptr;
+    v->gemm_stage_offset = gemm_tables ? p->extra_ptr256h.data() : nullptr;
+    v->gemm_stage = gemm_tables ? p->extra256h.data() : nullptr;
     return LORA_OK;
 }
 

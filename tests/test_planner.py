@@ -34,6 +34,21 @@ def _check_tables(w, v):
     return tok, perm
 
 
+def _check_gemm_tables(w, v, tok, perm):
+    """the fused forward's row order and adapter stages, bit for bit against the reference derivation"""
+    if v["kernel_family"] != B.LORA_VARIANT_TILED:
+        return
+    if w.T == 0:
+        assert v["gemm_order"].shape[0] == 0 and v["gemm_stage"].shape[0] == 0
+        return
+    assert v["gemm_order"].shape[0] == w.T and v["gemm_stage_offset"].shape[0] == (w.T + 255) // 256 + 1
+    order, offset, stages = plan_ref.gemm_tables(w.T, tok, perm, w.adapter_rank)
+    assert np.array_equal(np.sort(v["gemm_order"]), np.arange(w.T))          # a permutation of the tokens
+    assert np.array_equal(v["gemm_order"], order)
+    assert np.array_equal(v["gemm_stage_offset"], offset)
+    assert np.array_equal(v["gemm_stage"], stages)
+
+
 def _check_tiles(w, v, tok, perm):
     if v["kernel_family"] != B.LORA_VARIANT_TILED:
         assert v["shrink_tiles"].shape[0] == 0 and v["expand_tiles"].shape[0] == 0
@@ -66,6 +81,7 @@ def test_config_tables_bit_exact(name):
     v, q = _export(w)
     tok, perm = _check_tables(w, v)
     _check_tiles(w, v, tok, perm)
+    _check_gemm_tables(w, v, tok, perm)
     R = max(8, (int(w.adapter_rank.max()) + 7) // 8 * 8)
     assert q[0] == R and q[1] == v["v_parts"] * w.T * R * 4 and q[2] >= q[1] and q[2] % 256 == 0
     expect = B.LORA_VARIANT_GENERAL if w.dtype == "f32" else B.LORA_VARIANT_TILED
@@ -86,6 +102,7 @@ def test_random_tables_and_tiles(segs, ranks, N):
     v, _ = _export(w, B.LORA_VARIANT_TILED)
     tok, perm = _check_tables(w, v)
     _check_tiles(w, v, tok, perm)
+    _check_gemm_tables(w, v, tok, perm)
 
 
 def test_plan_is_deterministic():

@@ -207,6 +207,58 @@ def test_large_tile_gemm_with_more_adapter_stages_than_the_tile_lists_hold():
     run_forward_case(w, n_sample=160)
 
 
+@pytest.mark.parametrize("shape", ["decode", "prefill"])
+def test_hip_graph_replays_match_the_eager_calls(shape):
+    """lora_delta and lora_fused_forward captured into a HIP graph: every replay, with eager calls of the same plan
+    and synchronisations in between, gives bit for bit what the eager calls give (the single-launch decode kernel
+    keeps hand-off counters across launches; the streaming and GEMM kernels set function attributes on first use)."""
+    if shape == "decode":      # one launch for shrink + expand
+        w = wl.random_case(901, 180, 512, 768, 24, (8, 16, 32, 64), max_seg=3, frac_none=0.1)
+    else:                      # streaming shrink / expand, ring GEMM with adapter stages
+        w = wl.random_case(902, 3600, 1024, 3600, 12, (16, 32, 64, 128), max_seg=300, frac_none=0.1)
+    dl = device.to_device(w, DEV, with_w=True)
+    tdt = device.torch_dtype(w)
+    plan = device.make_plan(w)
+    R, v_bytes, ws_bytes = B.lora_plan_query(plan)
+    B.lora_plan_upload(plan)
+    y0 = torch.from_numpy(_y_in(w)).to(DEV, tdt)
+
+    def buffers():
+        return (torch.zeros(max(v_bytes // 4, 1), dtype=torch.float32, device=DEV), y0.clone(),
+                torch.empty(w.T, w.N, dtype=tdt, device=DEV), torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV))
+
+    def run(v, y, yf, ws, stream=None):
+        B.lora_delta(plan, dl.x, w.K, dl.At_ptrs, dl.Bt_ptrs, v, y, w.N, 1.0, stream)
+        B.lora_fused_forward(plan, dl.x, w.K, dl.Wt, w.K, dl.At_ptrs, dl.Bt_ptrs, yf, w.N, ws, ws.numel(), stream)
+
+    v_e, y_e, yf_e, ws_e = buffers()
+    run(v_e, y_e, yf_e, ws_e)                                  # eager: also the first use of every kernel
+    torch.cuda.synchronize()
+
+    v_g, y_g, yf_g, ws_g = buffers()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            run(v_g, y_g, yf_g, ws_g, side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for replay in range(4):
+        y_g.copy_(y0)                                          # lora_delta accumulates onto y
+        yf_g.fill_(3.0)
+        v_g.fill_(-7.0)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_g, y_e), f"lora_delta: replay {replay} differs from the eager call"
+        assert torch.equal(yf_g, yf_e), f"lora_fused_forward: replay {replay} differs from the eager call"
+        v2, y2, yf2, ws2 = buffers()                           # eager work of the same plan between the replays
+        run(v2, y2, yf2, ws2)
+        torch.cuda.synchronize()
+        assert torch.equal(y2, y_e) and torch.equal(yf2, yf_e)
+    plan.destroy()
+
+
 # ---------------------------------------------------------------- edge cases
 @pytest.mark.parametrize("variant", [B.LORA_VARIANT_TILED, B.LORA_VARIANT_GENERAL])
 def test_ragged_small_cases(variant):

@@ -36,6 +36,12 @@
  * not destroy a plan while work that uses it is still in flight (the plan's
  * device tables are recycled for later plans, not synchronised on).
  *
+ * THREADS.  Distinct plans may be created, used and destroyed from distinct
+ * host threads at the same time (the pool of recycled device tables and the
+ * timing records are locked).  One plan is used by one thread, on one stream,
+ * at a time.  The tunables (lora_tuning_set) and the timing switch are
+ * process-wide: set them while no other thread plans or launches.
+ *
  * ERRORS.  Every function returns a lora_status; nothing throws.  All
  * descriptor validation happens in lora_plan_create, which is pure host code
  * and needs no GPU.  Compute calls check pointers, leading dimensions and

@@ -301,7 +301,10 @@ const char* lora_status_str(lora_status s);
  * (adapter groups with at least this many tokens use 64-token shrink tiles),
  * shrink_stream_min_tokens (batches with at least this many adapter tokens, ranks
  * <= 128 and K >= 1024 use the streaming shrink: tiles of up to 128 tokens over all
- * rank rows, At shared through LDS; the expand then streams likewise),
+ * rank rows, At shared through LDS; the expand then streams likewise; smaller
+ * batches that cannot run as lora_delta's single launch and hold an adapter group
+ * of at least 64 tokens, or 128 tokens in all, use them too; 2^30 or more
+ * switches the streaming kernels off),
  * shrink_stream_wgs (the streaming kernels use 64-token tiles when 128-token tiles
  * would give fewer workgroups than this), expand_stream_stages (stages of 64
  * features per wavefront that one workgroup of the streaming expand walks).

@@ -85,9 +85,23 @@ static void build_tiles(lora_plan* p)
     const int G = (int)p->group_adapter.size();
     // Prefill-sized batches (ranks up to 128) take the streaming shrink; its tiles hold 128 tokens, or 64
     // when 128 would leave the launch with few workgroups even after the K split.
-    int32_t max_rank = 0;
-    for (int g = 0; g < G; ++g) max_rank = std::max(max_rank, p->rank[p->group_adapter[g]]);
-    p->shrink_stream = (int64_t)p->perm.size() >= tu.shrink_stream_min_tokens && max_rank <= 128 && p->K >= 1024;
+    // Smaller batches take it too when they cannot run as the single decode launch (a group too long or a rank
+    // too high for the small tiles) and have a group of at least 64 tokens or 128 tokens in all: measured, the
+    // streaming kernels then need 18-33 us where the 32- and 64-token tiles of the other family need 24-52.
+    int32_t max_rank = 0, max_group = 0;
+    bool small_tiles_only = true;
+    for (int g = 0; g < G; ++g) {
+        const int32_t r = p->rank[p->group_adapter[g]], m = p->group_offset[g + 1] - p->group_offset[g];
+        max_rank = std::max(max_rank, r);
+        max_group = std::max(max_group, m);
+        if (m >= tu.shrink_tb2_min_rows || m >= tu.shrink_tb4_min_rows || m >= tu.expand_tb2_min_rows ||
+            m >= tu.expand_tb4_min_rows || r > 64)
+            small_tiles_only = false;
+    }
+    const int64_t active = (int64_t)p->perm.size();
+    p->shrink_stream = max_rank <= 128 && p->K >= 1024 &&
+                       (active >= tu.shrink_stream_min_tokens ||
+                        (tu.shrink_stream_min_tokens < (1 << 30) && !small_tiles_only && (max_group >= 64 || active >= 128)));
     p->expand_stream = p->shrink_stream && p->N >= 64;
     p->expand_stream_ks = 1;
     p->expand_stream_lds = 0;

@@ -267,3 +267,29 @@ def test_build_refuses_scratch_in_kernels_that_count_their_loads():
         b._check_no_scratch("k.hip", [other], ("gemm_ring_kernel",))
     assert b._without_remarks(ok + ["  459 | {", "      | ^", "2 remarks generated when compiling for gfx950.", "real warning"]) == ["real warning"]
 
+
+def test_streaming_tiles_for_small_batches_with_long_groups():
+    """Below shrink_stream_min_tokens the planner still picks the streaming tiles (up to 128 tokens of one adapter
+    over all its rank rows) when the batch cannot run as the single decode launch and holds a group of 64 tokens
+    or 128 tokens in all; batches of short groups keep the 16-token tiles; 2^30 switches streaming off."""
+    def shrink_rows(T, n_a, r, **tune):
+        before = B.lora_tuning_get()
+        try:
+            if tune:
+                B.lora_tuning_set(**tune)
+            seg = np.linspace(0, T, n_a + 1).astype(np.int32)
+            w = wl.Workload("s", "bf16", T, 4096, 4096, seg, np.arange(n_a, dtype=np.int32), np.full(n_a, r, np.int32),
+                            np.ones(n_a, np.float32), np.zeros((T, 4096), np.float32), None)
+            v, _ = _export(w, B.LORA_VARIANT_TILED)
+            tok, perm = _check_tables(w, v)
+            _check_tiles(w, v, tok, perm)
+            return int(v["shrink_tiles"][:, 2].max()), int(v["shrink_tiles"][:, 4].max())     # tokens, rank rows of the largest tile
+        finally:
+            B.lora_tuning_set(**before)
+    # (a streaming tile spans all rank rows of its adapter; the other family's tiles at most 64)
+    assert shrink_rows(256, 1, 128) == (64, 128)                # one group of 256 tokens: streaming, 64-token tiles (few workgroups)
+    assert shrink_rows(64, 1, 128) == (64, 128)                 # one group of 64 tokens
+    assert shrink_rows(256, 16, 128) == (16, 128)               # 16 tokens per group, rank 128, 256 tokens in all: streaming
+    assert shrink_rows(256, 16, 64)[0] == 16 and shrink_rows(256, 16, 64)[1] <= 32   # short groups, ranks <= 64: 16-token tiles of the decode launch
+    assert shrink_rows(48, 4, 128)[1] <= 64                     # 48 tokens in groups of 12: too small for the streaming kernels
+    assert shrink_rows(256, 1, 128, shrink_stream_min_tokens=1 << 30)[1] <= 64       # streaming switched off

@@ -14,8 +14,9 @@ are what is *unique* about a correct plan:
 Tile lists are the planner's free choice; `check_cover` verifies they tile the
 work exactly once and never mix adapters.
 
-`gemm_tables` derives the tables of the fused forward (unmerged inference in one
-product, section 4.4): the row order and the adapter stages of every 256-row tile.
+`check_gemm_tables` does the same for the tables of the fused forward (unmerged
+inference in one product, section 4.4): a row order that is a permutation, and per
+tile of rows exactly one stage per adapter present and block of its columns.
 """
 from __future__ import annotations
 
@@ -67,38 +68,25 @@ def check_cover(tiles_rows_cols, tok_adapter, perm, extent, adapter_rank=None, r
     return True
 
 
-def gemm_tables(T, tok_adapter, perm, adapter_rank, rows_per_tile=256, stage_cols=32, weight_cols=64):
-    """Row order and per-tile adapter stages of the fused forward.
+def check_gemm_tables(T, tok_adapter, adapter_rank, order, stage_offset, stages, rows_per_tile=256, stage_cols=32):
+    """Validity of the fused forward's tables (they are the planner's free choice; only this is fixed).
 
-    Rows: the tokens with an adapter in `perm` order, then the tokens without one in index order.  The whole blocks
-    of `rows_per_tile` rows are then put in decreasing order of their number of (adapter, block of `weight_cols`
-    columns) pairs, ties in their original order; a last partial block stays last.  A tile's stages: for each
-    adapter in the order its rows appear, one entry adapter | block << 24 per block of `stage_cols` columns of the
-    adapter's 2 r columns."""
+    The fused forward adds s_a (x A_a) B_a to the base product as extra contraction length: for every adapter a the
+    columns of [v_hi | v_lo] (2 r_a of them) are cut into blocks of `stage_cols`, and a tile of rows must run one
+    stage per (adapter present in the tile, block) -- each exactly once, or the delta of some token is dropped or
+    counted twice -- and none for adapters it does not hold.  `order` must visit every token exactly once."""
     tok = np.asarray(tok_adapter, dtype=np.int64)
     rank = np.asarray(adapter_rank, dtype=np.int64)
-    rows = [int(t) for t in perm] + [t for t in range(T) if tok[t] < 0]
-    assert len(rows) == T
-
-    def adapters_of(block):
-        seen = []
-        for t in block:
-            a = int(tok[t])
-            if a >= 0 and (not seen or seen[-1] != a):
-                seen.append(a)
-        return seen
-
-    def blocks_of(a, cols):
-        return -(-2 * int(rank[a]) // cols)
-
-    full = T // rows_per_tile
-    blocks = [rows[b * rows_per_tile:(b + 1) * rows_per_tile] for b in range(full)]
-    weight = [sum(blocks_of(a, weight_cols) for a in adapters_of(blk)) for blk in blocks]
-    idx = sorted(range(full), key=lambda b: -weight[b])          # sorted() is stable
-    order = [t for b in idx for t in blocks[b]] + rows[full * rows_per_tile:]
-    offset, stages = [0], []
-    for t0 in range(0, T, rows_per_tile):
-        for a in adapters_of(order[t0:t0 + rows_per_tile]):
-            stages.extend(a | (jb << 24) for jb in range(blocks_of(a, stage_cols)))
-        offset.append(len(stages))
-    return np.asarray(order, np.int32), np.asarray(offset, np.int32), np.asarray(stages, np.int32)
+    order = np.asarray(order, dtype=np.int64)
+    stage_offset = np.asarray(stage_offset, dtype=np.int64)
+    stages = np.asarray(stages, dtype=np.int64)
+    assert np.array_equal(np.sort(order), np.arange(T)), "row order is not a permutation of the tokens"
+    n_tiles = -(-T // rows_per_tile)
+    assert stage_offset.shape[0] == n_tiles + 1 and stage_offset[0] == 0 and stage_offset[-1] == stages.shape[0]
+    assert np.all(np.diff(stage_offset) >= 0)
+    for tile in range(n_tiles):
+        present = {int(a) for a in tok[order[tile * rows_per_tile:(tile + 1) * rows_per_tile]] if a >= 0}
+        want = sorted((a, jb) for a in present for jb in range(-(-2 * int(rank[a]) // stage_cols)))
+        got = sorted((int(s) & 0xffffff, int(s) >> 24) for s in stages[stage_offset[tile]:stage_offset[tile + 1]])
+        assert got == want, f"tile {tile}: adapter stages do not cover its adapters' columns exactly once"
+    return True

@@ -309,3 +309,48 @@ def test_numerical_budget_of_bf16_output():
     y = oracle.forward(w.x, w.W, w.token_adapter(), _adapters(w))
     nrm, elem = oracle.error_metrics(wl.round_to_bf16(y.astype(np.float32)), y)
     assert nrm <= 2e-3 and elem <= 2.0 ** -8 * 1.01
+
+
+def test_error_metrics_hand_worked_values():
+    """The two error measures every parity verdict passes through, against values worked by hand.
+
+    Reference [[3, 4], [0, 0.005]]: Frobenius norm sqrt(9 + 16 + 0.000025).  Candidate differs by
+    (+0.3, -0.4, +1.0, +0.001): difference norm sqrt(0.09 + 0.16 + 1 + 0.000001).  Entries whose reference is
+    at most the 1e-2 threshold (0 and 0.005) are left out of the elementwise measure, whatever their error
+    (1.0 and 20 %), so it is max(0.3/3, 0.4/4) = 0.1."""
+    ref = np.array([[3.0, 4.0], [0.0, 0.005]])
+    got = ref + np.array([[0.3, -0.4], [1.0, 0.001]])
+    nrm, elem = oracle.error_metrics(got, ref)
+    assert nrm == pytest.approx(np.sqrt(1.250001) / np.sqrt(25.000025), rel=1e-14)
+    assert elem == pytest.approx(0.1, rel=1e-12)
+    # sign of the difference and of the reference do not matter; the denominator is |reference|, not |candidate|
+    nrm2, elem2 = oracle.error_metrics(-got, -ref)
+    assert (nrm2, elem2) == (nrm, elem)
+    assert oracle.error_metrics(np.array([1.0]), np.array([2.0]))[1] == pytest.approx(0.5)     # not 1/1
+    assert oracle.error_metrics(np.array([2.0]), np.array([1.0]))[1] == pytest.approx(1.0)
+    # the threshold is strict and applies to |reference|: 0.01 itself is excluded, the next float is included
+    above = np.nextafter(0.01, 1.0)
+    assert oracle.error_metrics(np.array([0.02]), np.array([0.01]))[1] == 0.0
+    assert oracle.error_metrics(np.array([2 * above]), np.array([above]))[1] == pytest.approx(1.0)
+    assert oracle.error_metrics(np.array([-0.03]), np.array([-above]))[1] == pytest.approx(2.0, rel=1e-6)
+    # an entry just under and just over the 1e-2 elementwise tolerance, at a reference value of 0.5
+    _, under = oracle.error_metrics(np.array([0.5 * (1 + 0.0099)]), np.array([0.5]))
+    _, over = oracle.error_metrics(np.array([0.5 * (1 - 0.0101)]), np.array([0.5]))
+    assert under == pytest.approx(0.0099, rel=1e-9) and under <= 1e-2 < over == pytest.approx(0.0101, rel=1e-9)
+    # the same for the normwise tolerance 2e-3: a single wrong entry of 100 equal ones, error e -> e / 10
+    ref = np.ones((10, 10))
+    got = ref.copy()
+    got[3, 7] += 0.0199
+    assert oracle.error_metrics(got, ref)[0] == pytest.approx(0.00199, rel=1e-9)
+    got[3, 7] = 1.0201
+    assert oracle.error_metrics(got, ref)[0] > 2e-3
+    # zero-norm reference: the normwise measure falls back to the absolute norm of the difference (no division
+    # by zero, and a wrong candidate does not pass as 0); nothing is above the threshold, so elementwise is 0
+    nrm0, elem0 = oracle.error_metrics(np.array([[0.0, 3.0], [4.0, 0.0]]), np.zeros((2, 2)))
+    assert nrm0 == 5.0 and elem0 == 0.0
+    assert oracle.error_metrics(np.zeros((2, 2)), np.zeros((2, 2))) == (0.0, 0.0)
+    # float32 / bf16-like inputs are widened, not compared in their own precision
+    a32 = np.array([1.0 + 2.0 ** -20], dtype=np.float32)
+    assert oracle.error_metrics(a32, np.array([1.0]))[0] == 2.0 ** -20
+    # a custom threshold moves the mask only
+    assert oracle.error_metrics(np.array([0.002, 1.0]), np.array([0.001, 1.0]), threshold=1e-4)[1] == pytest.approx(1.0)

@@ -35,18 +35,15 @@ def _check_tables(w, v):
 
 
 def _check_gemm_tables(w, v, tok, perm):
-    """the fused forward's row order and adapter stages, bit for bit against the reference derivation"""
+    """the fused forward's row order and adapter stages: a permutation, and every tile's stages cover the columns of
+    exactly the adapters its rows carry, once each (the order of rows and stages is the planner's choice)"""
     if v["kernel_family"] != B.LORA_VARIANT_TILED:
         return
     if w.T == 0:
         assert v["gemm_order"].shape[0] == 0 and v["gemm_stage"].shape[0] == 0
         return
-    assert v["gemm_order"].shape[0] == w.T and v["gemm_stage_offset"].shape[0] == (w.T + 255) // 256 + 1
-    order, offset, stages = plan_ref.gemm_tables(w.T, tok, perm, w.adapter_rank)
-    assert np.array_equal(np.sort(v["gemm_order"]), np.arange(w.T))          # a permutation of the tokens
-    assert np.array_equal(v["gemm_order"], order)
-    assert np.array_equal(v["gemm_stage_offset"], offset)
-    assert np.array_equal(v["gemm_stage"], stages)
+    assert v["gemm_order"].shape[0] == w.T
+    plan_ref.check_gemm_tables(w.T, tok, w.adapter_rank, v["gemm_order"], v["gemm_stage_offset"], v["gemm_stage"])
 
 
 def _check_tiles(w, v, tok, perm):

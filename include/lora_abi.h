@@ -293,8 +293,9 @@ const char* lora_status_str(lora_status s);
  * when every tile is small, 1..16), shrink_small_jb (rank blocks of 16 per shrink
  * tile for adapter groups below shrink_tb2_min_rows, 1..2), shrink_target_wgs
  * (small launches split K over up to 4 workgroups per tile until they have this
- * many workgroups), fused_spin_limit (lora_delta's single launch: polls an expand
- * block waits for its shrink blocks, plus one; 1 = never wait, always recompute),
+ * many workgroups), fused_wait_us (lora_delta's single launch: microseconds an expand
+ * block waits for its shrink blocks before it computes its rows of v itself, plus one;
+ * 1 = never wait, always recompute; default 2 ms),
  * fused_delay (lora_delta's single launch: head start given to the shrink blocks'
  * loads, units of about 0.4 us, plus one), expand_wave_bytes_big (expand_wave_bytes
  * for adapter groups of at least expand_tb2_min_rows tokens), shrink_tb4_min_rows

@@ -43,13 +43,13 @@ def tables(T, seg_indptr, seg_adapter, adapter_rank):
             group_offset.astype(np.int32))
 
 
-def check_cover(tiles_rows_cols, tok_adapter, perm, extent, adapter_rank=None, rank_axis=False):
+def check_cover(tiles_rows_cols, tok_adapter, perm, extent, adapter_rank=None, rank_axis=False, rows=None):
     """Paint every tile onto a [T_active x extent] canvas and require each cell
     of an active token to be covered exactly once.
 
     tiles_rows_cols: iterable of (adapter, row0, nrows, c0, cn) with rows
     indexing `perm` and columns indexing [0, extent) -- or, when rank_axis is
-    set, [0, rank(adapter)).
+    set, [0, rank(adapter)).  rows: optional boolean mask over perm; rows outside it must not be covered at all.
     """
     n_act = len(perm)
     canvas = np.zeros((n_act, extent), dtype=np.int32)
@@ -63,6 +63,9 @@ def check_cover(tiles_rows_cols, tok_adapter, perm, extent, adapter_rank=None, r
         canvas[row0:row0 + nrows, c0:c0 + cn] += 1
     for p in range(n_act):
         lim = int(adapter_rank[tok_adapter[perm[p]]]) if rank_axis else extent
+        if rows is not None and not rows[p]:
+            assert np.all(canvas[p] == 0), f"row {p}: covered although its group has no such part"
+            continue
         assert np.all(canvas[p, :lim] == 1), f"row {p}: cells not covered exactly once"
         assert np.all(canvas[p, lim:] == 0)
     return True

@@ -13,7 +13,9 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblora_amd.so")
+# LORA_AMD_LIBRARY names another build of the same library (instrumented or experimental builds); unset, the
+# library built in-tree is the one that runs
+LIB_PATH = os.environ.get("LORA_AMD_LIBRARY") or os.path.join(_HERE, "liblora_amd.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -106,7 +108,7 @@ EXPORTED = ["lora_timing_begin", "lora_timing_end", "lora_timing_read", "lora_ke
 
 TUNING_FIELDS = ["shrink_waves", "shrink_tb2_min_rows", "shrink_max_jb", "expand_wave_bytes",
                  "expand_tb2_min_rows", "expand_tb4_min_rows", "tiled_min_tokens",
-                 "shrink_small_waves", "shrink_small_jb", "shrink_target_wgs", "fused_spin_limit", "fused_delay", "expand_wave_bytes_big", "shrink_tb4_min_rows",
+                 "shrink_small_waves", "shrink_small_jb", "shrink_target_wgs", "fused_wait_us", "fused_delay", "expand_wave_bytes_big", "shrink_tb4_min_rows",
                  "shrink_stream_min_tokens", "shrink_stream_wgs", "expand_stream_stages"]
 
 

@@ -154,30 +154,32 @@ bool tiled_call_ok(const void* base, int64_t ld) { return !misaligned(base, 16) 
 
 }  // namespace
 
-extern "C" void lora_plan_destroy(lora_plan* p)
+// Releases a plan's device tables (called by lora_plan_destroy, planner.cpp, through lora_plan_device_release).
+// Contract: the caller destroys a plan only after the work that uses it has finished.  The tables go back to a
+// small cache for later plans.
+static void release_device_tables(lora_plan* p)
 {
-    if (!p) return;
-    if (p->d_buf) {
-        // Contract: the caller destroys a plan only after the work that uses it has
-        // finished.  The tables go back to a small cache for later plans.
-        int cur = -1;
-        (void)hipGetDevice(&cur);
-        if (cur != p->device) (void)hipSetDevice(p->device);
-        bool kept = false;
-        {
-            std::lock_guard<std::mutex> lock(g_cache_mutex);
-            if (g_cache.size() < kCacheMax) {
-                g_cache.push_back(cached_buf{p->device, p->d_bytes, p->d_buf, p->h_stage});
-                kept = true;
-            }
+    int cur = -1;
+    (void)hipGetDevice(&cur);
+    if (cur != p->device) (void)hipSetDevice(p->device);
+    bool kept = false;
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        if (g_cache.size() < kCacheMax) {
+            g_cache.push_back(cached_buf{p->device, p->d_bytes, p->d_buf, p->h_stage});
+            kept = true;
         }
-        if (!kept) {
-            (void)hipFree(p->d_buf);
-            (void)hipHostFree(p->h_stage);
-        }
-        if (cur != p->device && cur >= 0) (void)hipSetDevice(cur);
     }
-    delete p;
+    if (!kept) {
+        (void)hipFree(p->d_buf);
+        (void)hipHostFree(p->h_stage);
+    }
+    if (cur != p->device && cur >= 0) (void)hipSetDevice(cur);
+    p->d_buf = nullptr;
+    p->h_stage = nullptr;
+}
+namespace {
+struct install_release { install_release() { lora_plan_device_release = release_device_tables; } } g_install_release;
 }
 
 extern "C" lora_status lora_plan_upload(lora_plan* p, void* hip_stream)
@@ -330,3 +332,4 @@ extern "C" lora_status lora_fused_forward(lora_plan* p, const void* x, int64_t l
         e = launch_gemm_general(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy, p, &d, v, d_Bt_ptrs, stream);
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
 }
+

@@ -494,9 +494,9 @@ hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, con
 // launches completed before it, and its expand tiles wait for
 // done[g] >= (e+1) * need[g].  There is no counter shared by all blocks.
 // Producers never wait, and blocks are dispatched in index order, so all
-// producers are dispatched before the first consumer.  Independently of that the wait is bounded: after spin_limit polls
-// an expand block stops waiting and computes its v rows itself from x and At
-// (slow, exact), so every wavefront reaches the end of the kernel in any case.
+// producers are dispatched before the first consumer.  Independently of that the wait is bounded in time: once
+// wait_ticks of the device's constant-rate wall clock have passed, an expand block stops waiting and computes
+// its v rows itself from x and At (slow, exact), so every wavefront reaches the end of the kernel in any case.
 struct lora_sync_slot {          // one per adapter group, 128 bytes
     unsigned long long done;
     unsigned long long cons;
@@ -513,7 +513,7 @@ __device__ __forceinline__ void fused_expand_item(
     const lora_tile tile, const int32_t* __restrict__ rows, const float* __restrict__ scale,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
     const float* v, lora_vspec vsp, const bf16_t* __restrict__ Bt, bf16_t* __restrict__ y, int64_t ldy, int N,
-    float beta, lora_sync_slot* sync, int spin_limit, int delay, float* vt, int* flag)
+    float beta, lora_sync_slot* sync, long long wait_ticks, int delay, float* vt, int* flag)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
@@ -570,9 +570,11 @@ __device__ __forceinline__ void fused_expand_item(
     // ---- wait for the group's shrink tiles (bounded) -----------------------
     if (threadIdx.x == 0) {
         const unsigned long long target = (ld_agent(&slot->cons) / ncons + 1ull) * need;
+        const long long t0 = (long long)wall_clock64();
         int ok = 0;
-        for (int it = 0; it <= spin_limit; ++it) {
+        for (;;) {
             if (ld_agent(&slot->done) >= target) { ok = 1; break; }
+            if ((long long)wall_clock64() - t0 >= wait_ticks) break;       // wait_ticks = 0: one look, no waiting
             __builtin_amdgcn_s_sleep(2);
         }
         *flag = ok;
@@ -580,7 +582,11 @@ __device__ __forceinline__ void fused_expand_item(
     __syncthreads();
     const bool published = *flag != 0;
     if (published) {
-        // v is read with agent-scope loads, which do not use lines cached before the count was seen
+        // Thread 0 saw the count (its load returned before it reached the barrier above), so every producer's
+        // v stores had been acknowledged by then.  v is read with agent-scope (sc1) loads, issued after the
+        // barrier: they are served by the level the stores were written through to, never by a line this CU
+        // or this XCD's L2 cached earlier (v is rewritten every launch).  The fence keeps the compiler from
+        // moving them up.
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         const int row = threadIdx.x >> 4, j4 = (threadIdx.x & 15) * 4;
         if (row < tile.nrows && j4 < r) {
@@ -691,7 +697,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
     const int32_t* __restrict__ shrink_rows, const int32_t* __restrict__ expand_rows, const float* __restrict__ scale,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* const* __restrict__ At_ptrs, int K,
     float* v, lora_vspec vsp, const bf16_t* const* __restrict__ Bt_ptrs,
-    bf16_t* __restrict__ y, int64_t ldy, int N, float beta, lora_sync_slot* sync, int spin_limit, int delay,
+    bf16_t* __restrict__ y, int64_t ldy, int N, float beta, lora_sync_slot* sync, long long wait_ticks, int delay,
     int n_adapters)
 {
     __shared__ floatx4 lds[4 * 2 * 64];      // 8 KB: shrink reduction buffer, or v rows [16][64] of an expand tile
@@ -717,9 +723,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
         uint4* patch = patches + (threadIdx.x >> 6) * 256;
         if (jb == 1) shrink_tile<1, 1, 8, true>(tile, rows, x, ldx, At, K, v, vsp, lds, patch);
         else shrink_tile<1, 2, 4, true>(tile, rows, x, ldx, At, K, v, vsp, lds, patch);
-        // publish: the write-through stores of every thread have completed before the
-        // block's count is added (no L2 write-back: that would cost microseconds per block)
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        // Publish.  v was stored with agent-scope (sc1) stores, which are written through to the level all
+        // XCDs share instead of staying in this XCD's L2.  A store's acknowledgement is what takes it off the
+        // wavefront's vmcnt counter, so after s_waitcnt vmcnt(0) this thread's part of v is visible to every
+        // agent-scope load on the device.  Every storing thread waits that way BEFORE the barrier; only then
+        // does thread 0 add the block to its group's count (an agent-scope atomic, performed where those
+        // loads are served).  A reader that has seen the count and then issues agent-scope loads of v gets
+        // the published values.  (A release fence at agent scope would also write back the whole L2, which
+        // holds the expand blocks' y stores: microseconds per block.)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (threadIdx.x == 0)
             __hip_atomic_fetch_add(&sync[(unsigned int)tile.shape >> 16].done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -730,10 +742,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
         const bf16_t* At = At_ptrs[tile.adapter];        // only the bounded-wait fallback reads it
         const int32_t* rows = expand_rows + (int64_t)(b - n_shrink) * 16;
         if (tile.reserved0 <= 32)
-            fused_expand_item<1>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, spin_limit, delay,
+            fused_expand_item<1>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, wait_ticks, delay,
                                  reinterpret_cast<float*>(lds), &flag);
         else
-            fused_expand_item<2>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, spin_limit, delay,
+            fused_expand_item<2>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, wait_ticks, delay,
                                  reinterpret_cast<float*>(lds), &flag);
     }
 }
@@ -745,9 +757,19 @@ hipError_t launch_delta_fused_small(const lora_plan* p, const lora_dev_tables& d
     const int S = (int)p->shrink_tiles.size(), E = (int)p->expand_tiles.size();
     if (S + E == 0) return hipSuccess;
     lora_sync_slot* sync = reinterpret_cast<lora_sync_slot*>(d.sync);
+    // the bound of the hand-off wait, from microseconds to ticks of the wall clock the kernel reads
+    static int wall_khz[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (wall_khz[dev] == 0) {
+        int khz = 0;
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) khz = 100000;
+        wall_khz[dev] = khz;
+    }
+    const long long wait_ticks = (long long)p->fused_wait_us * wall_khz[dev] / 1000;
     LORA_LAUNCH(LORA_K_DELTA_FUSED, delta_fused_small_kernel, dim3(S + E), dim3(256), 0, stream,
                 d.shrink_tiles, S, d.expand_tiles, d.shrink_rows, d.expand_rows, d.scale, (const bf16_t*)x, ldx,
                 (const bf16_t* const*)At, p->K, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta,
-                sync, p->fused_spin_limit, p->fused_delay, p->n_a);
+                sync, wait_ticks, p->fused_delay, p->n_a);
     return hipGetLastError();
 }

@@ -29,7 +29,7 @@ struct lora_plan {
     int32_t expand_stream_lds = 0; // streaming expand: dynamic LDS bytes of the launch
     bool expand_small = false;     // every expand tile is 16 tokens of rank <= 64: small kernel build
     bool fused_ok = false;         // both small: shrink and expand can run as one launch
-    int32_t fused_spin_limit = 0;  // polls an expand block spends waiting for its group's shrink tiles
+    int32_t fused_wait_us = 0;     // microseconds an expand block waits for its group's shrink tiles before it computes v itself
     int32_t fused_delay = 0;       // units of ~0.4 us an expand block waits before sending its first loads
     int32_t shrink_max_blocks = 1; // largest TB*JB among the shrink tiles (sizes the LDS reduction buffer)
     std::vector<int32_t> token_adapter, perm, group_adapter, group_offset, rank;
@@ -68,6 +68,10 @@ struct lora_plan {
     void* d_sync = nullptr;           // hand-off counters, 128 bytes per adapter group (only when fused_ok)
 };
 
+// How a plan's device tables are released: set by the translation unit that owns them (abi.hip) when the library
+// is loaded; stays null in host-only builds of the planner, where no plan ever has device tables.
+extern void (*lora_plan_device_release)(lora_plan*);
+
 // Process-wide planner tunables (the analogue of the paper's shape -> tile
 // table, section 4.3.2).  Defaults come from measurements on MI355X.
 struct lora_tuning {
@@ -81,7 +85,7 @@ struct lora_tuning {
     int32_t shrink_small_waves;    // wavefronts per shrink workgroup, small build (<= 16)
     int32_t shrink_small_jb;       // rank blocks per shrink tile for groups below shrink_tb2_min_rows (1 or 2)
     int32_t shrink_target_wgs;     // small build: split K over up to 4 workgroups until the launch has this many
-    int32_t fused_spin_limit;      // single-launch decode kernel: polls before an expand block computes v itself (+1; 1 = never wait)
+    int32_t fused_wait_us;      // single-launch decode kernel: microseconds an expand block waits before it computes v itself (+1; 1 = never wait)
     int32_t fused_delay;           // single-launch decode kernel: head start of the shrink blocks' loads, units of ~0.4 us (+1)
     int32_t expand_wave_bytes_big; // like expand_wave_bytes, for adapter groups of at least expand_tb2_min_rows tokens
     int32_t shrink_tb4_min_rows;   // groups with at least this many tokens use 64-token shrink tiles

@@ -23,7 +23,7 @@ lora_tuning g_lora_tuning = {
     /*shrink_small_waves*/ 16,
     /*shrink_small_jb*/ 1,
     /*shrink_target_wgs*/ 768,
-    /*fused_spin_limit*/ 200000,
+    /*fused_wait_us*/ 2001,
     /*fused_delay*/ 3,
     /*expand_wave_bytes_big*/ 131072,
     /*shrink_tb4_min_rows*/ 64,
@@ -259,7 +259,7 @@ static void build_tiles(lora_plan* p)
     // the numbers of shrink tiles
     // (bits 8..19 of its shape) and of expand tiles (bits 20..31) of its adapter group.
     p->fused_ok = p->shrink_small && p->expand_small && G <= 4096;
-    p->fused_spin_limit = tu.fused_spin_limit - 1;
+    p->fused_wait_us = tu.fused_wait_us - 1;
     p->fused_delay = std::max(0, std::min(tu.fused_delay - 1, 64));
     if (p->fused_ok) {
         std::vector<int32_t> need((size_t)G, 0), ncons((size_t)G, 0);
@@ -414,6 +414,15 @@ extern "C" lora_status lora_plan_create(const lora_batch_desc* d, lora_plan** ou
     }
     *out = p;
     return LORA_OK;
+}
+
+void (*lora_plan_device_release)(lora_plan*) = nullptr;
+
+extern "C" void lora_plan_destroy(lora_plan* p)
+{
+    if (!p) return;
+    if (p->d_buf && lora_plan_device_release) lora_plan_device_release(p);
+    delete p;
 }
 
 extern "C" lora_status lora_plan_query(const lora_plan* p, int32_t* v_row_stride, size_t* v_bytes,

@@ -114,38 +114,71 @@ def run_delta_case(w, variant=B.LORA_VARIANT_AUTO, ld_pad=0, check_beta0=True, r
     return view
 
 
+def _forward_rows(w, view, n_sample, seed):
+    """Rows of the oracle comparison for the big configurations: one seeded row out of every 16 consecutive rows of
+    the order the fused GEMM walks (so every 16-row MFMA block of every wavefront of every 256-row tile is hit), the
+    first and last token of every segment (at most n_sample of them) and n_sample seeded rows on top."""
+    rng = np.random.default_rng(seed)
+    order = view["gemm_order"] if view["gemm_order"].shape[0] == w.T else np.arange(w.T)
+    nblk = (w.T + 15) // 16
+    pick = np.minimum(np.arange(nblk) * 16 + rng.integers(0, 16, nblk), w.T - 1)
+    edge = np.unique(np.concatenate([w.seg_indptr[:-1], w.seg_indptr[1:] - 1]))
+    edge = edge[(edge >= 0) & (edge < w.T)]
+    if edge.size > n_sample:
+        edge = rng.choice(edge, n_sample, replace=False)
+    rest = rng.choice(w.T, min(n_sample, w.T), replace=False)
+    return np.unique(np.concatenate([order[pick], edge, rest])).astype(np.int64)
+
+
 def run_forward_case(w, n_sample=None, seed=5, variant=B.LORA_VARIANT_AUTO):
-    """base GEMM alone and the fused forward vs the oracle (on a row sample for
-    the big configurations: first/last token of every segment + random rows)."""
-    print(f"  forward {w.name} T={w.T} K={w.K} N={w.N} sample={n_sample}", flush=True)
+    """base GEMM alone and the fused forward vs the oracle (on a row sample for the big configurations, see
+    _forward_rows), then the fused forward on ALL rows against base GEMM + lora_delta of the same library."""
     dl = device.to_device(w, DEV, with_w=True)
     tdt = device.torch_dtype(w)
     plan = device.make_plan(w, variant)
+    view = B.lora_plan_export(plan)
     R, v_bytes, ws_bytes = B.lora_plan_query(plan)
     tok = oracle.token_adapter(w.T, w.seg_indptr, w.seg_adapter)
     ad = oracle.Adapters(w.adapter_rank, w.adapter_scale, w.A, w.B)
-    if n_sample is None or n_sample >= w.T:
-        rows = np.arange(w.T)
-    else:
-        rng = np.random.default_rng(seed)
-        edge = np.unique(np.concatenate([w.seg_indptr[:-1], w.seg_indptr[1:] - 1]))
-        edge = edge[(edge >= 0) & (edge < w.T)]
-        if edge.size > n_sample // 2:
-            edge = rng.choice(edge, n_sample // 2, replace=False)
-        rest = rng.choice(w.T, n_sample - edge.size, replace=False)
-        rows = np.unique(np.concatenate([edge, rest]))
+    rows = np.arange(w.T) if (n_sample is None or n_sample >= w.T) else _forward_rows(w, view, n_sample, seed)
+    print(f"  forward {w.name} T={w.T} K={w.K} N={w.N} oracle rows={rows.size}", flush=True)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
     y = torch.full((w.T, w.N), 9.0, dtype=tdt, device=DEV)
     B.lora_base_gemm(w.T, w.K, w.N, dl.dtype, dl.x, w.K, dl.Wt, w.K, y, w.N)
     torch.cuda.synchronize()
     base_ref = oracle.base(w.x, w.W, rows=rows)
     _assert_close(_to_np(y)[rows], base_ref, _tol(w), "base gemm")
+    y_base = y.clone()
 
     y.fill_(9.0)
     B.lora_fused_forward(plan, dl.x, w.K, dl.Wt, w.K, dl.At_ptrs, dl.Bt_ptrs, y, w.N, ws, ws.numel())
     torch.cuda.synchronize()
     y_ref = oracle.forward(w.x, w.W, tok, ad, rows=rows)
     _assert_close(_to_np(y)[rows], y_ref, _tol(w), "fused forward")
+
+    # Every row, GPU against GPU: y_fused = rnd(xW + d), y_base = rnd(xW), y_delta = rnd(d) with one rounding each
+    # (bf16: relative 2^-8; fp32: 2^-24) on top of fp32 accumulation noise, so element by element
+    # |y_fused - (y_base + y_delta)| <= u (|y_fused| + |y_base| + |y_delta|) + accumulation slack.
+    # A wrong row, a dropped or doubled adapter stage or a stale operand is an O(1) error.
+    if w.T:
+        v = torch.zeros(max(v_bytes // 4, 4), dtype=torch.float32, device=DEV)
+        y_delta = torch.zeros((w.T, w.N), dtype=tdt, device=DEV)
+        B.lora_delta(plan, dl.x, w.K, dl.At_ptrs, dl.Bt_ptrs, v, y_delta, w.N, 0.0)
+        torch.cuda.synchronize()
+        u = 2.0 ** -8 if w.dtype == "bf16" else 2.0 ** -24
+        slack = 1e-4 if w.dtype == "bf16" else 1e-5
+        yf, yb, yd = y.float(), y_base.float(), y_delta.float()
+        excess = (yf - (yb + yd)).abs() - (1.01 * u * (yf.abs() + yb.abs() + yd.abs()) + slack)
+        worst = float(excess.max())
+        ranks_tok = np.where(tok >= 0, w.adapter_rank[np.clip(tok, 0, None)], 0) if w.num_adapters else np.zeros(w.T, int)
+        none = torch.from_numpy(ranks_tok == 0).to(DEV)
+        same = float((y[none] == y_base[none]).float().mean()) if bool(none.any()) else 1.0
+        nrm = float(torch.linalg.norm(yf - (yb + yd)) / torch.linalg.norm(yb + yd).clamp_min(1e-30))
+        print(f"    fused vs base gemm + lora_delta, all {w.T} rows: normwise {nrm:.3e}, worst excess over the "
+              f"rounding bound {worst:.3e}; rows without adapter bit-identical to the base GEMM: {same:.4f}", flush=True)
+        assert worst <= 0.0, "fused forward differs from base GEMM + delta by more than the three roundings allow"
+        if bool(none.any()):      # no delta: the same product, at most the last bit apart (summation order)
+            assert bool(((y[none].float() - y_base[none].float()).abs() <= 2 * u * y_base[none].float().abs() + slack).all())
     plan.destroy()
 
 
@@ -168,8 +201,7 @@ def test_cfg2_decode():
 def test_cfg3_prefill(projection):
     w = wl.cfg3(projection)
     run_delta_case(w, check_beta0=(projection == 0))
-    if projection == 0:
-        run_forward_case(w, n_sample=256)
+    run_forward_case(w, n_sample=128)
 
 
 def test_cfg4_mixed():
@@ -179,8 +211,9 @@ def test_cfg4_mixed():
 
 
 def test_cfg4d_mixed_with_decode_requests():
-    w = wl.cfg4d(with_w=False)
+    w = wl.cfg4d()
     run_delta_case(w, rows=np.arange(0, w.T, 4), check_beta0=False)
+    run_forward_case(w, n_sample=192)
 
 
 @pytest.mark.parametrize("shape", ["attn", "mlp"])
@@ -348,7 +381,7 @@ def _delta_case(w, fallback=False):
     before = B.lora_tuning_get()
     try:
         if fallback:
-            B.lora_tuning_set(fused_spin_limit=1)      # never wait: every expand block recomputes its v rows
+            B.lora_tuning_set(fused_wait_us=1)      # never wait: every expand block recomputes its v rows
         dl = device.to_device(w, DEV, with_w=False)
         plan = device.make_plan(w)
     finally:

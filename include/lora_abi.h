@@ -233,6 +233,26 @@ lora_status lora_delta(lora_plan* plan, const void* x, int64_t ldx,
                        float* v, void* y, int64_t ldy, float beta, void* hip_stream);
 
 /*
+ * lora_delta_static -- lora_delta for callers that cannot allocate device memory or call anything that does: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and same result
+ * as lora_delta, without the v argument: v and the single launch's hand-off counters live in a device array that
+ * is part of the library's image (LORA_STATIC_V_BYTES + LORA_STATIC_MAX_GROUPS * 128 bytes, held by every GPU the
+ * library runs on until the process ends).  The call allocates nothing and frees nothing.
+ *   - The plan must already be on the current device (lora_plan_upload, which does allocate, at set-up);
+ *     otherwise LORA_ERR_INVALID_ARG.
+ *   - lora_plan_query's v_bytes above LORA_STATIC_V_BYTES, or more than LORA_STATIC_MAX_GROUPS distinct adapters
+ *     in use: LORA_ERR_UNSUPPORTED (use lora_delta with a caller-owned v).
+ *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents (the counters are
+ *     cleared by a small kernel at the start of every call that uses them): calls that overlap on one GPU
+ *     -- two streams, two threads -- race.  Calls on one stream, and calls on different GPUs, do not.
+ */
+#define LORA_STATIC_V_BYTES   (16u << 20)
+#define LORA_STATIC_MAX_GROUPS 4096
+lora_status lora_delta_static(lora_plan* plan, const void* x, int64_t ldx,
+                              const void* const* d_At_ptrs, const void* const* d_Bt_ptrs,
+                              void* y, int64_t ldy, float beta, void* hip_stream);
+
+/*
  * lora_base_gemm -- the base-model product shared by all requests of the batch
  * (section 1 / section 2, unmerged inference):  y = x W, Wt [N,K] with ldw.
  * bf16 MFMA with fp32 accumulation (fp32 dtype: VALU).  Used for the

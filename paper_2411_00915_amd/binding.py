@@ -28,6 +28,8 @@ LORA_OK, LORA_ERR_INVALID_ARG, LORA_ERR_UNSUPPORTED, LORA_ERR_NOMEM, LORA_ERR_WO
 LORA_F32, LORA_BF16 = 0, 1
 LORA_VARIANT_AUTO, LORA_VARIANT_GENERAL, LORA_VARIANT_TILED = 0, 1, 2
 LORA_MAX_RANK = 256
+LORA_STATIC_V_BYTES = 16 << 20
+LORA_STATIC_MAX_GROUPS = 4096
 
 _i32p = ctypes.POINTER(ctypes.c_int32)
 _f32p = ctypes.POINTER(ctypes.c_float)
@@ -76,6 +78,8 @@ _lib.lora_expand.restype = ctypes.c_int
 _lib.lora_expand.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_float, _vp]
 _lib.lora_delta.restype = ctypes.c_int
 _lib.lora_delta.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_float, _vp]
+_lib.lora_delta_static.restype = ctypes.c_int
+_lib.lora_delta_static.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_float, _vp]
 _lib.lora_base_gemm.restype = ctypes.c_int
 _lib.lora_base_gemm.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                 _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp]
@@ -103,7 +107,7 @@ _lib.lora_kernel_count.restype = ctypes.c_int32
 
 EXPORTED = ["lora_timing_begin", "lora_timing_end", "lora_timing_read", "lora_kernel_name", "lora_kernel_count",
             "lora_plan_create", "lora_plan_destroy", "lora_plan_query", "lora_plan_export",
-            "lora_plan_upload", "lora_shrink", "lora_expand", "lora_delta", "lora_base_gemm",
+            "lora_plan_upload", "lora_shrink", "lora_expand", "lora_delta", "lora_delta_static", "lora_base_gemm",
             "lora_fused_forward", "lora_merge", "lora_status_str", "lora_tuning_set", "lora_tuning_get"]
 
 TUNING_FIELDS = ["shrink_waves", "shrink_tb2_min_rows", "shrink_max_jb", "expand_wave_bytes",
@@ -281,6 +285,11 @@ def lora_expand(plan: Plan, v, d_Bt_ptrs, y, ldy: int, beta: float = 1.0, stream
 def lora_delta(plan: Plan, x, ldx: int, d_At_ptrs, d_Bt_ptrs, v, y, ldy: int, beta: float = 1.0, stream=None):
     _check(_lib.lora_delta(plan.handle, _ptr(x), int(ldx), _ptr(d_At_ptrs), _ptr(d_Bt_ptrs), _ptr(v), _ptr(y), int(ldy),
                            float(beta), _stream(stream)), "lora_delta")
+
+
+def lora_delta_static(plan: Plan, x, ldx: int, d_At_ptrs, d_Bt_ptrs, y, ldy: int, beta: float = 1.0, stream=None):
+    _check(_lib.lora_delta_static(plan.handle, _ptr(x), int(ldx), _ptr(d_At_ptrs), _ptr(d_Bt_ptrs), _ptr(y), int(ldy),
+                                  float(beta), _stream(stream)), "lora_delta_static")
 
 
 def lora_base_gemm(num_tokens: int, k: int, n: int, dtype: int, x, ldx: int, Wt, ldw: int, y, ldy: int, stream=None):

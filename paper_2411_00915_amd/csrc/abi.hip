@@ -9,7 +9,41 @@
 #include <cmath>
 
 #include "kernels.h"
+#include "launch.h"
 #include "plan_internal.h"
+
+// ---------------------------------------------------------------------------
+// Device array of lora_delta_static (see there): v and the hand-off counters for callers that cannot allocate.
+// Every device the library runs on holds its own copy of the array, at its own address, until the process ends.
+namespace {
+constexpr size_t kStaticSyncBytes = (size_t)LORA_STATIC_MAX_GROUPS * 128;            // one 128-byte slot per adapter group
+constexpr size_t kStaticBytes = kStaticSyncBytes + (size_t)LORA_STATIC_V_BYTES;
+}
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+unsigned char* g_static_ptr[kMaxDevices] = {nullptr};       // device address of `scratch` on each device (the array's
+                                                            // name is only a host-side handle for hipGetSymbolAddress)
+
+// address of the current device's copy of `scratch`; looked up once per device, with that device current
+lora_status static_scratch(unsigned char** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LORA_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return LORA_ERR_DEVICE;
+        }
+        g_static_ptr[dev] = static_cast<unsigned char*>(ptr);
+    }
+    *out = g_static_ptr[dev];
+    return LORA_OK;
+}
+}  // namespace
 
 namespace {
 
@@ -64,6 +98,11 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return LORA_ERR_DEVICE;
     if (p->d_buf) return p->device == dev ? LORA_OK : LORA_ERR_INVALID_ARG;   // a plan lives on one device
+
+    // set-up is also where the address of lora_delta_static's device array is looked up (the first use of a
+    // device array makes the runtime place it; the static call itself then finds it resolved)
+    unsigned char* static_base = nullptr;
+    (void)static_scratch(&static_base);
 
     const table_layout L = layout_of(p);
     // size classes (powers of two from 4 KiB) so that released buffers fit later plans
@@ -333,3 +372,67 @@ extern "C" lora_status lora_fused_forward(lora_plan* p, const void* x, int64_t l
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
 }
 
+// ---------------------------------------------------------------------------
+// lora_delta_static: lora_delta for callers that cannot allocate.  What lora_delta keeps in caller- or
+// library-allocated device memory beyond its inputs and outputs -- v (the shrink's partial sums) and the hand-off
+// counters of the single-launch kernel -- lives in one file-scope device array instead.  Every device the library
+// runs on holds its own copy of the array, at its own address, until the process ends.
+namespace {
+// zero-fill by a kernel (a memset node recorded into a captured graph is not reliable on replay)
+__global__ __launch_bounds__(256) void clear_words_kernel(uint4* dst, int n16)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) dst[i] = uint4{0, 0, 0, 0};
+}
+}  // namespace
+
+extern "C" lora_status lora_delta_static(lora_plan* p, const void* x, int64_t ldx,
+                                         const void* const* d_At_ptrs, const void* const* d_Bt_ptrs,
+                                         void* y, int64_t ldy, float beta, void* hip_stream)
+{
+    if (!p) return LORA_ERR_INVALID_ARG;
+    if (!(beta == 0.f || beta == 1.f)) return LORA_ERR_INVALID_ARG;
+    if (p->perm.empty()) return LORA_OK;
+    if (!x || !d_At_ptrs || !d_Bt_ptrs || !y) return LORA_ERR_INVALID_ARG;
+    if (ldx < p->K || ldy < p->N) return LORA_ERR_INVALID_ARG;
+    size_t v_bytes = 0;
+    lora_plan_query(p, nullptr, &v_bytes, nullptr);
+    if (v_bytes > (size_t)LORA_STATIC_V_BYTES || p->group_adapter.size() > (size_t)LORA_STATIC_MAX_GROUPS)
+        return LORA_ERR_UNSUPPORTED;                           // beyond the static array: use lora_delta
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return LORA_ERR_DEVICE;
+    if (!p->d_buf || p->device != dev) return LORA_ERR_INVALID_ARG;   // uploading would allocate: do it at set-up
+    unsigned char* base = nullptr;
+    lora_status st = static_scratch(&base);
+    if (st != LORA_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    float* v = reinterpret_cast<float*>(base + kStaticSyncBytes);
+    lora_dev_tables d = tables_of(p);
+    d.sync = base;
+    const bool single = p->family == LORA_VARIANT_TILED && p->fused_ok && tiled_call_ok(x, ldx) && tiled_call_ok(y, ldy) &&
+                        !misaligned(d_At_ptrs, 8) && !misaligned(d_Bt_ptrs, 8);
+    hipError_t e;
+    if (single) {
+        // the counters' launch arithmetic assumes one plan per slot: the array is shared by all plans, so they
+        // start every call at zero
+        const int n16 = (int)(p->group_adapter.size() * 128 / 16);
+        LORA_LAUNCH(LORA_K_CLEAR, clear_words_kernel, dim3((n16 + 255) / 256), dim3(256), 0, stream,
+                    reinterpret_cast<uint4*>(base), n16);
+        if (hipGetLastError() != hipSuccess) return LORA_ERR_DEVICE;
+        e = launch_delta_fused_small(p, d, x, ldx, d_At_ptrs, d_Bt_ptrs, v, y, ldy, beta, stream);
+        return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
+    }
+    if (misaligned(x, elem_bytes(p->dtype)) || misaligned(y, elem_bytes(p->dtype)) || misaligned(d_At_ptrs, 8) ||
+        misaligned(d_Bt_ptrs, 8))
+        return LORA_ERR_INVALID_ARG;
+    if (p->family == LORA_VARIANT_TILED && tiled_call_ok(x, ldx) && tiled_call_ok(y, ldy)) {
+        e = launch_shrink_tiled(p, d, x, ldx, d_At_ptrs, v, stream);
+        if (e == hipSuccess) e = launch_expand_tiled(p, d, v, d_Bt_ptrs, y, ldy, beta, stream);
+    } else if (p->family == LORA_VARIANT_TILED && p->variant_req == LORA_VARIANT_TILED) {
+        return LORA_ERR_UNSUPPORTED;
+    } else {
+        e = launch_shrink_general(p, d, x, ldx, d_At_ptrs, v, stream);
+        if (e == hipSuccess) e = launch_expand_general(p, d, v, d_Bt_ptrs, y, ldy, beta, stream);
+    }
+    return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
+}

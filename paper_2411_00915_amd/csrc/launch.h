@@ -23,6 +23,7 @@ enum lora_kernel_id {
     LORA_K_MERGE,
     LORA_K_GEMM_RING,
     LORA_K_GEMM_RING_DELTA,
+    LORA_K_CLEAR,
     LORA_K_COUNT
 };
 

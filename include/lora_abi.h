@@ -39,8 +39,9 @@
  * THREADS.  Distinct plans may be created, used and destroyed from distinct
  * host threads at the same time (the pool of recycled device tables and the
  * timing records are locked).  One plan is used by one thread, on one stream,
- * at a time.  The tunables (lora_tuning_set) and the timing switch are
- * process-wide: set them while no other thread plans or launches.
+ * at a time.  The default tunables and the shape table are process-wide and locked; every plan
+ * keeps the snapshot it was made with.  The timing switch is process-wide: use it while no other
+ * thread launches.
  *
  * ERRORS.  Every function returns a lora_status; nothing throws.  All
  * descriptor validation happens in lora_plan_create, which is pure host code
@@ -62,6 +63,7 @@ extern "C" {
 #endif
 
 #define LORA_MAX_RANK 256
+#define LORA_TUNING_COUNT 17     /* number of planner tunables, see lora_tuning_set */
 
 typedef enum {
     LORA_OK = 0,
@@ -102,6 +104,11 @@ typedef struct {
     int32_t        n;              /* out features N >= 1 */
     int32_t        dtype;          /* lora_dtype of x, At, Bt, Wt, y (v is always fp32) */
     int32_t        variant;        /* lora_variant */
+    const int32_t* tuning;         /* optional: planner tunables for THIS plan, [tuning_count] in the order of
+                                      lora_tuning_set (entries <= 0 and entries beyond tuning_count: not given).
+                                      What is given here overrides the shape table's entry, which overrides the
+                                      process defaults.  NULL / 0: nothing given */
+    int32_t        tuning_count;
 } lora_batch_desc;
 
 /* One unit of kernel work: the rows [row0,row0+nrows) of `perm` (all of one
@@ -129,6 +136,9 @@ typedef struct {
     int32_t        kernel_family;   /* lora_variant actually chosen (GENERAL or TILED) */
     int32_t        shrink_waves;    /* wavefronts per workgroup of the shrink launch */
     int32_t        v_parts;         /* P: number of partial sums v holds (see lora_shrink) */
+    int32_t        tuning_source;   /* where this plan's tunables came from: 0 process defaults only, 1 an entry of
+                                       the shape table, + 2 if the descriptor gave values of its own */
+    int32_t        tuning[LORA_TUNING_COUNT];   /* the tunables this plan was made with (order of lora_tuning_set) */
     int32_t        reserved;
     const int32_t* token_adapter;   /* [T]  adapter of each token, -1 = none */
     const int32_t* perm;            /* [num_active] tokens with an adapter, stably sorted by adapter */
@@ -300,10 +310,10 @@ lora_status lora_merge(int32_t num_layers, int32_t n, int32_t k, int32_t rank, f
 const char* lora_status_str(lora_status s);
 
 /*
- * Planner tunables: the process-wide table that steers tile-shape choice, the
- * counterpart of the shape -> tile-configuration table the paper fills by
- * profiling (section 4.3.2, Algorithm 2).  `values` is an int32 array in the
- * order: shrink_waves (wavefronts per shrink workgroup, 1..8),
+ * Planner tunables: what steers the planner's choice of tile shapes, kernel family and K split.  Every plan is
+ * made with a snapshot of them: the process defaults (this call), overridden by the shape table's entry for the
+ * batch (lora_tuning_table_set, below), overridden by the values the batch descriptor gives.  `values` is an int32
+ * array of up to LORA_TUNING_COUNT entries in the order: shrink_waves (wavefronts per shrink workgroup, 1..8),
  * shrink_tb2_min_rows (adapter groups with at least this many tokens use
  * 32-token shrink tiles), shrink_max_jb (rank blocks of 16 per shrink tile,
  * 1..4), expand_wave_bytes (bytes of Bt and y one expand wavefront streams),
@@ -330,10 +340,33 @@ const char* lora_status_str(lora_status s);
  * would give fewer workgroups than this), expand_stream_stages (stages of 64
  * features per wavefront that one workgroup of the streaming expand walks).
  * Entries <= 0 keep the current value; plans made
- * earlier are unaffected.  Host only.
+ * earlier are unaffected.  Host only, thread-safe.
  */
 void lora_tuning_set(const int32_t* values, int32_t count);
 void lora_tuning_get(int32_t* values, int32_t count);
+
+/*
+ * The shape table: the counterpart of the table ATMM consults per input shape (section 4.3.1) and fills offline
+ * by profiling every candidate configuration per shape (section 4.3.2, Algorithm 2: loops over token counts in
+ * steps of 32, over the ranks, and over the tile configurations).  An entry holds the tunables that measured best
+ * on MI355X for one shape class; lora_plan_create looks the batch's class up and plans with that entry (on top of
+ * the process defaults, below the descriptor's own values).  The key of a batch:
+ *   tokens       tokens that have an adapter; the entry with the smallest `tokens` >= that count applies (entries
+ *                are made for multiples of 32), else the one with the largest
+ *   k, n         in / out features (exact match)
+ *   max_rank     largest rank in use, rounded up to 8, 16, 32, 64, 128 or 256 (exact match)
+ *   group_class  0: every adapter group has fewer than 64 tokens (decode-shaped), 1: otherwise (exact match)
+ * The library ships with the table its offline search (paper_2411_00915_amd/autotune.py) wrote on MI355X;
+ * lora_tuning_table_set replaces it for the process (entries are copied; NULL / 0 restores the shipped table),
+ * lora_tuning_table_get copies up to `capacity` entries out and returns the table's size.  Plans made earlier keep
+ * what they were made with.  Thread-safe.
+ */
+typedef struct {
+    int32_t tokens, k, n, max_rank, group_class;
+    int32_t values[LORA_TUNING_COUNT];      /* order of lora_tuning_set; <= 0: keep the default */
+} lora_tuning_entry;
+lora_status lora_tuning_table_set(const lora_tuning_entry* entries, int32_t count);
+int32_t     lora_tuning_table_get(lora_tuning_entry* entries, int32_t capacity);
 
 /*
  * Per-kernel timing for benchmarks (the paper times its operator over repeated
@@ -351,6 +384,23 @@ lora_status lora_timing_read(int32_t kernel_id, int64_t* count, double* total_us
                              double* min_us, double* max_us);
 const char* lora_kernel_name(int32_t kernel_id);
 int32_t     lora_kernel_count(void);
+
+/*
+ * lora_probe -- measured ceilings of the machine, for benchmark reports (the per-kernel timers above time them
+ * like any kernel of the library).  buffer: device memory, 16-byte aligned, `bytes` long.
+ *   LORA_PROBE_EMPTY  a launch of 1280 workgroups that does nothing: the floor of any kernel duration
+ *   LORA_PROBE_READ   one-shot read of the first floor(bytes / 32 KiB) * 32 KiB of the buffer, no dependency
+ *                     between loads (every lane asks for its eight 16-byte pieces at once, whole cache lines per
+ *                     wavefront, non-temporal): what a launch of that size can get out of HBM at best
+ *   LORA_PROBE_MFMA   `iters` x 16 independent v_mfma_f32_16x16x32_bf16 per wavefront on register operands, 2048
+ *                     workgroups of 4 wavefronts (2048 * 4 * iters * 16 * 16384 flops); writes the shader-clock
+ *                     ticks and the wall-clock ticks the loop took on one wavefront to buffer[0], buffer[1] and
+ *                     the wall clock's rate in kHz to buffer[2], as uint64: the clock the chip holds under
+ *                     matrix load is buffer[0] / buffer[1] * buffer[2] kHz
+ * Errors: LORA_ERR_INVALID_ARG for a null or misaligned buffer, bytes < 64, an unknown kind, iters < 1.
+ */
+enum { LORA_PROBE_EMPTY = 0, LORA_PROBE_READ = 1, LORA_PROBE_MFMA = 2 };
+lora_status lora_probe(int32_t kind, void* buffer, size_t bytes, int32_t iters, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -28,6 +28,7 @@ LORA_OK, LORA_ERR_INVALID_ARG, LORA_ERR_UNSUPPORTED, LORA_ERR_NOMEM, LORA_ERR_WO
 LORA_F32, LORA_BF16 = 0, 1
 LORA_VARIANT_AUTO, LORA_VARIANT_GENERAL, LORA_VARIANT_TILED = 0, 1, 2
 LORA_MAX_RANK = 256
+LORA_TUNING_COUNT = 17
 LORA_STATIC_V_BYTES = 16 << 20
 LORA_STATIC_MAX_GROUPS = 4096
 
@@ -40,7 +41,7 @@ class BatchDesc(ctypes.Structure):
                 ("seg_indptr", _i32p), ("seg_adapter", _i32p),
                 ("num_adapters", ctypes.c_int32), ("adapter_rank", _i32p), ("adapter_scale", _f32p),
                 ("k", ctypes.c_int32), ("n", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("variant", ctypes.c_int32)]
+                ("variant", ctypes.c_int32), ("tuning", _i32p), ("tuning_count", ctypes.c_int32)]
 
 
 class Tile(ctypes.Structure):
@@ -53,7 +54,8 @@ class PlanView(ctypes.Structure):
     _fields_ = [("num_tokens", ctypes.c_int32), ("num_active", ctypes.c_int32),
                 ("num_groups", ctypes.c_int32), ("v_row_stride", ctypes.c_int32),
                 ("kernel_family", ctypes.c_int32), ("shrink_waves", ctypes.c_int32),
-                ("v_parts", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("v_parts", ctypes.c_int32), ("tuning_source", ctypes.c_int32),
+                ("tuning", ctypes.c_int32 * LORA_TUNING_COUNT), ("reserved", ctypes.c_int32),
                 ("token_adapter", _i32p), ("perm", _i32p), ("group_adapter", _i32p), ("group_offset", _i32p),
                 ("shrink_tiles", ctypes.POINTER(Tile)), ("num_shrink_tiles", ctypes.c_int32),
                 ("expand_tiles", ctypes.POINTER(Tile)), ("num_expand_tiles", ctypes.c_int32),
@@ -96,6 +98,19 @@ _lib.lora_tuning_set.argtypes = [_i32p, ctypes.c_int32]
 _lib.lora_tuning_get.restype = None
 _lib.lora_tuning_get.argtypes = [_i32p, ctypes.c_int32]
 
+
+
+class TuningEntry(ctypes.Structure):
+    _fields_ = [("tokens", ctypes.c_int32), ("k", ctypes.c_int32), ("n", ctypes.c_int32), ("max_rank", ctypes.c_int32),
+                ("group_class", ctypes.c_int32), ("values", ctypes.c_int32 * LORA_TUNING_COUNT)]
+
+
+_lib.lora_tuning_table_set.restype = ctypes.c_int
+_lib.lora_tuning_table_set.argtypes = [ctypes.POINTER(TuningEntry), ctypes.c_int32]
+_lib.lora_tuning_table_get.restype = ctypes.c_int32
+_lib.lora_tuning_table_get.argtypes = [ctypes.POINTER(TuningEntry), ctypes.c_int32]
+_lib.lora_probe.restype = ctypes.c_int
+_lib.lora_probe.argtypes = [ctypes.c_int32, _vp, ctypes.c_size_t, ctypes.c_int32, _vp]
 _lib.lora_timing_begin.restype = ctypes.c_int
 _lib.lora_timing_end.restype = ctypes.c_int
 _lib.lora_timing_read.restype = ctypes.c_int
@@ -108,7 +123,8 @@ _lib.lora_kernel_count.restype = ctypes.c_int32
 EXPORTED = ["lora_timing_begin", "lora_timing_end", "lora_timing_read", "lora_kernel_name", "lora_kernel_count",
             "lora_plan_create", "lora_plan_destroy", "lora_plan_query", "lora_plan_export",
             "lora_plan_upload", "lora_shrink", "lora_expand", "lora_delta", "lora_delta_static", "lora_base_gemm",
-            "lora_fused_forward", "lora_merge", "lora_status_str", "lora_tuning_set", "lora_tuning_get"]
+            "lora_fused_forward", "lora_merge", "lora_status_str", "lora_tuning_set", "lora_tuning_get",
+            "lora_tuning_table_set", "lora_tuning_table_get", "lora_probe"]
 
 TUNING_FIELDS = ["shrink_waves", "shrink_tb2_min_rows", "shrink_max_jb", "expand_wave_bytes",
                  "expand_tb2_min_rows", "expand_tb4_min_rows", "tiled_min_tokens",
@@ -156,13 +172,46 @@ def lora_tuning_get() -> dict:
 
 
 def lora_tuning_set(**kw) -> None:
-    """Set planner tunables (values <= 0 or missing keep the current value)."""
-    vals = [int(kw.get(f, 0)) for f in TUNING_FIELDS]
-    unknown = set(kw) - set(TUNING_FIELDS)
-    if unknown:
-        raise KeyError(f"unknown tuning fields: {sorted(unknown)}")
+    """Set the process's default tunables (values <= 0 or missing keep the current value)."""
+    vals = _tuning_values(kw)
     buf = (ctypes.c_int32 * len(vals))(*vals)
     _lib.lora_tuning_set(buf, len(vals))
+
+
+def _tuning_values(tunables: dict):
+    unknown = set(tunables) - set(TUNING_FIELDS)
+    if unknown:
+        raise KeyError(f"unknown tuning fields: {sorted(unknown)}")
+    return [int(tunables.get(f, 0)) for f in TUNING_FIELDS]
+
+
+def lora_tuning_table_set(entries) -> None:
+    """Replace the process's shape table.  entries: iterable of dicts with the key fields tokens, k, n, max_rank,
+    group_class and `tunables` (name -> value); None or empty restores the table the library ships with."""
+    entries = list(entries or [])
+    arr = (TuningEntry * max(len(entries), 1))()
+    for i, e in enumerate(entries):
+        arr[i].tokens, arr[i].k, arr[i].n = int(e["tokens"]), int(e["k"]), int(e["n"])
+        arr[i].max_rank, arr[i].group_class = int(e["max_rank"]), int(e["group_class"])
+        for j, val in enumerate(_tuning_values(e["tunables"])):
+            arr[i].values[j] = val
+    _check(_lib.lora_tuning_table_set(arr if entries else None, len(entries)), "lora_tuning_table_set")
+
+
+def lora_tuning_table_get() -> list:
+    n = _lib.lora_tuning_table_get(None, 0)
+    arr = (TuningEntry * max(n, 1))()
+    n = min(n, _lib.lora_tuning_table_get(arr, n))
+    return [dict(tokens=arr[i].tokens, k=arr[i].k, n=arr[i].n, max_rank=arr[i].max_rank, group_class=arr[i].group_class,
+                 tunables={f: int(arr[i].values[j]) for j, f in enumerate(TUNING_FIELDS) if arr[i].values[j] > 0})
+            for i in range(n)]
+
+
+LORA_PROBE_EMPTY, LORA_PROBE_READ, LORA_PROBE_MFMA = 0, 1, 2
+
+
+def lora_probe(kind: int, buffer, nbytes: int, iters: int = 1, stream=None):
+    _check(_lib.lora_probe(int(kind), _ptr(buffer), int(nbytes), int(iters), _stream(stream)), "lora_probe")
 
 
 def lora_timing_begin():
@@ -207,8 +256,9 @@ class Plan:
 
 
 def lora_plan(num_tokens, seg_indptr, seg_adapter, adapter_rank, adapter_scale, k, n, dtype,
-              variant=LORA_VARIANT_AUTO) -> Plan:
-    """lora_plan_create; tables are host arrays (numpy or sequences)."""
+              variant=LORA_VARIANT_AUTO, tuning: Optional[dict] = None) -> Plan:
+    """lora_plan_create; tables are host arrays (numpy or sequences).  tuning: tunables for this plan only
+    (name -> value), on top of the shape table's entry and the process defaults."""
     indptr = np.ascontiguousarray(seg_indptr, dtype=np.int32)
     seg_ad = np.ascontiguousarray(seg_adapter, dtype=np.int32)
     rank = np.ascontiguousarray(adapter_rank, dtype=np.int32)
@@ -216,7 +266,11 @@ def lora_plan(num_tokens, seg_indptr, seg_adapter, adapter_rank, adapter_scale, 
     desc = BatchDesc(int(num_tokens), int(seg_ad.shape[0]),
                      indptr.ctypes.data_as(_i32p), seg_ad.ctypes.data_as(_i32p),
                      int(rank.shape[0]), rank.ctypes.data_as(_i32p), scale.ctypes.data_as(_f32p),
-                     int(k), int(n), int(dtype), int(variant))
+                     int(k), int(n), int(dtype), int(variant), None, 0)
+    if tuning:
+        vals = (ctypes.c_int32 * LORA_TUNING_COUNT)(*_tuning_values(tuning))
+        desc.tuning = ctypes.cast(vals, _i32p)
+        desc.tuning_count = LORA_TUNING_COUNT
     out = _vp()
     _check(_lib.lora_plan_create(ctypes.byref(desc), ctypes.byref(out)), "lora_plan_create")
     return Plan(out.value, None)
@@ -257,7 +311,8 @@ def lora_plan_export(plan: Plan) -> dict:
 
     return dict(num_tokens=v.num_tokens, num_active=v.num_active, num_groups=v.num_groups,
                 v_row_stride=v.v_row_stride, kernel_family=v.kernel_family, shrink_waves=v.shrink_waves,
-                v_parts=v.v_parts,
+                v_parts=v.v_parts, tuning_source=v.tuning_source,
+                tuning={f: int(v.tuning[j]) for j, f in enumerate(TUNING_FIELDS)},
                 token_adapter=arr(v.token_adapter, v.num_tokens), perm=arr(v.perm, v.num_active),
                 group_adapter=arr(v.group_adapter, v.num_groups),
                 group_offset=arr(v.group_offset, v.num_groups + 1),

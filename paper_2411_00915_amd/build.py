@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "liblora_amd.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["planner.cpp", "kernels_general.hip", "kernels_tiled.hip", "kernels_stream.hip", "kernels_gemm.hip", "abi.hip", "timing.hip"]
+SOURCES = ["planner.cpp", "kernels_general.hip", "kernels_tiled.hip", "kernels_stream.hip", "kernels_gemm.hip", "abi.hip", "timing.hip", "probe.hip"]
 
 HIP_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -24,6 +24,9 @@ enum lora_kernel_id {
     LORA_K_GEMM_RING,
     LORA_K_GEMM_RING_DELTA,
     LORA_K_CLEAR,
+    LORA_K_PROBE_EMPTY,
+    LORA_K_PROBE_READ,
+    LORA_K_PROBE_MFMA,
     LORA_K_COUNT
 };
 

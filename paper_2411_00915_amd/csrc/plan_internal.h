@@ -16,8 +16,33 @@ static inline int lora_shape_jb(int32_t code) { return (code >> 4) & 15; }
 static inline int lora_shape_part(int32_t code) { return (code >> 8) & 15; }
 static inline int lora_shape_parts(int32_t code) { return (code >> 12) & 15; }
 
+// Planner tunables (defaults come from measurements on MI355X).  A plan is made with a snapshot: the process
+// defaults, overridden by the shape table's entry for the batch, overridden by the descriptor's own values.
+struct lora_tuning {
+    int32_t shrink_waves;          // wavefronts per shrink workgroup (big build, <= 8)
+    int32_t shrink_tb2_min_rows;   // groups with at least this many tokens use 32-row wave tiles
+    int32_t shrink_max_jb;         // rank blocks of 16 per shrink tile (1, 2 or 4)
+    int32_t expand_wave_bytes;     // target bytes of Bt + y one expand wavefront streams
+    int32_t expand_tb2_min_rows;   // token-count thresholds for 32 / 64 row expand tiles
+    int32_t expand_tb4_min_rows;
+    int32_t tiled_min_tokens;      // AUTO: batches with fewer active tokens use the general kernels
+    int32_t shrink_small_waves;    // wavefronts per shrink workgroup, small build (<= 16)
+    int32_t shrink_small_jb;       // rank blocks per shrink tile for groups below shrink_tb2_min_rows (1 or 2)
+    int32_t shrink_target_wgs;     // small build: split K over up to 4 workgroups until the launch has this many
+    int32_t fused_wait_us;         // single-launch decode kernel: microseconds an expand block waits before it computes v itself (+1; 1 = never wait)
+    int32_t fused_delay;           // single-launch decode kernel: head start of the shrink blocks' loads, units of ~0.4 us (+1)
+    int32_t expand_wave_bytes_big; // like expand_wave_bytes, for adapter groups of at least expand_tb2_min_rows tokens
+    int32_t shrink_tb4_min_rows;   // groups with at least this many tokens use 64-token shrink tiles
+    int32_t shrink_stream_min_tokens;  // batches with at least this many adapter tokens use the streaming shrink
+    int32_t shrink_stream_wgs;     // streaming shrink: 64-token tiles when 128-token tiles give fewer workgroups than this
+    int32_t expand_stream_stages;  // streaming expand: stages (of 64 features per wavefront) one workgroup walks
+};
+static_assert(sizeof(lora_tuning) == LORA_TUNING_COUNT * sizeof(int32_t), "lora_tuning and LORA_TUNING_COUNT disagree");
+
 struct lora_plan {
     int32_t T = 0, S = 0, n_a = 0, K = 0, N = 0, dtype = 0, variant_req = 0;
+    lora_tuning tuning{};          // the tunables this plan is made with
+    int32_t tuning_source = 0;     // 0 defaults, 1 shape table entry, +2 values given by the descriptor
     int32_t R = 8;                 // v row stride (floats)
     int32_t v_parts = 1;           // v holds this many partial sums [P][T][R]; consumers add them in order
     int32_t family = LORA_VARIANT_GENERAL;
@@ -72,25 +97,3 @@ struct lora_plan {
 // is loaded; stays null in host-only builds of the planner, where no plan ever has device tables.
 extern void (*lora_plan_device_release)(lora_plan*);
 
-// Process-wide planner tunables (the analogue of the paper's shape -> tile
-// table, section 4.3.2).  Defaults come from measurements on MI355X.
-struct lora_tuning {
-    int32_t shrink_waves;          // wavefronts per shrink workgroup (big build, <= 8)
-    int32_t shrink_tb2_min_rows;   // groups with at least this many tokens use 32-row wave tiles
-    int32_t shrink_max_jb;         // rank blocks of 16 per shrink tile (1, 2 or 4)
-    int32_t expand_wave_bytes;     // target bytes of Bt + y one expand wavefront streams
-    int32_t expand_tb2_min_rows;   // token-count thresholds for 32 / 64 row expand tiles
-    int32_t expand_tb4_min_rows;
-    int32_t tiled_min_tokens;      // AUTO: batches with fewer active tokens use the general kernels
-    int32_t shrink_small_waves;    // wavefronts per shrink workgroup, small build (<= 16)
-    int32_t shrink_small_jb;       // rank blocks per shrink tile for groups below shrink_tb2_min_rows (1 or 2)
-    int32_t shrink_target_wgs;     // small build: split K over up to 4 workgroups until the launch has this many
-    int32_t fused_wait_us;      // single-launch decode kernel: microseconds an expand block waits before it computes v itself (+1; 1 = never wait)
-    int32_t fused_delay;           // single-launch decode kernel: head start of the shrink blocks' loads, units of ~0.4 us (+1)
-    int32_t expand_wave_bytes_big; // like expand_wave_bytes, for adapter groups of at least expand_tb2_min_rows tokens
-    int32_t shrink_tb4_min_rows;   // groups with at least this many tokens use 64-token shrink tiles
-    int32_t shrink_stream_min_tokens;  // batches with at least this many adapter tokens use the streaming shrink
-    int32_t shrink_stream_wgs;     // streaming shrink: 64-token tiles when 128-token tiles give fewer workgroups than this
-    int32_t expand_stream_stages;  // streaming expand: stages (of 64 features per wavefront) one workgroup walks
-};
-extern lora_tuning g_lora_tuning;

@@ -8,10 +8,14 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <vector>
 
 #include "plan_internal.h"
 
+namespace {
+std::mutex g_tuning_mutex;                       // guards the process defaults and the shape table
 lora_tuning g_lora_tuning = {
     /*shrink_waves*/ 8,
     /*shrink_tb2_min_rows*/ 64,
@@ -32,19 +36,93 @@ lora_tuning g_lora_tuning = {
     /*expand_stream_stages*/ 16,
 };
 
+// The shape table the library ships with: written by the offline search (autotune.py) on MI355X.
+const lora_tuning_entry kShippedTable[] = {
+#include "tuning_table.inc"
+};
+constexpr int32_t kShippedCount = (int32_t)(sizeof(kShippedTable) / sizeof(kShippedTable[0]));
+std::vector<lora_tuning_entry> g_table(kShippedTable, kShippedTable + kShippedCount);
+
+int32_t rank_class(int32_t r)
+{
+    int32_t c = 8;
+    while (c < r) c *= 2;
+    return c;
+}
+
+void overlay(lora_tuning* t, const int32_t* values, int32_t count)
+{
+    int32_t* dst = reinterpret_cast<int32_t*>(t);
+    for (int32_t i = 0; i < count && i < LORA_TUNING_COUNT; ++i)
+        if (values[i] > 0) dst[i] = values[i];
+}
+
+// The tunables of one plan: defaults, then the table entry of the batch's shape class, then the descriptor's own.
+void snapshot_tuning(lora_plan* p, const lora_batch_desc* d, int32_t active_tokens, int32_t max_rank, int32_t max_group)
+{
+    std::lock_guard<std::mutex> lock(g_tuning_mutex);
+    p->tuning = g_lora_tuning;
+    p->tuning_source = 0;
+    const int32_t rc = rank_class(max_rank), gc = max_group >= 64 ? 1 : 0;
+    const lora_tuning_entry* best = nullptr;
+    for (const lora_tuning_entry& e : g_table) {
+        if (e.k != p->K || e.n != p->N || e.max_rank != rc || e.group_class != gc) continue;
+        if (!best) { best = &e; continue; }
+        const bool e_covers = e.tokens >= active_tokens, b_covers = best->tokens >= active_tokens;
+        if (e_covers != b_covers ? e_covers : (e_covers ? e.tokens < best->tokens : e.tokens > best->tokens)) best = &e;
+    }
+    if (best && active_tokens > 0) {
+        overlay(&p->tuning, best->values, LORA_TUNING_COUNT);
+        p->tuning_source = 1;
+    }
+    if (d->tuning && d->tuning_count > 0) {
+        bool any = false;
+        for (int32_t i = 0; i < d->tuning_count && i < LORA_TUNING_COUNT; ++i) any = any || d->tuning[i] > 0;
+        overlay(&p->tuning, d->tuning, d->tuning_count);
+        if (any) p->tuning_source += 2;
+    }
+}
+}  // namespace
+
 extern "C" void lora_tuning_set(const int32_t* values, int32_t count)
 {
-    int32_t* dst = reinterpret_cast<int32_t*>(&g_lora_tuning);
-    const int32_t n = (int32_t)(sizeof(lora_tuning) / sizeof(int32_t));
-    for (int32_t i = 0; i < count && i < n; ++i)
-        if (values[i] > 0) dst[i] = values[i];
+    if (!values) return;
+    std::lock_guard<std::mutex> lock(g_tuning_mutex);
+    overlay(&g_lora_tuning, values, count);
 }
 
 extern "C" void lora_tuning_get(int32_t* values, int32_t count)
 {
+    if (!values) return;
+    std::lock_guard<std::mutex> lock(g_tuning_mutex);
     const int32_t* src = reinterpret_cast<const int32_t*>(&g_lora_tuning);
-    const int32_t n = (int32_t)(sizeof(lora_tuning) / sizeof(int32_t));
-    for (int32_t i = 0; i < count && i < n; ++i) values[i] = src[i];
+    for (int32_t i = 0; i < count && i < LORA_TUNING_COUNT; ++i) values[i] = src[i];
+}
+
+extern "C" lora_status lora_tuning_table_set(const lora_tuning_entry* entries, int32_t count)
+{
+    if (count < 0 || (count > 0 && !entries)) return LORA_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < count; ++i)
+        if (entries[i].tokens < 0 || entries[i].k < 1 || entries[i].n < 1 || entries[i].max_rank != rank_class(entries[i].max_rank) ||
+            entries[i].max_rank > LORA_MAX_RANK || entries[i].group_class < 0 || entries[i].group_class > 1)
+            return LORA_ERR_INVALID_ARG;
+    try {
+        std::vector<lora_tuning_entry> next = count ? std::vector<lora_tuning_entry>(entries, entries + count)
+                                                    : std::vector<lora_tuning_entry>(kShippedTable, kShippedTable + kShippedCount);
+        std::lock_guard<std::mutex> lock(g_tuning_mutex);
+        g_table.swap(next);
+    } catch (const std::bad_alloc&) {
+        return LORA_ERR_NOMEM;
+    }
+    return LORA_OK;
+}
+
+extern "C" int32_t lora_tuning_table_get(lora_tuning_entry* entries, int32_t capacity)
+{
+    std::lock_guard<std::mutex> lock(g_tuning_mutex);
+    if (entries)
+        for (int32_t i = 0; i < capacity && i < (int32_t)g_table.size(); ++i) entries[i] = g_table[i];
+    return (int32_t)g_table.size();
 }
 
 static bool validate(const lora_batch_desc* d)
@@ -53,6 +131,7 @@ static bool validate(const lora_batch_desc* d)
     if (d->k < 1 || d->n < 1) return false;
     if (d->dtype != LORA_F32 && d->dtype != LORA_BF16) return false;
     if (d->variant < LORA_VARIANT_AUTO || d->variant > LORA_VARIANT_TILED) return false;
+    if (d->tuning_count < 0 || (d->tuning_count > 0 && !d->tuning)) return false;
     if (!d->seg_indptr) return false;                       // even S = 0 has the single entry [0]
     if (d->num_segments > 0 && !d->seg_adapter) return false;
     if (d->num_adapters > 0 && (!d->adapter_rank || !d->adapter_scale)) return false;
@@ -78,7 +157,7 @@ static int32_t round_up(int32_t v, int32_t m) { return (v + m - 1) / m * m; }
 // of output features that the workgroup's four wavefronts split evenly.
 static void build_tiles(lora_plan* p)
 {
-    const lora_tuning& tu = g_lora_tuning;
+    const lora_tuning& tu = p->tuning;
     p->shrink_max_blocks = 1;
     p->shrink_small = true;
     p->expand_small = true;
@@ -397,6 +476,11 @@ extern "C" lora_status lora_plan_create(const lora_batch_desc* d, lora_plan** ou
         for (int32_t a = 0; a < p->n_a; ++a) table_max = std::max(table_max, p->rank[a]);
         p->R = std::max(8, round_up(table_max, 8));
 
+        int32_t max_group = 0;
+        for (size_t g = 0; g + 1 < p->group_offset.size(); ++g)
+            max_group = std::max(max_group, p->group_offset[g + 1] - p->group_offset[g]);
+        snapshot_tuning(p, d, (int32_t)p->perm.size(), max_rank, max_group);
+
         // the tiled kernels take bf16, 16-byte rows (K and ranks multiples of 8), ranks <= 128
         p->tiled_layout_ok = (p->dtype == LORA_BF16) && (p->K % 8 == 0) && ranks_mult8 && max_rank <= 128;
         const int32_t n_active = (int32_t)p->perm.size();
@@ -405,7 +489,7 @@ extern "C" lora_status lora_plan_create(const lora_batch_desc* d, lora_plan** ou
         else if (p->variant_req == LORA_VARIANT_TILED)
             p->family = LORA_VARIANT_TILED;
         else
-            p->family = (n_active >= g_lora_tuning.tiled_min_tokens) ? LORA_VARIANT_TILED : LORA_VARIANT_GENERAL;
+            p->family = (n_active >= p->tuning.tiled_min_tokens) ? LORA_VARIANT_TILED : LORA_VARIANT_GENERAL;
         if (p->family == LORA_VARIANT_TILED) build_tiles(p);
         if (p->tiled_layout_ok && p->n_a < (1 << 24)) build_gemm_tables(p);
     } catch (const std::bad_alloc&) {
@@ -448,6 +532,9 @@ extern "C" lora_status lora_plan_export(const lora_plan* p, lora_plan_view* v)
     v->kernel_family = p->family;
     v->shrink_waves = p->shrink_waves;
     v->v_parts = p->v_parts;
+    v->tuning_source = p->tuning_source;
+    std::memcpy(v->tuning, &p->tuning, sizeof(p->tuning));
+    v->reserved = 0;
     v->token_adapter = p->token_adapter.data();
     v->perm = p->perm.data();
     v->group_adapter = p->group_adapter.data();

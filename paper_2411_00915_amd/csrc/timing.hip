@@ -17,7 +17,7 @@ const char* kNames[LORA_K_COUNT] = {"shrink_general_kernel", "expand_general_ker
                                     "expand_tiled_kernel", "gemm_general_kernel", "gemm_tiled_kernel",
                                     "gemm_tiled_kernel<delta>", "delta_fused_small_kernel", "v_split_kernel",
                                     "shrink_stream_kernel", "expand_stream_kernel", "merge_kernel",
-                                    "gemm_ring_kernel", "gemm_ring_kernel<delta>", "clear_words_kernel"};
+                                    "gemm_ring_kernel", "gemm_ring_kernel<delta>", "clear_words_kernel", "probe_empty_kernel", "probe_read_kernel", "probe_mfma_kernel"};
 }  // namespace
 
 bool lora_timing_on() { return g_on; }

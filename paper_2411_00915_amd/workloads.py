@@ -84,8 +84,30 @@ def _normal(rng: np.random.Generator, shape, var: float, dtype: str) -> np.ndarr
     return round_to_bf16(a) if dtype == "bf16" else a
 
 
+_TABLES_ONLY = False
+
+
+class tables_only:
+    """Context manager: the generators inside it return the segment, rank and scale tables of a configuration
+    without drawing its matrices (x, W, A, B stay None / empty).  The tables come before the matrices in the draw
+    order, so they are the same either way.  For benchmarks, which fill device buffers of the right sizes with
+    random values instead of uploading gigabytes of host draws."""
+
+    def __enter__(self):
+        global _TABLES_ONLY
+        self._before, _TABLES_ONLY = _TABLES_ONLY, True
+        return self
+
+    def __exit__(self, *exc):
+        global _TABLES_ONLY
+        _TABLES_ONLY = self._before
+        return False
+
+
 def _draw_matrices(rng, dtype, T, K, N, ranks, with_w, used=None):
     """Draw order is fixed: x, W, A_0..A_{n-1}, B_0..B_{n-1}."""
+    if _TABLES_ONLY:
+        return None, None, [], []
     x = _normal(rng, (T, K), 1.0, dtype)
     W = _normal(rng, (K, N), 1.0 / K, dtype) if with_w else None
     A = [_normal(rng, (K, int(r)), 1.0 / K, dtype) for r in ranks]

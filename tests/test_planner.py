@@ -197,6 +197,7 @@ def test_compute_calls_reject_bad_arguments_without_a_gpu():
 def test_tuning_roundtrip_changes_tiles():
     before = B.lora_tuning_get()
     try:
+        B.lora_tuning_table_set([dict(tokens=0, k=1, n=1, max_rank=8, group_class=0, tunables={})])   # no entry applies
         w = wl.cfg3(with_w=False)
         a = _export(w)[0]
         B.lora_tuning_set(shrink_tb2_min_rows=1 << 20, shrink_tb4_min_rows=1 << 20, expand_tb2_min_rows=1 << 20,
@@ -210,6 +211,7 @@ def test_tuning_roundtrip_changes_tiles():
         _check_tiles(w, b, tok, perm)
     finally:
         B.lora_tuning_set(**before)
+        B.lora_tuning_table_set([])
     assert B.lora_tuning_get() == before
 
 
@@ -223,28 +225,54 @@ def test_library_exports_every_declared_symbol():
     assert names == set(B.EXPORTED)
 
 
-def test_shape_keyed_tuning_table_roundtrip(tmp_path):
-    from paper_2411_00915_amd import tuning_table as tt
-    path = str(tmp_path / "table.json")
-    before = B.lora_tuning_get()
+def test_shape_table_is_consulted_inside_plan_create():
+    """The shape-keyed table (paper section 4.3.2): lora_plan_create looks the batch's class up -- tokens with an
+    adapter (smallest entry at or above, else the largest), K, N, rank class, group class -- and plans with the
+    entry on top of the process defaults; values in the descriptor override both; every plan keeps its snapshot."""
+    defaults = B.lora_tuning_get()
+    shipped = B.lora_tuning_table_get()
+    assert all(set(e["tunables"]) <= set(B.TUNING_FIELDS) for e in shipped)
+    w = wl.cfg2(with_w=False)                                   # 256 tokens, 4096 -> 4096, ranks up to 64, decode-shaped
     try:
-        assert tt.shape_key(300, 4096, 4096, 64) == "T512_K4096_N4096_R64" and tt.shape_key(512, 8, 8, 8).startswith("T512_")
-        tt.store(tt.shape_key(4096, 4096, 4096, 64), {"expand_stream_stages": 8, "shrink_stream_wgs": 2048}, path)
-        tt.store(tt.shape_key(256, 4096, 4096, 64), {"fused_delay": 5}, path)
-        assert tt.apply_for_shape(3000, 4096, 4096, 64, path) == {"expand_stream_stages": 8, "shrink_stream_wgs": 2048}
-        now = B.lora_tuning_get()
-        assert now["expand_stream_stages"] == 8 and now["shrink_stream_wgs"] == 2048 and now["fused_delay"] == before["fused_delay"]
-        assert tt.apply_for_shape(17, 64, 64, 8, path, defaults=before) is None      # no entry: defaults stay
-        assert B.lora_tuning_get() == before
-        with open(path, "w") as f:
-            f.write('{"T1_K1_N1_R1": {"no_such_tunable": 1}}')
+        B.lora_tuning_table_set([
+            dict(tokens=128, k=4096, n=4096, max_rank=64, group_class=0, tunables={"expand_wave_bytes": 4096}),
+            dict(tokens=512, k=4096, n=4096, max_rank=64, group_class=0, tunables={"expand_wave_bytes": 32768, "fused_delay": 7}),
+            dict(tokens=1024, k=4096, n=4096, max_rank=64, group_class=0, tunables={"expand_wave_bytes": 65536}),
+            dict(tokens=512, k=4096, n=4096, max_rank=64, group_class=1, tunables={"expand_wave_bytes": 8192}),
+            dict(tokens=512, k=4096, n=4096, max_rank=32, group_class=0, tunables={"expand_wave_bytes": 8192}),
+            dict(tokens=512, k=4096, n=11008, max_rank=64, group_class=0, tunables={"expand_wave_bytes": 8192}),
+        ])
+        assert len(B.lora_tuning_table_get()) == 6
+        p = device.make_plan(w)
+        v = B.lora_plan_export(p)
+        assert v["tuning_source"] == 1
+        assert v["tuning"]["expand_wave_bytes"] == 32768 and v["tuning"]["fused_delay"] == 7      # the 512-token entry
+        assert v["tuning"]["shrink_target_wgs"] == defaults["shrink_target_wgs"]                   # not in the entry
+        n_tab = v["expand_tiles"].shape[0]
+        # the descriptor's own values win over the entry
+        q = device.make_plan(w, tuning={"expand_wave_bytes": 8192})
+        vq = B.lora_plan_export(q)
+        assert vq["tuning_source"] == 3 and vq["tuning"]["expand_wave_bytes"] == 8192 and vq["tuning"]["fused_delay"] == 7
+        assert vq["expand_tiles"].shape[0] > n_tab                                                 # smaller tiles, more of them
+        tok, perm = _check_tables(w, vq)
+        _check_tiles(w, vq, tok, perm)
+        # beyond the largest bucket: the largest entry; a shape class without entry: defaults
+        big = wl.random_case(5, 1500, 4096, 4096, 600, (8, 64), max_seg=1, with_w=False)
+        assert B.lora_plan_export(device.make_plan(big))["tuning"]["expand_wave_bytes"] == 65536
+        other = wl.random_case(6, 100, 512, 512, 30, (8, 64), max_seg=1, with_w=False)
+        vo = B.lora_plan_export(device.make_plan(other))
+        assert vo["tuning_source"] == 0 and vo["tuning"] == defaults
+        # replacing the table does not touch plans already made
+        B.lora_tuning_table_set([])
+        assert B.lora_plan_export(p)["tuning"]["expand_wave_bytes"] == 32768
+        assert B.lora_tuning_table_get() == shipped
+        with pytest.raises(B.LoraError):
+            B.lora_tuning_table_set([dict(tokens=64, k=64, n=64, max_rank=48, group_class=0, tunables={})])   # not a rank class
         with pytest.raises(KeyError):
-            tt.load(path)
-        # the table that ships with the package loads and names only known tunables
-        shipped = tt.load()
-        assert all(set(e) <= set(B.TUNING_FIELDS) for e in shipped.values())
+            B.lora_tuning_table_set([dict(tokens=64, k=64, n=64, max_rank=64, group_class=0, tunables={"no_such_tunable": 1})])
     finally:
-        B.lora_tuning_set(**before)
+        B.lora_tuning_table_set([])
+    assert B.lora_tuning_get() == defaults
 
 
 def test_build_refuses_scratch_in_kernels_that_count_their_loads():

@@ -388,7 +388,8 @@ int32_t     lora_kernel_count(void);
 /*
  * lora_probe -- measured ceilings of the machine, for benchmark reports (the per-kernel timers above time them
  * like any kernel of the library).  buffer: device memory, 16-byte aligned, `bytes` long.
- *   LORA_PROBE_EMPTY  a launch of 1280 workgroups that does nothing: the floor of any kernel duration
+ *   LORA_PROBE_EMPTY  a launch of 1280 workgroups (iters > 1: of iters workgroups) of 256 threads that does nothing:
+ *                     the floor of any kernel duration
  *   LORA_PROBE_READ   one-shot read of the first floor(bytes / 32 KiB) * 32 KiB of the buffer, no dependency
  *                     between loads (every lane asks for its eight 16-byte pieces at once, whole cache lines per
  *                     wavefront, non-temporal): what a launch of that size can get out of HBM at best

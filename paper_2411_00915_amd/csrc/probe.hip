@@ -65,7 +65,8 @@ extern "C" lora_status lora_probe(int32_t kind, void* buffer, size_t bytes, int3
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (!buffer || bytes < 64 || (reinterpret_cast<uintptr_t>(buffer) & 15)) return LORA_ERR_INVALID_ARG;
     if (kind == LORA_PROBE_EMPTY) {
-        LORA_LAUNCH(LORA_K_PROBE_EMPTY, probe_empty_kernel, dim3(1280), dim3(256), 0, stream, static_cast<unsigned*>(buffer), 0);
+        // (iters > 1: that many workgroups instead of 1280)
+        LORA_LAUNCH(LORA_K_PROBE_EMPTY, probe_empty_kernel, dim3(iters > 1 ? iters : 1280), dim3(256), 0, stream, static_cast<unsigned*>(buffer), 0);
     } else if (kind == LORA_PROBE_READ) {
         constexpr int U = 8;                                       // 128 bytes in flight per lane, 32 KB per workgroup
         const size_t blocks = bytes / (256 * U * 16);

@@ -48,6 +48,32 @@
  * and needs no GPU.  Compute calls check pointers, leading dimensions and
  * alignment before launching and map HIP failures to LORA_ERR_DEVICE.
  *
+ * MIXTURE MODE (section 4.4.1: one adapter m stays merged in the base weight
+ * while requests of other adapters run in the same batch; their branch takes
+ * m's update off again, the paper's deLoRA).  A plan made with
+ * merged_adapter_plus1 = m + 1 computes, on the merged weight W',
+ *
+ *     tokens of adapter m:          y = x W'                      (no branch)
+ *     tokens of adapter a != m:     y = x W' + s_a (x A_a) B_a - s_m (x A_m) B_m
+ *     tokens without adapter:       y = x W'                    - s_m (x A_m) B_m
+ *
+ * which equals unmerged inference on W up to the rounding of W'.  The caller
+ * passes the same pointer tables as always (entry m is read for the removal);
+ * no concatenated matrices exist anywhere.  Inside, the removal is a second
+ * batch over the same tokens ("every token that is not m's uses adapter m with
+ * scale -s_m") with tiles of its own: lora_shrink writes its partial sums
+ * behind the batch's own in v (lora_plan_view: unmerge_v_offset, row stride and
+ * parts), lora_expand and lora_delta add first the removal (with the caller's
+ * beta), then the tokens' own branches (accumulating): two passes over y, each
+ * rounding it once, so a token with an adapter of its own gets
+ * rnd(rnd(beta y + removal) + own) -- within u (|beta y + removal| + |y|) of
+ * the exact value, u the unit roundoff of the dtype.  lora_fused_forward's
+ * GEMM takes the removal in as one more group of adapter stages per tile of
+ * rows, inside the same fp32 accumulators: one rounding, as without mixture
+ * mode.  "Rows of tokens without adapter are
+ * left untouched" then holds for the tokens of adapter m only.
+ * merged_adapter_plus1 naming an adapter of rank 0: same as 0.
+ *
  * ALIGNMENT for the tuned bf16 kernels: base pointers 16 bytes; K, ldx, ldy,
  * ldw multiples of 8; ranks multiples of 8.  Anything else (and fp32) runs
  * through a general kernel with no alignment demands.
@@ -109,6 +135,9 @@ typedef struct {
                                       What is given here overrides the shape table's entry, which overrides the
                                       process defaults.  NULL / 0: nothing given */
     int32_t        tuning_count;
+    int32_t        merged_adapter_plus1;  /* mixture mode (section 4.4.1): 1 + the index of the adapter whose update
+                                      the caller has folded into the base weight this batch runs on
+                                      (W' = W + s_m A_m B_m, e.g. by lora_merge); 0 = none.  See MIXTURE MODE below */
 } lora_batch_desc;
 
 /* One unit of kernel work: the rows [row0,row0+nrows) of `perm` (all of one
@@ -156,6 +185,18 @@ typedef struct {
     const int32_t* gemm_order;           /* [num_gemm_rows] */
     const int32_t* gemm_stage_offset;    /* [num_gemm_tiles + 1] exclusive prefix sums into gemm_stage */
     const int32_t* gemm_stage;           /* [gemm_stage_offset[num_gemm_tiles]] */
+    /* Mixture mode (merged_adapter_plus1 > 0 and that adapter has rank > 0); otherwise -1 / 0 / NULL.  The stage
+     * list of a tile that holds a token the removal applies to ends with the entries
+     * merged_adapter | 1 << 23 | block << 24, one per block of the merged adapter's 2 r columns; gemm_order then
+     * lists tokens with an adapter of their own, tokens without one, and last the merged adapter's tokens. */
+    int32_t        merged_adapter;       /* m, or -1 */
+    int32_t        num_unmerge;          /* tokens the removal applies to: all that are not m's */
+    int32_t        unmerge_v_row_stride; /* row stride (floats) and parts of the removal's share of v */
+    int32_t        unmerge_v_parts;
+    size_t         unmerge_v_offset;     /* bytes from the start of v to that share (256-byte aligned) */
+    const int32_t* unmerge_perm;         /* [num_unmerge] those tokens, ascending */
+    const lora_tile* unmerge_shrink_tiles;  int32_t num_unmerge_shrink_tiles;   /* tile lists of the removal */
+    const lora_tile* unmerge_expand_tiles;  int32_t num_unmerge_expand_tiles;
 } lora_plan_view;
 
 /*
@@ -169,7 +210,7 @@ typedef struct {
  * byte-identical tables.  One plan serves every layer / projection that shares
  * the segment table, K, N, ranks and scales.
  *
- * Returns LORA_ERR_INVALID_ARG for: null desc/out; negative sizes; null tables
+ * Returns LORA_ERR_INVALID_ARG for: null desc/out; negative sizes; merged_adapter_plus1 outside [0, n_a]; null tables
  * with non-zero counts; seg_indptr not starting at 0, decreasing, or not ending
  * at T; adapter id outside [-1, n_a); rank outside [0, LORA_MAX_RANK];
  * non-finite scale; K or N < 1; unknown dtype or variant.
@@ -177,8 +218,9 @@ typedef struct {
 lora_status lora_plan_create(const lora_batch_desc* desc, lora_plan** out);
 void        lora_plan_destroy(lora_plan* plan);   /* NULL is allowed */
 
-/* v_row_stride R (floats), bytes of the v buffer (P*T*R*4), and the bytes of
- * workspace lora_fused_forward needs (v plus its bf16 split).  Any out pointer may be NULL. */
+/* v_row_stride R (floats), bytes of the v buffer (P*T*R*4; in mixture mode that, rounded up to 256, plus the
+ * removal's share), and the bytes of workspace lora_fused_forward needs (v plus its bf16 split).  Any out pointer
+ * may be NULL. */
 lora_status lora_plan_query(const lora_plan* plan, int32_t* v_row_stride,
                             size_t* v_bytes, size_t* fused_workspace_bytes);
 
@@ -250,8 +292,8 @@ lora_status lora_delta(lora_plan* plan, const void* x, int64_t ldx,
  * library runs on until the process ends).  The call allocates nothing and frees nothing.
  *   - The plan must already be on the current device (lora_plan_upload, which does allocate, at set-up);
  *     otherwise LORA_ERR_INVALID_ARG.
- *   - lora_plan_query's v_bytes above LORA_STATIC_V_BYTES, or more than LORA_STATIC_MAX_GROUPS distinct adapters
- *     in use: LORA_ERR_UNSUPPORTED (use lora_delta with a caller-owned v).
+ *   - lora_plan_query's v_bytes above LORA_STATIC_V_BYTES, more than LORA_STATIC_MAX_GROUPS distinct adapters
+ *     in use, or a plan in mixture mode: LORA_ERR_UNSUPPORTED (use lora_delta with a caller-owned v).
  *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents (the counters are
  *     cleared by a small kernel at the start of every call that uses them): calls that overlap on one GPU
  *     -- two streams, two threads -- race.  Calls on one stream, and calls on different GPUs, do not.

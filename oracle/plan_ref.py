@@ -71,13 +71,31 @@ def check_cover(tiles_rows_cols, tok_adapter, perm, extent, adapter_rank=None, r
     return True
 
 
-def check_gemm_tables(T, tok_adapter, adapter_rank, order, stage_offset, stages, rows_per_tile=256, stage_cols=32):
+def mixture_tables(T, seg_indptr, seg_adapter, adapter_rank, merged):
+    """Mixture mode (section 4.4.1): adapter `merged` is folded into the base weight.  Requests of that adapter then
+    need no branch; every other request -- with an adapter of its own or with none -- needs the merged update taken
+    off again.  Returns (seg_adapter of the tokens' own branches: the merged adapter's segments carry none,
+    removal: boolean [T], True where the removal applies)."""
+    seg_adapter = np.asarray(seg_adapter, dtype=np.int64)
+    lens = np.diff(np.asarray(seg_indptr, dtype=np.int64))
+    own = np.where(seg_adapter == merged, -1, seg_adapter)
+    removal = np.repeat(seg_adapter != merged, lens)
+    assert removal.shape[0] == T
+    return own.astype(np.int32), removal
+
+
+def check_gemm_tables(T, tok_adapter, adapter_rank, order, stage_offset, stages, rows_per_tile=256, stage_cols=32,
+                      merged=-1, removal=None):
     """Validity of the fused forward's tables (they are the planner's free choice; only this is fixed).
 
     The fused forward adds s_a (x A_a) B_a to the base product as extra contraction length: for every adapter a the
     columns of [v_hi | v_lo] (2 r_a of them) are cut into blocks of `stage_cols`, and a tile of rows must run one
     stage per (adapter present in the tile, block) -- each exactly once, or the delta of some token is dropped or
-    counted twice -- and none for adapters it does not hold.  `order` must visit every token exactly once."""
+    counted twice -- and none for adapters it does not hold.  `order` must visit every token exactly once.
+
+    Mixture mode (`merged` >= 0, `removal` a boolean mask over tokens): a tile that holds a token of the mask must
+    also run the merged adapter's blocks once more, marked by bit 23 of the stage (they apply to the masked rows,
+    whatever adapter these have); a tile without such a token must not."""
     tok = np.asarray(tok_adapter, dtype=np.int64)
     rank = np.asarray(adapter_rank, dtype=np.int64)
     order = np.asarray(order, dtype=np.int64)
@@ -88,8 +106,16 @@ def check_gemm_tables(T, tok_adapter, adapter_rank, order, stage_offset, stages,
     assert stage_offset.shape[0] == n_tiles + 1 and stage_offset[0] == 0 and stage_offset[-1] == stages.shape[0]
     assert np.all(np.diff(stage_offset) >= 0)
     for tile in range(n_tiles):
-        present = {int(a) for a in tok[order[tile * rows_per_tile:(tile + 1) * rows_per_tile]] if a >= 0}
+        rows = order[tile * rows_per_tile:(tile + 1) * rows_per_tile]
+        present = {int(a) for a in tok[rows] if a >= 0}
         want = sorted((a, jb) for a in present for jb in range(-(-2 * int(rank[a]) // stage_cols)))
-        got = sorted((int(s) & 0xffffff, int(s) >> 24) for s in stages[stage_offset[tile]:stage_offset[tile + 1]])
+        mine = stages[stage_offset[tile]:stage_offset[tile + 1]]
+        got = sorted((int(s) & 0xffffff, int(s) >> 24) for s in mine if not int(s) & (1 << 23))
         assert got == want, f"tile {tile}: adapter stages do not cover its adapters' columns exactly once"
+        marked = sorted((int(s) & 0x7fffff, int(s) >> 24) for s in mine if int(s) & (1 << 23))
+        if merged >= 0 and np.any(np.asarray(removal)[rows]):
+            assert marked == [(merged, jb) for jb in range(-(-2 * int(rank[merged]) // stage_cols))], \
+                f"tile {tile}: the merged adapter's removal does not cover its columns exactly once"
+        else:
+            assert not marked, f"tile {tile}: removal stages although no row needs them"
     return True

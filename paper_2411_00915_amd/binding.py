@@ -41,7 +41,8 @@ class BatchDesc(ctypes.Structure):
                 ("seg_indptr", _i32p), ("seg_adapter", _i32p),
                 ("num_adapters", ctypes.c_int32), ("adapter_rank", _i32p), ("adapter_scale", _f32p),
                 ("k", ctypes.c_int32), ("n", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("variant", ctypes.c_int32), ("tuning", _i32p), ("tuning_count", ctypes.c_int32)]
+                ("variant", ctypes.c_int32), ("tuning", _i32p), ("tuning_count", ctypes.c_int32),
+                ("merged_adapter_plus1", ctypes.c_int32)]
 
 
 class Tile(ctypes.Structure):
@@ -60,7 +61,12 @@ class PlanView(ctypes.Structure):
                 ("shrink_tiles", ctypes.POINTER(Tile)), ("num_shrink_tiles", ctypes.c_int32),
                 ("expand_tiles", ctypes.POINTER(Tile)), ("num_expand_tiles", ctypes.c_int32),
                 ("num_gemm_rows", ctypes.c_int32), ("num_gemm_tiles", ctypes.c_int32),
-                ("gemm_order", _i32p), ("gemm_stage_offset", _i32p), ("gemm_stage", _i32p)]
+                ("gemm_order", _i32p), ("gemm_stage_offset", _i32p), ("gemm_stage", _i32p),
+                ("merged_adapter", ctypes.c_int32), ("num_unmerge", ctypes.c_int32),
+                ("unmerge_v_row_stride", ctypes.c_int32), ("unmerge_v_parts", ctypes.c_int32),
+                ("unmerge_v_offset", ctypes.c_size_t), ("unmerge_perm", _i32p),
+                ("unmerge_shrink_tiles", ctypes.POINTER(Tile)), ("num_unmerge_shrink_tiles", ctypes.c_int32),
+                ("unmerge_expand_tiles", ctypes.POINTER(Tile)), ("num_unmerge_expand_tiles", ctypes.c_int32)]
 
 
 _vp = ctypes.c_void_p
@@ -256,9 +262,10 @@ class Plan:
 
 
 def lora_plan(num_tokens, seg_indptr, seg_adapter, adapter_rank, adapter_scale, k, n, dtype,
-              variant=LORA_VARIANT_AUTO, tuning: Optional[dict] = None) -> Plan:
+              variant=LORA_VARIANT_AUTO, tuning: Optional[dict] = None, merged_adapter: Optional[int] = None) -> Plan:
     """lora_plan_create; tables are host arrays (numpy or sequences).  tuning: tunables for this plan only
-    (name -> value), on top of the shape table's entry and the process defaults."""
+    (name -> value), on top of the shape table's entry and the process defaults.  merged_adapter: mixture mode,
+    the adapter that is folded into the base weight the batch runs on (None: no adapter is)."""
     indptr = np.ascontiguousarray(seg_indptr, dtype=np.int32)
     seg_ad = np.ascontiguousarray(seg_adapter, dtype=np.int32)
     rank = np.ascontiguousarray(adapter_rank, dtype=np.int32)
@@ -266,7 +273,8 @@ def lora_plan(num_tokens, seg_indptr, seg_adapter, adapter_rank, adapter_scale, 
     desc = BatchDesc(int(num_tokens), int(seg_ad.shape[0]),
                      indptr.ctypes.data_as(_i32p), seg_ad.ctypes.data_as(_i32p),
                      int(rank.shape[0]), rank.ctypes.data_as(_i32p), scale.ctypes.data_as(_f32p),
-                     int(k), int(n), int(dtype), int(variant), None, 0)
+                     int(k), int(n), int(dtype), int(variant), None, 0,
+                     0 if merged_adapter is None else int(merged_adapter) + 1)
     if tuning:
         vals = (ctypes.c_int32 * LORA_TUNING_COUNT)(*_tuning_values(tuning))
         desc.tuning = ctypes.cast(vals, _i32p)
@@ -321,7 +329,12 @@ def lora_plan_export(plan: Plan) -> dict:
                 gemm_order=arr(v.gemm_order, v.num_gemm_rows),
                 gemm_stage_offset=arr(v.gemm_stage_offset, v.num_gemm_tiles + 1 if v.num_gemm_tiles else 0),
                 gemm_stage=(arr(v.gemm_stage, int(v.gemm_stage_offset[v.num_gemm_tiles])) if v.num_gemm_tiles
-                            else np.zeros(0, np.int32)))
+                            else np.zeros(0, np.int32)),
+                merged_adapter=v.merged_adapter, num_unmerge=v.num_unmerge,
+                unmerge_v_row_stride=v.unmerge_v_row_stride, unmerge_v_parts=v.unmerge_v_parts,
+                unmerge_v_offset=int(v.unmerge_v_offset), unmerge_perm=arr(v.unmerge_perm, v.num_unmerge),
+                unmerge_shrink_tiles=tiles(v.unmerge_shrink_tiles, v.num_unmerge_shrink_tiles),
+                unmerge_expand_tiles=tiles(v.unmerge_expand_tiles, v.num_unmerge_expand_tiles))
 
 
 def lora_plan_upload(plan: Plan, stream=None):

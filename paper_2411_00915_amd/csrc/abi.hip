@@ -62,7 +62,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 struct table_layout {
-    size_t perm, token_adapter, rank, scale, shrink_tiles, expand_tiles, sync, sync_bytes, total;
+    size_t perm, token_adapter, row_key, rank, scale, shrink_tiles, expand_tiles, sync, sync_bytes, total;
     size_t order, extra_ptr128, extra128, extra_ptr256, extra256, extra_ptr256h, extra256h, zeros, shrink_rows, expand_rows;
 };
 
@@ -73,6 +73,7 @@ table_layout layout_of(const lora_plan* p)
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     L.perm = take(p->perm.size() * sizeof(int32_t));
     L.token_adapter = take(p->token_adapter.size() * sizeof(int32_t));
+    L.row_key = take(p->row_key.size() * sizeof(int32_t));
     L.rank = take(p->rank.size() * sizeof(int32_t));
     L.scale = take(p->scale.size() * sizeof(float));
     L.shrink_tiles = take(p->shrink_tiles.size() * sizeof(lora_tile));
@@ -98,6 +99,10 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return LORA_ERR_DEVICE;
     if (p->d_buf) return p->device == dev ? LORA_OK : LORA_ERR_INVALID_ARG;   // a plan lives on one device
+    if (p->unmerge) {                                                         // mixture mode: the removal's tables first
+        const lora_status st = ensure_uploaded(p->unmerge, stream);
+        if (st != LORA_OK) return st;
+    }
 
     // set-up is also where the address of lora_delta_static's device array is looked up (the first use of a
     // device array makes the runtime place it; the static call itself then finds it resolved)
@@ -133,6 +138,7 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     auto put = [&](size_t off, const void* src, size_t bytes) { if (bytes) std::memcpy(h + off, src, bytes); };
     put(L.perm, p->perm.data(), p->perm.size() * sizeof(int32_t));
     put(L.token_adapter, p->token_adapter.data(), p->token_adapter.size() * sizeof(int32_t));
+    put(L.row_key, p->row_key.data(), p->row_key.size() * sizeof(int32_t));
     put(L.rank, p->rank.data(), p->rank.size() * sizeof(int32_t));
     put(L.scale, p->scale.data(), p->scale.size() * sizeof(float));
     put(L.shrink_tiles, p->shrink_tiles.data(), p->shrink_tiles.size() * sizeof(lora_tile));
@@ -161,6 +167,7 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     p->h_stage = hbuf;
     p->d_perm = reinterpret_cast<int32_t*>(d + L.perm);
     p->d_token_adapter = reinterpret_cast<int32_t*>(d + L.token_adapter);
+    p->d_row_key = reinterpret_cast<int32_t*>(d + L.row_key);
     p->d_rank = reinterpret_cast<int32_t*>(d + L.rank);
     p->d_scale = reinterpret_cast<float*>(d + L.scale);
     p->d_shrink_tiles = reinterpret_cast<lora_tile*>(d + L.shrink_tiles);
@@ -181,12 +188,19 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
 
 lora_dev_tables tables_of(const lora_plan* p)
 {
-    return lora_dev_tables{p->d_perm, p->d_token_adapter, p->d_rank, p->d_scale, p->d_shrink_tiles, p->d_expand_tiles,
+    return lora_dev_tables{p->d_perm, p->d_token_adapter, p->d_row_key, p->d_rank, p->d_scale, p->d_shrink_tiles, p->d_expand_tiles,
                            p->d_sync, p->d_order, p->d_extra_ptr128, p->d_extra128, p->d_extra_ptr256, p->d_extra256, p->d_extra_ptr256h, p->d_extra256h, p->d_zeros,
                            p->d_shrink_rows, p->d_expand_rows};
 }
 
 size_t elem_bytes(int32_t dtype) { return dtype == LORA_F32 ? 4 : 2; }
+
+// mixture mode: the removal's share of the caller's v
+float* removal_v(const lora_plan* p, float* v)
+{
+    return v ? reinterpret_cast<float*>(reinterpret_cast<char*>(v) + lora_unmerge_v_offset(p)) : nullptr;
+}
+const float* removal_v(const lora_plan* p, const float* v) { return removal_v(p, const_cast<float*>(v)); }
 
 // layout the tiled kernels need at call time
 bool tiled_call_ok(const void* base, int64_t ld) { return !misaligned(base, 16) && ld % 8 == 0; }
@@ -227,10 +241,10 @@ extern "C" lora_status lora_plan_upload(lora_plan* p, void* hip_stream)
     return ensure_uploaded(p, static_cast<hipStream_t>(hip_stream));
 }
 
-extern "C" lora_status lora_shrink(lora_plan* p, const void* x, int64_t ldx,
-                                   const void* const* d_At_ptrs, float* v, void* hip_stream)
+// The three calls on one plan's own tiles; the entry points below add the second batch of a plan in mixture mode.
+static lora_status shrink_own(lora_plan* p, const void* x, int64_t ldx,
+                              const void* const* d_At_ptrs, float* v, void* hip_stream)
 {
-    if (!p) return LORA_ERR_INVALID_ARG;
     if (p->perm.empty()) return LORA_OK;                       // no token has an adapter: nothing to do
     if (!x || !d_At_ptrs || !v) return LORA_ERR_INVALID_ARG;
     if (ldx < p->K) return LORA_ERR_INVALID_ARG;
@@ -249,11 +263,20 @@ extern "C" lora_status lora_shrink(lora_plan* p, const void* x, int64_t ldx,
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
 }
 
-extern "C" lora_status lora_expand(lora_plan* p, const float* v, const void* const* d_Bt_ptrs,
-                                   void* y, int64_t ldy, float beta, void* hip_stream)
+extern "C" lora_status lora_shrink(lora_plan* p, const void* x, int64_t ldx,
+                                   const void* const* d_At_ptrs, float* v, void* hip_stream)
 {
     if (!p) return LORA_ERR_INVALID_ARG;
-    if (!(beta == 0.f || beta == 1.f)) return LORA_ERR_INVALID_ARG;
+    if (p->unmerge) {                                          // mixture mode: the removal's share of v lies behind
+        const lora_status st = shrink_own(p->unmerge, x, ldx, d_At_ptrs, removal_v(p, v), hip_stream);
+        if (st != LORA_OK) return st;
+    }
+    return shrink_own(p, x, ldx, d_At_ptrs, v, hip_stream);
+}
+
+static lora_status expand_own(lora_plan* p, const float* v, const void* const* d_Bt_ptrs,
+                              void* y, int64_t ldy, float beta, void* hip_stream)
+{
     if (p->perm.empty()) return LORA_OK;
     if (!v || !d_Bt_ptrs || !y) return LORA_ERR_INVALID_ARG;
     if (ldy < p->N) return LORA_ERR_INVALID_ARG;
@@ -272,12 +295,25 @@ extern "C" lora_status lora_expand(lora_plan* p, const float* v, const void* con
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
 }
 
-extern "C" lora_status lora_delta(lora_plan* p, const void* x, int64_t ldx,
-                                  const void* const* d_At_ptrs, const void* const* d_Bt_ptrs,
-                                  float* v, void* y, int64_t ldy, float beta, void* hip_stream)
+extern "C" lora_status lora_expand(lora_plan* p, const float* v, const void* const* d_Bt_ptrs,
+                                   void* y, int64_t ldy, float beta, void* hip_stream)
 {
     if (!p) return LORA_ERR_INVALID_ARG;
     if (!(beta == 0.f || beta == 1.f)) return LORA_ERR_INVALID_ARG;
+    if (p->unmerge && !p->unmerge->perm.empty()) {
+        // mixture mode: the removal reaches every row any branch of this batch touches, so it takes the caller's
+        // beta and the tokens' own branches accumulate onto it
+        const lora_status st = expand_own(p->unmerge, removal_v(p, v), d_Bt_ptrs, y, ldy, beta, hip_stream);
+        if (st != LORA_OK) return st;
+        beta = 1.f;
+    }
+    return expand_own(p, v, d_Bt_ptrs, y, ldy, beta, hip_stream);
+}
+
+static lora_status delta_own(lora_plan* p, const void* x, int64_t ldx,
+                             const void* const* d_At_ptrs, const void* const* d_Bt_ptrs,
+                             float* v, void* y, int64_t ldy, float beta, void* hip_stream)
+{
     if (p->perm.empty()) return LORA_OK;
     if (!x || !d_At_ptrs || !d_Bt_ptrs || !v || !y) return LORA_ERR_INVALID_ARG;
     if (ldx < p->K || ldy < p->N) return LORA_ERR_INVALID_ARG;
@@ -289,9 +325,23 @@ extern "C" lora_status lora_delta(lora_plan* p, const void* x, int64_t ldx,
         const hipError_t e = launch_delta_fused_small(p, tables_of(p), x, ldx, d_At_ptrs, d_Bt_ptrs, v, y, ldy, beta, stream);
         return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
     }
-    lora_status st = lora_shrink(p, x, ldx, d_At_ptrs, v, hip_stream);
+    lora_status st = shrink_own(p, x, ldx, d_At_ptrs, v, hip_stream);
     if (st != LORA_OK) return st;
-    return lora_expand(p, v, d_Bt_ptrs, y, ldy, beta, hip_stream);
+    return expand_own(p, v, d_Bt_ptrs, y, ldy, beta, hip_stream);
+}
+
+extern "C" lora_status lora_delta(lora_plan* p, const void* x, int64_t ldx,
+                                  const void* const* d_At_ptrs, const void* const* d_Bt_ptrs,
+                                  float* v, void* y, int64_t ldy, float beta, void* hip_stream)
+{
+    if (!p) return LORA_ERR_INVALID_ARG;
+    if (!(beta == 0.f || beta == 1.f)) return LORA_ERR_INVALID_ARG;
+    if (p->unmerge && !p->unmerge->perm.empty()) {             // mixture mode: removal first, see lora_expand
+        const lora_status st = delta_own(p->unmerge, x, ldx, d_At_ptrs, d_Bt_ptrs, removal_v(p, v), y, ldy, beta, hip_stream);
+        if (st != LORA_OK) return st;
+        beta = 1.f;
+    }
+    return delta_own(p, x, ldx, d_At_ptrs, d_Bt_ptrs, v, y, ldy, beta, hip_stream);
 }
 
 extern "C" lora_status lora_base_gemm(int32_t T, int32_t K, int32_t N, int32_t dtype,
@@ -306,9 +356,9 @@ extern "C" lora_status lora_base_gemm(int32_t T, int32_t K, int32_t N, int32_t d
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
     if (gemm_tiled_supported(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy))
-        e = launch_gemm_tiled(T, K, N, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
+        e = launch_gemm_tiled(T, K, N, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, gemm_removal{}, nullptr, stream);
     else
-        e = launch_gemm_general(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, stream);
+        e = launch_gemm_general(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, gemm_removal{}, nullptr, stream);
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
 }
 
@@ -343,7 +393,8 @@ extern "C" lora_status lora_fused_forward(lora_plan* p, const void* x, int64_t l
     if (p->T == 0) return LORA_OK;
     if (!x || !Wt || !y || ldx < p->K || ldw < p->K || ldy < p->N) return LORA_ERR_INVALID_ARG;
     if ((int64_t)(p->T + 15) / 16 > 65535) return LORA_ERR_UNSUPPORTED;
-    const bool has_delta = !p->perm.empty();
+    const lora_plan* u = p->unmerge && !p->unmerge->perm.empty() ? p->unmerge : nullptr;
+    const bool has_delta = !p->perm.empty() || u;
     if (has_delta) {
         if (!d_At_ptrs || !d_Bt_ptrs) return LORA_ERR_INVALID_ARG;
         size_t need = 0;
@@ -351,24 +402,28 @@ extern "C" lora_status lora_fused_forward(lora_plan* p, const void* x, int64_t l
         if (!workspace || workspace_bytes < need || misaligned(workspace, 256)) return LORA_ERR_WORKSPACE;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // workspace: v (own parts, then the removal's), the bf16 split of the own v, the split of the removal's
     float* v = static_cast<float*>(workspace);
     size_t v_bytes = 0;
     lora_plan_query(p, nullptr, &v_bytes, nullptr);
-    void* vb = workspace ? static_cast<char*>(workspace) + (v_bytes + 255) / 256 * 256 : nullptr;   // bf16 split of v
+    char* vb = workspace ? static_cast<char*>(workspace) + align_up(v_bytes, 256) : nullptr;
+    char* vb2 = vb ? vb + align_up((size_t)p->T * 2 * p->R * 2, 256) : nullptr;
     if (has_delta) {
-        lora_status st = lora_shrink(p, x, ldx, d_At_ptrs, v, hip_stream);
-        if (st != LORA_OK) return st;
-    } else {
-        lora_status st = ensure_uploaded(p, stream);
+        lora_status st = lora_shrink(p, x, ldx, d_At_ptrs, v, hip_stream);      // both batches in mixture mode
         if (st != LORA_OK) return st;
     }
+    lora_status st = ensure_uploaded(p, stream);
+    if (st != LORA_OK) return st;
     const lora_dev_tables d = tables_of(p);
+    lora_dev_tables d2{};
+    if (u) d2 = tables_of(u);
+    gemm_removal rm{u, u ? &d2 : nullptr, u ? removal_v(p, v) : nullptr, u ? vb2 : nullptr};
     hipError_t e;
     if (gemm_tiled_supported(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy) &&
         (!has_delta || (int32_t)p->order.size() == p->T))
-        e = launch_gemm_tiled(p->T, p->K, p->N, x, ldx, Wt, ldw, y, ldy, p, &d, v, vb, d_Bt_ptrs, stream);
+        e = launch_gemm_tiled(p->T, p->K, p->N, x, ldx, Wt, ldw, y, ldy, p, &d, v, vb, rm, d_Bt_ptrs, stream);
     else
-        e = launch_gemm_general(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy, p, &d, v, d_Bt_ptrs, stream);
+        e = launch_gemm_general(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy, p, &d, v, rm, d_Bt_ptrs, stream);
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
 }
 
@@ -392,6 +447,7 @@ extern "C" lora_status lora_delta_static(lora_plan* p, const void* x, int64_t ld
 {
     if (!p) return LORA_ERR_INVALID_ARG;
     if (!(beta == 0.f || beta == 1.f)) return LORA_ERR_INVALID_ARG;
+    if (p->unmerge) return LORA_ERR_UNSUPPORTED;               // mixture mode: two batches, use lora_delta
     if (p->perm.empty()) return LORA_OK;
     if (!x || !d_At_ptrs || !d_Bt_ptrs || !y) return LORA_ERR_INVALID_ARG;
     if (ldx < p->K || ldy < p->N) return LORA_ERR_INVALID_ARG;

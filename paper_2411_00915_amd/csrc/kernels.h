@@ -20,6 +20,7 @@ static inline lora_vspec lora_vspec_of(const lora_plan* p)
 struct lora_dev_tables {
     const int32_t* perm;
     const int32_t* token_adapter;
+    const int32_t* row_key;        // fused GEMM: adapter of the token (bits 0..22 all ones: none) | removal bit
     const int32_t* rank;
     const float* scale;
     const lora_tile* shrink_tiles;
@@ -60,17 +61,26 @@ hipError_t launch_delta_fused_small(const lora_plan* p, const lora_dev_tables& d
                                     const void* const* At, const void* const* Bt, float* v, void* y, int64_t ldy,
                                     float beta, hipStream_t stream);
 
+// mixture mode: the second batch (every token that is not the merged adapter's, with that adapter and the negated
+// scale) whose delta the fused GEMM folds in besides the tokens' own; plan == nullptr: none
+struct gemm_removal {
+    const lora_plan* plan = nullptr;
+    const lora_dev_tables* tables = nullptr;
+    const float* v = nullptr;      // its shrink's output
+    void* vb = nullptr;            // room for the bf16 split of it, T * 2 * plan->R elements
+};
+
 // base GEMM  y = x Wt^T  (+ optional adapter delta in the epilogue when p != nullptr)
 hipError_t launch_gemm_general(int32_t T, int32_t K, int32_t N, int32_t dtype, const void* x, int64_t ldx,
                                const void* Wt, int64_t ldw, void* y, int64_t ldy,
-                               const lora_plan* p, const lora_dev_tables* d, const float* v,
+                               const lora_plan* p, const lora_dev_tables* d, const float* v, const gemm_removal& rm,
                                const void* const* Bt, hipStream_t stream);
 bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const void* x, int64_t ldx,
                           const void* Wt, int64_t ldw, const void* y, int64_t ldy);
 hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx,
                              const void* Wt, int64_t ldw, void* y, int64_t ldy,
                              const lora_plan* p, const lora_dev_tables* d, const float* v, void* vb,
-                             const void* const* Bt, hipStream_t stream);
+                             const gemm_removal& rm, const void* const* Bt, hipStream_t stream);
 
 // mode switch: Wt_l += s Bt_l At_l for L layers in one launch (device arrays of L pointers each)
 hipError_t launch_merge_tiled(int32_t L, int32_t N, int32_t K, int32_t r, float s, void* const* Wt, int64_t ldw,

@@ -74,15 +74,32 @@ constexpr int META_MAX = 256;      // adapter stages of a tile whose metadata is
 
 struct gemm_delta_args {
     const int32_t* order;          // [T] tokens sorted by adapter, then tokens without adapter; nullptr = identity
-    const int32_t* token_adapter;  // [T]
+    const int32_t* row_key;        // [T] the token's adapter (bits 0..22; all ones: none) | removal bit
     const int32_t* rank;
     const int32_t* extra_ptr;      // [token tiles + 1]
-    const int32_t* extra;          // adapter | rank block << 24
+    const int32_t* extra;          // stage id (adapter, | removal bit) | rank block << 24
     const bf16_t* vb;              // [T][2][R]: v_hi, v_lo
     int R;
     const bf16_t* const* Bt_ptrs;
     const bf16_t* zeros;           // 16 zero bytes: the source of chunks that are masked out
+    const bf16_t* vb2;             // mixture mode: [T][2][R2] split of the removal's v (read by the marked stages)
+    int R2;
 };
+
+// Stage ids and row keys.  An ordinary stage (id = adapter) concerns the rows of that adapter.  A stage whose id
+// carries the removal bit (mixture mode: the merged adapter's update is taken off again) concerns every row whose key
+// carries it: the rows of all other adapters and of none.  Rows beyond T have the key "none" without the bit.
+constexpr int STAGE_REMOVAL = LORA_UNMERGE_BIT, KEY_NONE = LORA_UNMERGE_BIT - 1;
+__device__ __forceinline__ bool stage_hits(int row_key, int stage_id)
+{
+    return (stage_id & STAGE_REMOVAL) ? (row_key & STAGE_REMOVAL) != 0 : (row_key & KEY_NONE) == stage_id;
+}
+// columns [part * r + j, + 8) of the token's [v_hi | v_lo] that the stage reads
+__device__ __forceinline__ const bf16_t* stage_v(const gemm_delta_args& da, int stage_id, int token, int part, int j)
+{
+    return (stage_id & STAGE_REMOVAL) ? da.vb2 + ((int64_t)token * 2 + part) * da.R2 + j
+                                      : da.vb + ((int64_t)token * 2 + part) * da.R + j;
+}
 
 // Workgroups are dealt round-robin to the 8 XCDs; every XCD gets a contiguous run of tiles (so its L2 sees
 // neighbouring tiles).  Inside a run the tiles go in groups of GN feature tiles, token tile fastest over GN
@@ -143,7 +160,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
         gx[i] = x + (int64_t)tok * ldx + c * 8;
         slot[i] = lds_slot(row, c);
         slot_w[i] = lds_slot_w(row, c);
-        if constexpr (DELTA) lds_rows[i * 256 + tid] = make_int2(tok, pos_ok ? da.token_adapter[tok] : -1);
+        if constexpr (DELTA) lds_rows[i * 256 + tid] = make_int2(tok, pos_ok ? da.row_key[tok] : KEY_NONE);
     }
 
     floatx16 acc[WB][WB];
@@ -167,7 +184,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
         stages += n_extra;
         for (int e = tid; e < n_extra && e < META_MAX; e += 256) {
             const int packed = da.extra[extra_base + e];
-            const int a_id = packed & 0xffffff;
+            const int a_id = packed & KEY_NONE;
             const uint64_t bt = reinterpret_cast<uint64_t>(da.Bt_ptrs[a_id]);
             lds_meta[e] = uint4{(uint32_t)packed, (uint32_t)da.rank[a_id], (uint32_t)bt, (uint32_t)(bt >> 32)};
         }
@@ -200,8 +217,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
                 Bt = reinterpret_cast<const bf16_t*>((uint64_t)m.z | ((uint64_t)m.w << 32));
             } else {
                 packed = da.extra[extra_base + e];
-                r = da.rank[packed & 0xffffff];
-                Bt = da.Bt_ptrs[packed & 0xffffff];
+                r = da.rank[packed & KEY_NONE];
+                Bt = da.Bt_ptrs[packed & KEY_NONE];
             }
             const int a_id = packed & 0xffffff;
             // column of the adapter's [v_hi | v_lo] concatenation; r % 8 == 0, so a chunk lies in one half
@@ -215,8 +232,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
                 if (nr >= N) nr = N - 1;
                 const int2 ta = lds_rows[i * 256 + tid];         // (token, its adapter)
                 rw[i] = in ? *reinterpret_cast<const uint4*>(Bt + (int64_t)nr * r + j) : uint4{0, 0, 0, 0};
-                rx[i] = (in && ta.y == a_id)
-                            ? *reinterpret_cast<const uint4*>(da.vb + ((int64_t)ta.x * 2 + part) * da.R + j)
+                rx[i] = (in && stage_hits(ta.y, a_id))
+                            ? *reinterpret_cast<const uint4*>(stage_v(da, a_id, ta.x, part, j))
                             : uint4{0, 0, 0, 0};
             }
         }
@@ -256,7 +273,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
             for (int b = 0; b < WB; ++b) {
                 // row wt + 32 b + l32 of the tile is staged by thread (row * 8) & 255 as its chunk slot (row * 8) >> 8
                 const int q = (wt + b * 32 + (lane & 31)) * 8;
-                skip[b] = __ballot(lds_rows[(q >> 8) * 256 + (q & 255)].y == a_id) == 0;
+                skip[b] = __ballot(stage_hits(lds_rows[(q >> 8) * 256 + (q & 255)].y, a_id)) == 0;
             }
         }
     };
@@ -305,7 +322,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
                     if (nr >= N) nr = N - 1;
                     const int2 ta = lds_rows[i * 256 + tid];
                     pw[i] = in ? Bt + (int64_t)nr * r + j : da.zeros;
-                    px[i] = (in && ta.y == a_id) ? da.vb + ((int64_t)ta.x * 2 + part) * da.R + j : da.zeros;
+                    px[i] = (in && stage_hits(ta.y, a_id)) ? stage_v(da, a_id, ta.x, part, j) : da.zeros;
                 }
             }
         };
@@ -502,7 +519,7 @@ __global__ __launch_bounds__(512) void gemm_ring_kernel(
         const int tok = DELTA ? da.order[pos] : pos;
         pw[j] = Wt + (int64_t)nr * ldw + cw[j] * 8;
         px[j] = x + (int64_t)tok * ldx + cx * 8;
-        if constexpr (DELTA) lds_rows[j * 512 + tid] = make_int2(tok, pos_ok ? da.token_adapter[tok] : -1);
+        if constexpr (DELTA) lds_rows[j * 512 + tid] = make_int2(tok, pos_ok ? da.row_key[tok] : KEY_NONE);
     }
 
     const int stages_k = K / RK;                                     // K % 32 == 0, stages_k >= 4 (checked by the launcher)
@@ -513,7 +530,7 @@ __global__ __launch_bounds__(512) void gemm_ring_kernel(
         stages += n_extra;
         for (int e = tid; e < n_extra; e += 512) {
             const int packed = da.extra[extra_base + e];
-            const int a_id = packed & 0xffffff;
+            const int a_id = packed & KEY_NONE;
             const uint64_t bt = reinterpret_cast<uint64_t>(da.Bt_ptrs[a_id]);
             lds_meta[e] = uint4{(uint32_t)packed, (uint32_t)da.rank[a_id], (uint32_t)bt, (uint32_t)(bt >> 32)};
         }
@@ -549,7 +566,7 @@ __global__ __launch_bounds__(512) void gemm_ring_kernel(
                 const int jw = colw >= r ? colw - r : colw;          // r % 8 == 0: a chunk lies in one half
                 const int2 ta = lds_rows[j * 512 + tid];
                 pw[j] = colw < 2 * r ? Bt + (int64_t)nr * r + jw : da.zeros;
-                px[j] = (inx && ta.y == a_id) ? da.vb + ((int64_t)ta.x * 2 + partx) * da.R + (colx - partx * r) : da.zeros;
+                px[j] = (inx && stage_hits(ta.y, a_id)) ? stage_v(da, a_id, ta.x, partx, colx - partx * r) : da.zeros;
             }
         }
     };
@@ -745,27 +762,38 @@ bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const 
     return tiles < (1ll << 31);
 }
 
-// p != nullptr: fold the adapter delta in; v holds the shrink's output and vb (room for T*2*R bf16) receives its split
+// p != nullptr: fold the adapter delta in; v holds the shrink's output and vb (room for T*2*R bf16) receives its split;
+// rm: likewise for the removal of the merged adapter (mixture mode)
 hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx,
                              const void* Wt, int64_t ldw, void* y, int64_t ldy,
                              const lora_plan* p, const lora_dev_tables* d, const float* v, void* vb,
-                             const void* const* Bt, hipStream_t stream)
+                             const gemm_removal& rm, const void* const* Bt, hipStream_t stream)
 {
     // 256 x 256 tiles once there are enough of them to fill the 256 compute units
     const bool big = (int64_t)((N + 255) / 256) * ((T + 255) / 256) >= 192;
-    const bool delta = p && !p->perm.empty();
+    const bool delta = p && (!p->perm.empty() || rm.plan);
     // the ring kernel: whole 32-k stages, at least four of them, every tile's adapter stages fit its LDS list
     const bool ring_ok = big && K % RK == 0 && K / RK >= 4 && (!delta || p->max_extra256h <= META_MAX);
     gemm_delta_args da{};
     if (delta) {
-        LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)p->perm.size()), dim3(64), 0, stream,
-                    d->perm, d->token_adapter, d->rank, v, lora_vspec_of(p), (bf16_t*)vb);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        da = gemm_delta_args{d->order, d->token_adapter, d->rank,
+        if (!p->perm.empty()) {
+            LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)p->perm.size()), dim3(64), 0, stream,
+                        d->perm, d->token_adapter, d->rank, v, lora_vspec_of(p), (bf16_t*)vb);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        if (rm.plan) {
+            LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)rm.plan->perm.size()), dim3(64), 0, stream,
+                        rm.tables->perm, rm.tables->token_adapter, rm.tables->rank, rm.v, lora_vspec_of(rm.plan),
+                        (bf16_t*)rm.vb);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        da = gemm_delta_args{d->order, d->row_key, d->rank,
                              ring_ok ? d->extra_ptr256h : big ? d->extra_ptr256 : d->extra_ptr128,
                              ring_ok ? d->extra256h : big ? d->extra256 : d->extra128, (const bf16_t*)vb, p->R,
-                             (const bf16_t* const*)Bt, (const bf16_t*)d->zeros};
+                             (const bf16_t* const*)Bt, (const bf16_t*)d->zeros,
+                             (const bf16_t*)rm.vb, rm.plan ? rm.plan->R : 0};
     }
     if (ring_ok)
         return delta ? launch_ring<true>(T, K, N, x, ldx, Wt, ldw, y, ldy, da, stream)

@@ -105,9 +105,9 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(
     int T_, int K, int N, const T* __restrict__ x, int64_t ldx, const T* __restrict__ Wt, int64_t ldw,
     T* __restrict__ y, int64_t ldy,
     const int32_t* __restrict__ token_adapter, const int32_t* __restrict__ rank,
-    const float* __restrict__ v, lora_vspec vsp, const T* const* __restrict__ Bt)
+    const float* __restrict__ v, lora_vspec vsp, const T* const* __restrict__ Bt,
+    const int32_t* __restrict__ token_adapter2, const float* __restrict__ v2, lora_vspec vsp2)
 {
-    const int R = vsp.R;
     __shared__ float xs[16][17];
     __shared__ float ws[16][17];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -125,19 +125,24 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(
         __syncthreads();
     }
     if (t < T_ && n < N) {
-        if (token_adapter) {
-            const int a = token_adapter[t];
-            if (a >= 0) {
-                const int r = rank[a];
-                const T* Bn = Bt[a] + (int64_t)n * r;
-                float d = 0.f;
-                for (int j = 0; j < r; ++j) {
-                    float vj = v[(int64_t)t * R + j];
-                    for (int q = 1; q < vsp.P; ++q) vj += v[q * vsp.part + (int64_t)t * R + j];
-                    d = fmaf(vj, elem<T>::load(Bn + j), d);
-                }
-                acc += d;
+        // the token's own branch, then (mixture mode) the removal of the merged adapter: the same sum over the
+        // second batch's token -> adapter map and v
+        for (int pass = 0; pass < 2; ++pass) {
+            const int32_t* ta = pass ? token_adapter2 : token_adapter;
+            if (!ta) continue;
+            const int a = ta[t];
+            if (a < 0) continue;
+            const float* vv = pass ? v2 : v;
+            const lora_vspec sp = pass ? vsp2 : vsp;
+            const int r = rank[a];
+            const T* Bn = Bt[a] + (int64_t)n * r;
+            float d = 0.f;
+            for (int j = 0; j < r; ++j) {
+                float vj = vv[(int64_t)t * sp.R + j];
+                for (int q = 1; q < sp.P; ++q) vj += vv[q * sp.part + (int64_t)t * sp.R + j];
+                d = fmaf(vj, elem<T>::load(Bn + j), d);
             }
+            acc += d;
         }
         elem<T>::store(y + (int64_t)t * ldy + n, acc);
     }
@@ -145,7 +150,7 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(
 
 hipError_t launch_gemm_general(int32_t T, int32_t K, int32_t N, int32_t dtype, const void* x, int64_t ldx,
                                const void* Wt, int64_t ldw, void* y, int64_t ldy,
-                               const lora_plan* p, const lora_dev_tables* d, const float* v,
+                               const lora_plan* p, const lora_dev_tables* d, const float* v, const gemm_removal& rm,
                                const void* const* Bt, hipStream_t stream)
 {
     if (T == 0) return hipSuccess;
@@ -153,12 +158,14 @@ hipError_t launch_gemm_general(int32_t T, int32_t K, int32_t N, int32_t dtype, c
     const int32_t* ta = p ? d->token_adapter : nullptr;
     const int32_t* rk = p ? d->rank : nullptr;
     const lora_vspec R = p ? lora_vspec_of(p) : lora_vspec{0, 1, 0};
+    const int32_t* ta2 = rm.plan ? rm.tables->token_adapter : nullptr;
+    const lora_vspec R2 = rm.plan ? lora_vspec_of(rm.plan) : lora_vspec{0, 1, 0};
     if (dtype == LORA_F32)
         LORA_LAUNCH(LORA_K_GEMM_GENERAL, (gemm_general_kernel<float>), grid, dim3(256), 0, stream, T, K, N, (const float*)x, ldx, (const float*)Wt, ldw,
-            (float*)y, ldy, ta, rk, v, R, (const float* const*)Bt);
+            (float*)y, ldy, ta, rk, v, R, (const float* const*)Bt, ta2, rm.v, R2);
     else
         LORA_LAUNCH(LORA_K_GEMM_GENERAL, (gemm_general_kernel<bf16_t>), grid, dim3(256), 0, stream, T, K, N, (const bf16_t*)x, ldx, (const bf16_t*)Wt, ldw,
-            (bf16_t*)y, ldy, ta, rk, v, R, (const bf16_t* const*)Bt);
+            (bf16_t*)y, ldy, ta, rk, v, R, (const bf16_t* const*)Bt, ta2, rm.v, R2);
     return hipGetLastError();
 }
 

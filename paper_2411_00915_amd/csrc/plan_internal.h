@@ -68,6 +68,15 @@ struct lora_plan {
     int32_t max_extra256h = 0;
     std::vector<int32_t> shrink_rows, expand_rows;   // single-launch decode kernel: 16 tokens per tile, padded
     bool tiled_layout_ok = false;  // K and all active ranks multiples of 8
+    // fused GEMM: what a row is matched against an adapter stage by: its adapter in bits 0..22 (all ones: none),
+    // bit 23 set when the removal of the merged adapter applies to it
+    std::vector<int32_t> row_key;
+
+    // Mixture mode: adapter `merged` is folded into the base weight.  This plan then holds the tokens' own branches
+    // (the merged adapter's tokens count as tokens without adapter) and `unmerge` is a plan over the same tokens in
+    // which every token that is not the merged adapter's uses that adapter with the negated scale.
+    int32_t merged = -1;
+    lora_plan* unmerge = nullptr;  // owned
 
     // device mirror (one allocation), valid when d_buf != nullptr
     int device = -1;
@@ -76,6 +85,7 @@ struct lora_plan {
     void* h_stage = nullptr;       // pinned staging for the stream-ordered copy
     int32_t* d_perm = nullptr;
     int32_t* d_token_adapter = nullptr;
+    int32_t* d_row_key = nullptr;
     int32_t* d_rank = nullptr;
     float* d_scale = nullptr;
     lora_tile* d_shrink_tiles = nullptr;
@@ -96,4 +106,14 @@ struct lora_plan {
 // How a plan's device tables are released: set by the translation unit that owns them (abi.hip) when the library
 // is loaded; stays null in host-only builds of the planner, where no plan ever has device tables.
 extern void (*lora_plan_device_release)(lora_plan*);
+
+// stage ids and row keys of the fused GEMM: bit 23 marks the stages / the rows of the merged adapter's removal
+constexpr int32_t LORA_UNMERGE_BIT = 1 << 23;
+
+// bytes of v a plan's own tiles use, and where the removal's share starts (mixture mode)
+static inline size_t lora_own_v_bytes(const lora_plan* p)
+{
+    return (size_t)p->v_parts * (size_t)p->T * (size_t)p->R * sizeof(float);
+}
+static inline size_t lora_unmerge_v_offset(const lora_plan* p) { return (lora_own_v_bytes(p) + 255) / 256 * 256; }
 

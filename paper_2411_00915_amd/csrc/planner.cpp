@@ -132,6 +132,7 @@ static bool validate(const lora_batch_desc* d)
     if (d->dtype != LORA_F32 && d->dtype != LORA_BF16) return false;
     if (d->variant < LORA_VARIANT_AUTO || d->variant > LORA_VARIANT_TILED) return false;
     if (d->tuning_count < 0 || (d->tuning_count > 0 && !d->tuning)) return false;
+    if (d->merged_adapter_plus1 < 0 || d->merged_adapter_plus1 > d->num_adapters) return false;
     if (!d->seg_indptr) return false;                       // even S = 0 has the single entry [0]
     if (d->num_segments > 0 && !d->seg_adapter) return false;
     if (d->num_adapters > 0 && (!d->adapter_rank || !d->adapter_scale)) return false;
@@ -380,24 +381,39 @@ static void build_tiles(lora_plan* p)
 // adapters, and folds each adapter's delta in as extra k-stages (v_hi, v_lo against Bt_a).  The full
 // blocks of 256 sorted rows are then put heaviest first (most adapter stages): workgroups start in
 // index order, so the long tiles run early and the short ones fill the tail of the launch.
+// Mixture mode: the removal of the merged adapter concerns every token of `unmerge`'s single adapter group; a tile
+// that holds such a token gets the merged adapter's stages once more, marked, after its own.  Tokens without adapter
+// that need the removal sort before the merged adapter's tokens, so that tiles of the latter keep no stage at all.
 static void build_gemm_tables(lora_plan* p)
 {
+    const lora_plan* u = p->unmerge;
+    p->row_key.resize((size_t)p->T);
+    for (int32_t t = 0; t < p->T; ++t) {
+        const int32_t a = p->token_adapter[t];
+        p->row_key[t] = (a < 0 ? LORA_UNMERGE_BIT - 1 : a) | (u && u->token_adapter[t] >= 0 ? LORA_UNMERGE_BIT : 0);
+    }
     std::vector<int32_t> sorted = p->perm;
     sorted.reserve((size_t)p->T);
-    for (int32_t t = 0; t < p->T; ++t)
-        if (p->token_adapter[t] < 0) sorted.push_back(t);
+    for (int pass = 0; pass < 2; ++pass)
+        for (int32_t t = 0; t < p->T; ++t)
+            if (p->token_adapter[t] < 0 && ((p->row_key[t] & LORA_UNMERGE_BIT) != 0) == (pass == 0)) sorted.push_back(t);
 
     // adapter stages of the rows [p0, p1) of `rows`: one per `cols` columns of [v_hi | v_lo] (2 r columns) and
     // adapter; the rows of one adapter are adjacent
     auto stages_of = [&](const std::vector<int32_t>& rows, int32_t p0, int32_t p1, int32_t cols, std::vector<int32_t>* lst) {
         int32_t n = 0, last = -1;
+        bool removal = false;
         for (int32_t q = p0; q < p1; ++q) {
+            removal = removal || (p->row_key[rows[q]] & LORA_UNMERGE_BIT);
             const int32_t a = p->token_adapter[rows[q]];
             if (a < 0 || a == last) continue;
             last = a;
             for (int32_t jb = 0; jb * cols < 2 * p->rank[a]; ++jb, ++n)
                 if (lst) lst->push_back(a | (jb << 24));
         }
+        if (removal)
+            for (int32_t jb = 0; jb * cols < 2 * p->rank[p->merged]; ++jb, ++n)
+                if (lst) lst->push_back(p->merged | LORA_UNMERGE_BIT | (jb << 24));
         return n;
     };
 
@@ -430,13 +446,17 @@ static void build_gemm_tables(lora_plan* p)
     }
 }
 
-extern "C" lora_status lora_plan_create(const lora_batch_desc* d, lora_plan** out)
+// One plan over the descriptor's segments as they stand; `unmerge` (may be null) is the removal's plan of a batch
+// in mixture mode, which the new plan takes over.
+static lora_status create_plain(const lora_batch_desc* d, int32_t merged, lora_plan* unmerge, lora_plan** out)
 {
-    if (!d || !out) return LORA_ERR_INVALID_ARG;
-    *out = nullptr;
-    if (!validate(d)) return LORA_ERR_INVALID_ARG;
     lora_plan* p = new (std::nothrow) lora_plan();
-    if (!p) return LORA_ERR_NOMEM;
+    if (!p) {
+        lora_plan_destroy(unmerge);
+        return LORA_ERR_NOMEM;
+    }
+    p->merged = unmerge ? merged : -1;
+    p->unmerge = unmerge;
     try {
         p->T = d->num_tokens; p->S = d->num_segments; p->n_a = d->num_adapters;
         p->K = d->k; p->N = d->n; p->dtype = d->dtype; p->variant_req = d->variant;
@@ -491,13 +511,47 @@ extern "C" lora_status lora_plan_create(const lora_batch_desc* d, lora_plan** ou
         else
             p->family = (n_active >= p->tuning.tiled_min_tokens) ? LORA_VARIANT_TILED : LORA_VARIANT_GENERAL;
         if (p->family == LORA_VARIANT_TILED) build_tiles(p);
-        if (p->tiled_layout_ok && p->n_a < (1 << 24)) build_gemm_tables(p);
+        // (in mixture mode the removal's v must have the layout the GEMM's stages read, too)
+        if (p->tiled_layout_ok && p->n_a < LORA_UNMERGE_BIT && (!unmerge || unmerge->tiled_layout_ok)) build_gemm_tables(p);
     } catch (const std::bad_alloc&) {
-        delete p;
+        lora_plan_destroy(p);
         return LORA_ERR_NOMEM;
     }
     *out = p;
     return LORA_OK;
+}
+
+extern "C" lora_status lora_plan_create(const lora_batch_desc* d, lora_plan** out)
+{
+    if (!d || !out) return LORA_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!validate(d)) return LORA_ERR_INVALID_ARG;
+    const int32_t m = d->merged_adapter_plus1 - 1;
+    if (m < 0 || d->adapter_rank[m] == 0) return create_plain(d, -1, nullptr, out);
+
+    // Mixture mode (section 4.4.1) as two batches over the same tokens: the removal of the merged adapter
+    // (every segment that is not m's uses m, scale negated) and the tokens' own branches (m's segments use none).
+    lora_plan* removal = nullptr;
+    try {
+        std::vector<int32_t> seg((size_t)d->num_segments);
+        std::vector<float> scale(d->adapter_scale, d->adapter_scale + d->num_adapters);
+        scale[m] = -scale[m];
+        for (int32_t s = 0; s < d->num_segments; ++s) seg[s] = d->seg_adapter[s] == m ? -1 : m;
+        lora_batch_desc dr = *d;
+        dr.seg_adapter = seg.data();
+        dr.adapter_scale = scale.data();
+        dr.merged_adapter_plus1 = 0;
+        lora_status st = create_plain(&dr, -1, nullptr, &removal);
+        if (st != LORA_OK) return st;
+        for (int32_t s = 0; s < d->num_segments; ++s) seg[s] = d->seg_adapter[s] == m ? -1 : d->seg_adapter[s];
+        lora_batch_desc own = *d;
+        own.seg_adapter = seg.data();
+        own.merged_adapter_plus1 = 0;
+        return create_plain(&own, m, removal, out);
+    } catch (const std::bad_alloc&) {
+        lora_plan_destroy(removal);
+        return LORA_ERR_NOMEM;
+    }
 }
 
 void (*lora_plan_device_release)(lora_plan*) = nullptr;
@@ -506,6 +560,7 @@ extern "C" void lora_plan_destroy(lora_plan* p)
 {
     if (!p) return;
     if (p->d_buf && lora_plan_device_release) lora_plan_device_release(p);
+    lora_plan_destroy(p->unmerge);
     delete p;
 }
 
@@ -513,12 +568,17 @@ extern "C" lora_status lora_plan_query(const lora_plan* p, int32_t* v_row_stride
                                        size_t* fused_workspace_bytes)
 {
     if (!p) return LORA_ERR_INVALID_ARG;
-    const size_t vb = (size_t)p->v_parts * (size_t)p->T * (size_t)p->R * sizeof(float);
+    size_t vb = lora_own_v_bytes(p);
+    size_t split = ((size_t)p->T * 2 * p->R * 2 + 255) / 256 * 256;
+    if (p->unmerge) {
+        vb = lora_unmerge_v_offset(p) + lora_own_v_bytes(p->unmerge);
+        split += ((size_t)p->T * 2 * p->unmerge->R * 2 + 255) / 256 * 256;
+    }
     if (v_row_stride) *v_row_stride = p->R;
     if (v_bytes) *v_bytes = vb;
-    // workspace of the fused call: v (all parts), then its bf16 split [T][2][R]
-    if (fused_workspace_bytes)
-        *fused_workspace_bytes = (vb + 255) / 256 * 256 + ((size_t)p->T * 2 * p->R * 2 + 255) / 256 * 256;
+    // workspace of the fused call: v (all parts; in mixture mode the removal's share behind it), then the bf16
+    // split [T][2][R] of each
+    if (fused_workspace_bytes) *fused_workspace_bytes = (vb + 255) / 256 * 256 + split;
     return LORA_OK;
 }
 
@@ -549,6 +609,17 @@ extern "C" lora_status lora_plan_export(const lora_plan* p, lora_plan_view* v)
     v->gemm_order = gemm_tables ? p->order.data() : nullptr;
     v->gemm_stage_offset = gemm_tables ? p->extra_ptr256h.data() : nullptr;
     v->gemm_stage = gemm_tables ? p->extra256h.data() : nullptr;
+    const lora_plan* u = p->unmerge;
+    v->merged_adapter = p->merged;
+    v->num_unmerge = u ? (int32_t)u->perm.size() : 0;
+    v->unmerge_v_row_stride = u ? u->R : 0;
+    v->unmerge_v_parts = u ? u->v_parts : 0;
+    v->unmerge_v_offset = u ? lora_unmerge_v_offset(p) : 0;
+    v->unmerge_perm = u ? u->perm.data() : nullptr;
+    v->unmerge_shrink_tiles = u ? u->shrink_tiles.data() : nullptr;
+    v->num_unmerge_shrink_tiles = u ? (int32_t)u->shrink_tiles.size() : 0;
+    v->unmerge_expand_tiles = u ? u->expand_tiles.data() : nullptr;
+    v->num_unmerge_expand_tiles = u ? (int32_t)u->expand_tiles.size() : 0;
     return LORA_OK;
 }
 

@@ -65,6 +65,6 @@ def to_device(w: Workload, device="cuda:0", with_w: bool = True) -> DeviceLayer:
     return DeviceLayer(abi_dtype(w), x, Wt, At_buf, Bt_buf, At_ptrs, Bt_ptrs, At_off, Bt_off)
 
 
-def make_plan(w: Workload, variant: int = B.LORA_VARIANT_AUTO, tuning=None) -> B.Plan:
+def make_plan(w: Workload, variant: int = B.LORA_VARIANT_AUTO, tuning=None, merged_adapter=None) -> B.Plan:
     return B.lora_plan(w.T, w.seg_indptr, w.seg_adapter, w.adapter_rank, w.adapter_scale,
-                       w.K, w.N, abi_dtype(w), variant, tuning)
+                       w.K, w.N, abi_dtype(w), variant, tuning, merged_adapter)

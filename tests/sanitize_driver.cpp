@@ -213,6 +213,65 @@ static void check_plan(const batch& b)
     lora_plan_destroy(p);
 }
 
+// Mixture mode: the plan of the tokens' own branches plus the removal of the merged adapter over all other tokens.
+static void check_mixture(const batch& b)
+{
+    if (b.rank.empty()) return;
+    const int32_t m = (int32_t)(rnd() % b.rank.size());
+    lora_batch_desc d = b.desc();
+    d.merged_adapter_plus1 = m + 1;
+    lora_plan* p = nullptr;
+    REQUIRE(lora_plan_create(&d, &p) == LORA_OK && p);
+    lora_plan_view v{};
+    REQUIRE(lora_plan_export(p, &v) == LORA_OK);
+    size_t v_bytes = 0, ws_bytes = 0;
+    int32_t R = 0;
+    REQUIRE(lora_plan_query(p, &R, &v_bytes, &ws_bytes) == LORA_OK);
+    if (b.rank[m] == 0) {
+        REQUIRE(v.merged_adapter == -1 && v.num_unmerge == 0);
+    } else {
+        REQUIRE(v.merged_adapter == m);
+        std::vector<int32_t> want;
+        for (size_t s = 0; s < b.seg_adapter.size(); ++s)
+            for (int32_t t = b.indptr[s]; t < b.indptr[s + 1]; ++t) {
+                if (b.seg_adapter[s] != m) want.push_back(t);
+                REQUIRE(v.token_adapter[t] != m);
+            }
+        REQUIRE(v.num_unmerge == (int32_t)want.size());
+        for (size_t i = 0; i < want.size(); ++i) REQUIRE(v.unmerge_perm[i] == want[i]);
+        REQUIRE(v.unmerge_v_offset % 256 == 0 && v.unmerge_v_offset >= (size_t)v.v_parts * (size_t)b.T * (size_t)R * 4);
+        REQUIRE(v_bytes == v.unmerge_v_offset + (size_t)v.unmerge_v_parts * (size_t)b.T * (size_t)v.unmerge_v_row_stride * 4);
+        REQUIRE(ws_bytes >= v_bytes);
+        for (int32_t i = 0; i < v.num_unmerge_shrink_tiles; ++i) {
+            const lora_tile& t = v.unmerge_shrink_tiles[i];
+            REQUIRE(t.adapter == m && t.row0 >= 0 && t.nrows > 0 && t.row0 + t.nrows <= v.num_unmerge);
+            REQUIRE(t.c0 >= 0 && t.cn > 0 && t.c0 + t.cn <= b.rank[m]);
+        }
+        for (int32_t i = 0; i < v.num_unmerge_expand_tiles; ++i) {
+            const lora_tile& t = v.unmerge_expand_tiles[i];
+            REQUIRE(t.adapter == m && t.row0 >= 0 && t.nrows > 0 && t.row0 + t.nrows <= v.num_unmerge);
+            REQUIRE(t.c0 >= 0 && t.cn > 0 && t.c0 + t.cn <= b.N);
+        }
+        // marked stages only in tiles that hold a token of the removal, and then all of the merged adapter's blocks
+        for (int32_t tile = 0; tile < v.num_gemm_tiles; ++tile) {
+            bool needs = false;
+            for (int32_t q = tile * 256; q < std::min((tile + 1) * 256, b.T); ++q) {
+                const int32_t t = v.gemm_order[q];
+                REQUIRE(t >= 0 && t < b.T);
+                needs = needs || std::binary_search(want.begin(), want.end(), t);
+            }
+            int32_t marked = 0;
+            for (int32_t i = v.gemm_stage_offset[tile]; i < v.gemm_stage_offset[tile + 1]; ++i)
+                if (v.gemm_stage[i] & (1 << 23)) {
+                    REQUIRE((v.gemm_stage[i] & 0x7fffff) == m && (v.gemm_stage[i] >> 24) == marked);
+                    ++marked;
+                }
+            REQUIRE(marked == (needs ? (2 * b.rank[m] + 31) / 32 : 0));
+        }
+    }
+    lora_plan_destroy(p);
+}
+
 static void check_errors()
 {
     batch b = random_batch(0);
@@ -312,6 +371,7 @@ int main()
     lora_tuning_get(tuning, 32);
     lora_tuning_set(tuning, 32);
     for (int i = 0; i < 220; ++i) check_plan(random_batch(i % 4));
+    for (int i = 0; i < 120; ++i) check_mixture(random_batch(i % 4));
     {   // no segments, no tokens
         batch b;
         b.indptr = {0}; b.rank = {8}; b.scale = {1.f}; b.K = 64; b.N = 64;

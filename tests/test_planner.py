@@ -71,6 +71,69 @@ def _check_tiles(w, v, tok, perm):
         assert t[2] <= 16 * tb and tb in (1, 2, 4, 8) and t[3] % 64 == 0
 
 
+def _check_mixture(w, m, variant=B.LORA_VARIANT_AUTO):
+    """Mixture mode: the plan must be the plan of the tokens' own branches (merged adapter's segments without
+    adapter) plus a second batch, over exactly the tokens that are not the merged adapter's, all on that adapter."""
+    p = device.make_plan(w, variant, merged_adapter=m)
+    v = B.lora_plan_export(p)
+    R, v_bytes, ws_bytes = B.lora_plan_query(p)
+    p.destroy()
+    if m < 0 or m >= w.num_adapters or w.adapter_rank[m] == 0:
+        assert v["merged_adapter"] == -1 and v["num_unmerge"] == 0 and v["unmerge_v_offset"] == 0
+        tok, perm = _check_tables(w, v)
+        _check_tiles(w, v, tok, perm)
+        return v
+    own_seg, removal = plan_ref.mixture_tables(w.T, w.seg_indptr, w.seg_adapter, w.adapter_rank, m)
+    own = wl.Workload(w.name, w.dtype, w.T, w.K, w.N, w.seg_indptr, own_seg, w.adapter_rank, w.adapter_scale, w.x, None)
+    tok, perm = _check_tables(own, v)
+    _check_tiles(own, v, tok, perm)
+    assert v["merged_adapter"] == m
+    assert np.array_equal(v["unmerge_perm"], np.nonzero(removal)[0])
+    # the removal's tiles: every (token, rank index of m) and every (token, feature) exactly once
+    rem_tok = np.where(removal, m, -1)
+    rperm = v["unmerge_perm"]
+    P2 = v["unmerge_v_parts"]
+    if len(rperm) and v["unmerge_shrink_tiles"].shape[0]:
+        for part in range(P2):
+            st_ = [(t[0], t[1], t[2], t[3], t[4]) for t in v["unmerge_shrink_tiles"] if (t[5] >> 8) & 15 == part]
+            plan_ref.check_cover(st_, rem_tok, rperm, int(w.adapter_rank[m]), adapter_rank=w.adapter_rank, rank_axis=True)
+        plan_ref.check_cover([(t[0], t[1], t[2], t[3], t[4]) for t in v["unmerge_expand_tiles"]], rem_tok, rperm, w.N)
+    # v: own parts, then (256-byte aligned) the removal's
+    own_bytes = v["v_parts"] * w.T * R * 4
+    assert v["unmerge_v_offset"] == (own_bytes + 255) // 256 * 256
+    assert v_bytes == v["unmerge_v_offset"] + P2 * w.T * v["unmerge_v_row_stride"] * 4
+    assert ws_bytes >= v_bytes + 2 * w.T * (R + v["unmerge_v_row_stride"]) * 2 and ws_bytes % 256 == 0
+    if v["gemm_order"].shape[0]:
+        plan_ref.check_gemm_tables(w.T, tok, w.adapter_rank, v["gemm_order"], v["gemm_stage_offset"], v["gemm_stage"],
+                                   merged=m, removal=removal)
+    return v
+
+
+@pytest.mark.parametrize("name,m", [("cfg2", 5), ("cfg3", 1), ("cfg4", 0), ("cfg4", 77), ("cfg1", 2)])
+def test_mixture_mode_tables(name, m):
+    w = wl.CONFIGS[name](with_w=False)
+    v = _check_mixture(w, m)
+    assert v["num_unmerge"] == w.T - int(np.sum(plan_ref.tables(w.T, w.seg_indptr, w.seg_adapter, w.adapter_rank)[0] == m))
+    if name == "cfg3":
+        # 3 of the 4 requests need the removal; the tiles of the merged adapter's 1024 tokens carry no stage at all
+        assert v["num_unmerge"] == 3072 and v["num_active"] == 3072
+        off = v["gemm_stage_offset"]
+        assert sum(1 for t in range(len(off) - 1) if off[t] == off[t + 1]) == 4
+
+
+@settings(max_examples=100, deadline=None)
+@given(st.lists(st.tuples(st.integers(0, 40), st.integers(-1, 5)), min_size=0, max_size=20),
+       st.lists(st.sampled_from([0, 8, 16, 32, 64, 128]), min_size=6, max_size=6),
+       st.integers(0, 5), st.sampled_from([64, 1000]))
+def test_random_mixture_tables(segs, ranks, m, N):
+    lengths = [s[0] for s in segs]
+    T = sum(lengths)
+    indptr = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32) if segs else np.zeros(1, np.int32)
+    w = wl.Workload("h", "bf16", T, 64, N, indptr, np.asarray([s[1] for s in segs], np.int32), np.asarray(ranks, np.int32),
+                    np.ones(6, np.float32), np.zeros((T, 64), np.float32), None)
+    _check_mixture(w, m, B.LORA_VARIANT_TILED)
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg4d", "cfg5"])
 def test_config_tables_bit_exact(name):
     w = wl.CONFIGS[name](with_w=False) if name != "cfg5" else wl.cfg5("attn", with_w=False)
@@ -155,6 +218,10 @@ def test_error_paths():
         st_, h = B.lora_plan_create_raw(d)
         assert st_ == B.LORA_ERR_INVALID_ARG and not h
     assert B.lora_plan_create_raw(None)[0] == B.LORA_ERR_INVALID_ARG
+    for bad_m in (3, -1):                            # two adapters: 0 (none), 1 and 2 are the valid values
+        d, keep = _desc()
+        d.merged_adapter_plus1 = bad_m
+        assert B.lora_plan_create_raw(d)[0] == B.LORA_ERR_INVALID_ARG
     d, keep = _desc()
     d.seg_indptr = None
     assert B.lora_plan_create_raw(d)[0] == B.LORA_ERR_INVALID_ARG

@@ -242,9 +242,12 @@ extern "C" lora_status lora_plan_upload(lora_plan* p, void* hip_stream)
 }
 
 // The three calls on one plan's own tiles; the entry points below add the second batch of a plan in mixture mode.
+// vb / split_done: see launch_shrink_tiled
 static lora_status shrink_own(lora_plan* p, const void* x, int64_t ldx,
-                              const void* const* d_At_ptrs, float* v, void* hip_stream)
+                              const void* const* d_At_ptrs, float* v, void* hip_stream, void* vb = nullptr,
+                              bool* split_done = nullptr)
 {
+    if (split_done) *split_done = false;
     if (p->perm.empty()) return LORA_OK;                       // no token has an adapter: nothing to do
     if (!x || !d_At_ptrs || !v) return LORA_ERR_INVALID_ARG;
     if (ldx < p->K) return LORA_ERR_INVALID_ARG;
@@ -255,7 +258,7 @@ static lora_status shrink_own(lora_plan* p, const void* x, int64_t ldx,
     const lora_dev_tables d = tables_of(p);
     hipError_t e;
     if (p->family == LORA_VARIANT_TILED && tiled_call_ok(x, ldx))
-        e = launch_shrink_tiled(p, d, x, ldx, d_At_ptrs, v, stream);
+        e = launch_shrink_tiled(p, d, x, ldx, d_At_ptrs, v, stream, vb, split_done);
     else if (p->family == LORA_VARIANT_TILED && p->variant_req == LORA_VARIANT_TILED)
         return LORA_ERR_UNSUPPORTED;                           // tiled kernels were demanded but x is not laid out for them
     else
@@ -356,7 +359,7 @@ extern "C" lora_status lora_base_gemm(int32_t T, int32_t K, int32_t N, int32_t d
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
     if (gemm_tiled_supported(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy))
-        e = launch_gemm_tiled(T, K, N, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, gemm_removal{}, nullptr, stream);
+        e = launch_gemm_tiled(T, K, N, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, nullptr, false, gemm_removal{}, nullptr, stream);
     else
         e = launch_gemm_general(T, K, N, dtype, x, ldx, Wt, ldw, y, ldy, nullptr, nullptr, nullptr, gemm_removal{}, nullptr, stream);
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
@@ -408,8 +411,10 @@ extern "C" lora_status lora_fused_forward(lora_plan* p, const void* x, int64_t l
     lora_plan_query(p, nullptr, &v_bytes, nullptr);
     char* vb = workspace ? static_cast<char*>(workspace) + align_up(v_bytes, 256) : nullptr;
     char* vb2 = vb ? vb + align_up((size_t)p->T * 2 * p->R * 2, 256) : nullptr;
+    bool split_done = false, split2_done = false;                // the streaming shrink writes the split of v itself
     if (has_delta) {
-        lora_status st = lora_shrink(p, x, ldx, d_At_ptrs, v, hip_stream);      // both batches in mixture mode
+        lora_status st = shrink_own(p, x, ldx, d_At_ptrs, v, hip_stream, vb, &split_done);
+        if (st == LORA_OK && u) st = shrink_own(p->unmerge, x, ldx, d_At_ptrs, removal_v(p, v), hip_stream, vb2, &split2_done);
         if (st != LORA_OK) return st;
     }
     lora_status st = ensure_uploaded(p, stream);
@@ -417,11 +422,11 @@ extern "C" lora_status lora_fused_forward(lora_plan* p, const void* x, int64_t l
     const lora_dev_tables d = tables_of(p);
     lora_dev_tables d2{};
     if (u) d2 = tables_of(u);
-    gemm_removal rm{u, u ? &d2 : nullptr, u ? removal_v(p, v) : nullptr, u ? vb2 : nullptr};
+    gemm_removal rm{u, u ? &d2 : nullptr, u ? removal_v(p, v) : nullptr, u ? vb2 : nullptr, split2_done};
     hipError_t e;
     if (gemm_tiled_supported(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy) &&
         (!has_delta || (int32_t)p->order.size() == p->T))
-        e = launch_gemm_tiled(p->T, p->K, p->N, x, ldx, Wt, ldw, y, ldy, p, &d, v, vb, rm, d_Bt_ptrs, stream);
+        e = launch_gemm_tiled(p->T, p->K, p->N, x, ldx, Wt, ldw, y, ldy, p, &d, v, vb, split_done, rm, d_Bt_ptrs, stream);
     else
         e = launch_gemm_general(p->T, p->K, p->N, p->dtype, x, ldx, Wt, ldw, y, ldy, p, &d, v, rm, d_Bt_ptrs, stream);
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;

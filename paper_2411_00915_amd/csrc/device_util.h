@@ -10,6 +10,10 @@ __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(
 // round to nearest, ties to even
 __device__ __forceinline__ bf16_t f32_to_bf16(float f)
 {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const __bf16 h = (__bf16)f;                       // the hardware conversion of gfx950 (v_cvt_pk_bf16_f32)
+    return __builtin_bit_cast(unsigned short, h);
+#endif
     uint32_t u = __float_as_uint(f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;   // NaN
     u += 0x7fffu + ((u >> 16) & 1u);

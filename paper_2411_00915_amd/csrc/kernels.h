@@ -45,14 +45,17 @@ hipError_t launch_expand_general(const lora_plan* p, const lora_dev_tables& d, c
                                  const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream);
 
 // tiled MFMA family (bf16; K, ranks, ldx, ldy multiples of 8; 16-byte aligned bases)
+// vb != nullptr: room for the split of v into two bf16 terms, [T][2][R]; *split_done tells whether the launch wrote it
 hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
-                               const void* const* At, float* v, hipStream_t stream);
+                               const void* const* At, float* v, hipStream_t stream, void* vb = nullptr,
+                               bool* split_done = nullptr);
 hipError_t launch_expand_tiled(const lora_plan* p, const lora_dev_tables& d, const float* v,
                                const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream);
 
 // streaming kernels for prefill-sized batches (plans with shrink_stream / expand_stream; called by the two above)
 hipError_t launch_shrink_stream(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
-                                const void* const* At, float* v, hipStream_t stream);
+                                const void* const* At, float* v, hipStream_t stream, void* vb = nullptr,
+                                bool* split_done = nullptr);
 hipError_t launch_expand_stream(const lora_plan* p, const lora_dev_tables& d, const float* v,
                                 const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream);
 
@@ -68,6 +71,7 @@ struct gemm_removal {
     const lora_dev_tables* tables = nullptr;
     const float* v = nullptr;      // its shrink's output
     void* vb = nullptr;            // room for the bf16 split of it, T * 2 * plan->R elements
+    bool split_done = false;       // the shrink has written the split already
 };
 
 // base GEMM  y = x Wt^T  (+ optional adapter delta in the epilogue when p != nullptr)
@@ -79,7 +83,7 @@ bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const 
                           const void* Wt, int64_t ldw, const void* y, int64_t ldy);
 hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx,
                              const void* Wt, int64_t ldw, void* y, int64_t ldy,
-                             const lora_plan* p, const lora_dev_tables* d, const float* v, void* vb,
+                             const lora_plan* p, const lora_dev_tables* d, const float* v, void* vb, bool split_done,
                              const gemm_removal& rm, const void* const* Bt, hipStream_t stream);
 
 // mode switch: Wt_l += s Bt_l At_l for L layers in one launch (device arrays of L pointers each)

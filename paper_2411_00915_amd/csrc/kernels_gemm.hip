@@ -56,6 +56,33 @@ constexpr int BK = 64;    // k per stage; a tile row is 128 bytes = 8 chunks of 
 __device__ __forceinline__ int lds_slot(int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); }
 __device__ __forceinline__ int lds_slot_w(int row, int chunk) { return row * 8 + (chunk ^ (((row >> 1) & 3) | ((row >> 2) & 4))); }
 
+// 16-byte loads through pointers that come out of a table or are computed from one: the address space is stated,
+// or they would be flat loads (which also count as LDS traffic, so that waits on them are coarse)
+__device__ __forceinline__ uint4 ldg16(const void* p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+    const u32x4 r = *(const __attribute__((address_space(1))) u32x4*)(uintptr_t)p;
+    return uint4{r[0], r[1], r[2], r[3]};
+#else       // the host pass only parses device functions
+    return *reinterpret_cast<const uint4*>(p);
+#endif
+}
+
+// the same from a wavefront-uniform base plus a 32-bit byte offset per lane (one address register per lane for any
+// number of loads that share the offset)
+__device__ __forceinline__ uint4 ldg16_off(const void* uniform_base, uint32_t byte_off)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+    const __attribute__((address_space(1))) char* b = (const __attribute__((address_space(1))) char*)(uintptr_t)uniform_base;
+    const u32x4 r = *(const __attribute__((address_space(1))) u32x4*)(b + byte_off);
+    return uint4{r[0], r[1], r[2], r[3]};
+#else
+    return *reinterpret_cast<const uint4*>(static_cast<const char*>(uniform_base) + byte_off);
+#endif
+}
+
 __device__ __forceinline__ void split_bf16(const float* f, op16& hi, op16& lo)
 {
     uint32_t h[8], l[8];
@@ -84,6 +111,7 @@ struct gemm_delta_args {
     const bf16_t* zeros;           // 16 zero bytes: the source of chunks that are masked out
     const bf16_t* vb2;             // mixture mode: [T][2][R2] split of the removal's v (read by the marked stages)
     int R2;
+    int merged;                    // mixture mode: the merged adapter, else -1
 };
 
 // Stage ids and row keys.  An ordinary stage (id = adapter) concerns the rows of that adapter.  A stage whose id
@@ -482,10 +510,15 @@ __global__ __launch_bounds__(512) void gemm_ring_kernel(
     // registers).  A wavefront cannot issue an MFMA while it issues a load (each load costs it about one
     // MFMA slot, also with all lanes masked off); with a second wavefront on the SIMD the matrix core takes
     // that one's MFMA meanwhile.
+    //
+    // DELTA: the rows of the tile are tokens in adapter-sorted order, and after the K loop every wavefront adds the
+    // adapter deltas of its own 64 tokens to its accumulators by itself: for each adapter among them (one or two,
+    // mostly) and each block of 32 ranks, Bt_a[its 128 features, 32 ranks] as the MFMA row operand straight from
+    // memory, and the tokens' v (its two bf16 terms) as the column operands, masked to the adapter's tokens.  No LDS, no workgroup barrier, no work for the rows of other wavefronts: a wavefront pays
+    // for the adapters of its own 64 tokens only, where a shared adapter stage would cost all eight of them a whole
+    // 256 x 256 x 32 step per adapter and block of ranks.
     constexpr int BM = 256, BT = 256, WA = 8, WX = 4;
     uint4* ring = gemm_lds;                                          // [RING][RING_STAGE]
-    uint4* lds_meta = gemm_lds + RING * RING_STAGE;                  // DELTA: [META_MAX] adapter stages of the tile
-    int2* lds_rows = reinterpret_cast<int2*>(lds_meta + META_MAX);   // DELTA: [2][512] (token, adapter) of staged rows
 
     int tile_n, tile_t;
     tile_of_workgroup(blockIdx.x, tiles_n, tiles_t, tile_n, tile_t);
@@ -519,23 +552,17 @@ __global__ __launch_bounds__(512) void gemm_ring_kernel(
         const int tok = DELTA ? da.order[pos] : pos;
         pw[j] = Wt + (int64_t)nr * ldw + cw[j] * 8;
         px[j] = x + (int64_t)tok * ldx + cx * 8;
-        if constexpr (DELTA) lds_rows[j * 512 + tid] = make_int2(tok, pos_ok ? da.row_key[tok] : KEY_NONE);
+    }
+    // DELTA: token and key of row wt + lane of the tile (this wavefront's 64 tokens, one per lane)
+    int my_tok = 0, my_key = KEY_NONE;
+    if constexpr (DELTA) {
+        const int pos = t0 + wt + lane;
+        my_tok = da.order[pos < T ? pos : T - 1];
+        my_key = pos < T ? da.row_key[my_tok] : KEY_NONE;
     }
 
     const int stages_k = K / RK;                                     // K % 32 == 0, stages_k >= 4 (checked by the launcher)
-    int n_extra = 0, stages = stages_k;
-    if constexpr (DELTA) {
-        const int extra_base = da.extra_ptr[tile_t];
-        n_extra = da.extra_ptr[tile_t + 1] - extra_base;             // <= META_MAX (checked by the launcher)
-        stages += n_extra;
-        for (int e = tid; e < n_extra; e += 512) {
-            const int packed = da.extra[extra_base + e];
-            const int a_id = packed & KEY_NONE;
-            const uint64_t bt = reinterpret_cast<uint64_t>(da.Bt_ptrs[a_id]);
-            lds_meta[e] = uint4{(uint32_t)packed, (uint32_t)da.rank[a_id], (uint32_t)bt, (uint32_t)(bt >> 32)};
-        }
-        __syncthreads();                                             // lds_meta / lds_rows are complete
-    }
+    const int stages = stages_k;
 
     floatx4 acc[WA][WX];
 #pragma unroll
@@ -543,31 +570,11 @@ __global__ __launch_bounds__(512) void gemm_ring_kernel(
 #pragma unroll
         for (int b = 0; b < WX; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // source pointers of the stage to fetch next: a K stage advances them by 32 elements, an adapter stage sets
-    // them afresh (W chunks to Bt_a[feature row, ranks], x chunks to the token's [v_hi | v_lo] columns, every
-    // chunk that is masked out to a block of zeros), so every stage issues the same four unconditional loads
+    // source pointers of the stage to fetch next
     auto advance = [&](int next) {
-        if (!DELTA || next < stages_k) {
+        if (next < stages) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) { pw[j] += RK; px[j] += RK; }
-        } else if (next < stages) {
-            const uint4 m = lds_meta[next - stages_k];
-            const int a_id = (int)m.x & 0xffffff, r = (int)m.y;
-            const bf16_t* Bt = reinterpret_cast<const bf16_t*>((uint64_t)m.z | ((uint64_t)m.w << 32));
-            const int col0 = ((int)m.x >> 24) * RK;
-            const int colx = col0 + cx * 8;
-            const bool inx = colx < 2 * r;
-            const int partx = colx >= r ? 1 : 0;
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                int nr = n0 + (wave * 2 + j) * 16 + (lane >> 2);
-                if (nr >= N) nr = N - 1;
-                const int colw = col0 + cw[j] * 8;
-                const int jw = colw >= r ? colw - r : colw;          // r % 8 == 0: a chunk lies in one half
-                const int2 ta = lds_rows[j * 512 + tid];
-                pw[j] = colw < 2 * r ? Bt + (int64_t)nr * r + jw : da.zeros;
-                px[j] = (inx && stage_hits(ta.y, a_id)) ? stage_v(da, a_id, ta.x, partx, colx - partx * r) : da.zeros;
-            }
         }
     };
     const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 2048), lds_x = lds_w + 16384;
@@ -644,7 +651,7 @@ __global__ __launch_bounds__(512) void gemm_ring_kernel(
         _Pragma("unroll") for (int j = 0; j < 2; ++j) { pw[j] += RK; px[j] += RK; }
         --s;
     }
-    // the stages around and inside the adapter part
+    // the stages whose fourth successor may lie beyond the end
     for (; s + 4 < stages; s += 2) {
         RING_HALF_STAGE(xbA, xbB, true, 6, false)
         advance(s + 4);
@@ -662,6 +669,58 @@ __global__ __launch_bounds__(512) void gemm_ring_kernel(
 #undef RING_HALF_STAGE
 #undef RING_MMA
 #undef RING_FENCE
+
+    // ---- adapter deltas of this wavefront's 64 tokens -----------------------
+    if constexpr (DELTA) {
+        // token of MFMA column l16 of token block b
+        int tokb[WX];
+#pragma unroll
+        for (int b = 0; b < WX; ++b) tokb[b] = __shfl(my_tok, 16 * b + l16);
+        // acc += Bt_a[features, ranks] x v[tokens in `members`, ranks]^T  (members: bit i = row wt + i of the tile)
+        auto apply = [&](int a, uint64_t members, const bf16_t* __restrict__ vb, int R) {
+            const int r = da.rank[a];
+            const char* Bt = reinterpret_cast<const char*>(da.Bt_ptrs[a]);
+            const int row = n0 + wn + frow;                          // feature of MFMA row l16 in block 0
+            for (int j0 = 0; j0 < r; j0 += 32) {
+                const int j = j0 + 8 * kg;                           // this lane's 8 ranks of the block
+                const bool in = j < r;                               // r % 8 == 0: all eight or none
+                const uint32_t lane_off = (uint32_t)(row * r + j) * 2u;
+                // all loads of the block go out before the first is waited for (no branch between them)
+                op16 wb[WA], vh[WX], vl[WX];
+#pragma unroll
+                for (int blk = 0; blk < WA; ++blk) {
+                    const int d = (blk >> 2) * 64 + (blk & 3) * 4;   // block blk holds the features row + d
+                    wb[blk].u = (in && row + d < N) ? ldg16_off(Bt + (int64_t)d * r * 2, lane_off) : uint4{0, 0, 0, 0};
+                }
+#pragma unroll
+                for (int b = 0; b < WX; ++b) {
+                    const bool mine = in && ((members >> (16 * b + l16)) & 1ull);
+                    const uint32_t off = (uint32_t)(tokb[b] * 2 * R + j) * 2u;   // (the launcher keeps T R 4 below 2^32)
+                    vh[b].u = mine ? ldg16_off(vb, off) : uint4{0, 0, 0, 0};
+                    vl[b].u = mine ? ldg16_off(vb, off + (uint32_t)R * 2u) : uint4{0, 0, 0, 0};
+                }
+#pragma unroll
+                for (int b = 0; b < WX; ++b) {
+                    if (((members >> (16 * b)) & 0xffffull) == 0) continue;      // wavefront-uniform
+#pragma unroll
+                    for (int blk = 0; blk < WA; ++blk) {
+                        acc[blk][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[blk].v, vh[b].v, acc[blk][b], 0, 0, 0);
+                        acc[blk][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[blk].v, vl[b].v, acc[blk][b], 0, 0, 0);
+                    }
+                }
+            }
+        };
+        const int own = my_key & KEY_NONE;
+        uint64_t todo = __ballot(own != KEY_NONE);
+        while (todo) {                                               // the distinct adapters among the 64 tokens
+            const int a = __builtin_amdgcn_readlane(own, __ffsll((unsigned long long)todo) - 1);
+            const uint64_t members = __ballot(own == a);
+            todo &= ~members;
+            apply(a, members, da.vb, da.R);
+        }
+        const uint64_t removal = __ballot((my_key & STAGE_REMOVAL) != 0);
+        if (removal) apply(da.merged, removal, da.vb2, da.R2);     // mixture mode: the merged adapter, negated, for all of them
+    }
 
     // ---- epilogue: one rounding, store (rows go back to their tokens) ------
 #pragma unroll
@@ -734,8 +793,7 @@ hipError_t launch_ring(int32_t T, int32_t K, int32_t N, const void* x, int64_t l
                        void* y, int64_t ldy, const gemm_delta_args& da, hipStream_t stream)
 {
     const int tiles_n = (N + 255) / 256, tiles_t = (T + 255) / 256;
-    const size_t lds_bytes = (size_t)RING * RING_STAGE * sizeof(uint4) +
-                             (DELTA ? META_MAX * sizeof(uint4) + (size_t)2 * 512 * sizeof(int2) : 0);
+    const size_t lds_bytes = (size_t)RING * RING_STAGE * sizeof(uint4);
     static std::atomic<bool> attr_set{false};                 // dynamic LDS above 64 KB has to be allowed once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_ring_kernel<DELTA>),
@@ -762,27 +820,31 @@ bool gemm_tiled_supported(int32_t T, int32_t K, int32_t N, int32_t dtype, const 
     return tiles < (1ll << 31);
 }
 
-// p != nullptr: fold the adapter delta in; v holds the shrink's output and vb (room for T*2*R bf16) receives its split;
+// p != nullptr: fold the adapter delta in; v holds the shrink's output and vb (room for T*2*R bf16) receives its split
+// (split_done: the shrink has written it already);
 // rm: likewise for the removal of the merged adapter (mixture mode)
 hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int64_t ldx,
                              const void* Wt, int64_t ldw, void* y, int64_t ldy,
-                             const lora_plan* p, const lora_dev_tables* d, const float* v, void* vb,
+                             const lora_plan* p, const lora_dev_tables* d, const float* v, void* vb, bool split_done,
                              const gemm_removal& rm, const void* const* Bt, hipStream_t stream)
 {
     // 256 x 256 tiles once there are enough of them to fill the 256 compute units
     const bool big = (int64_t)((N + 255) / 256) * ((T + 255) / 256) >= 192;
     const bool delta = p && (!p->perm.empty() || rm.plan);
-    // the ring kernel: whole 32-k stages, at least four of them, every tile's adapter stages fit its LDS list
-    const bool ring_ok = big && K % RK == 0 && K / RK >= 4 && (!delta || p->max_extra256h <= META_MAX);
+    // the ring kernel: whole 32-k stages, at least four of them
+    // (the ring kernel's delta part addresses the split of v by 32-bit byte offsets)
+    const bool ring_ok = big && K % RK == 0 && K / RK >= 4 &&
+                         (!delta || ((int64_t)T * p->R * 4 < (1ll << 32) && (!rm.plan || (int64_t)T * rm.plan->R * 4 < (1ll << 32))));
     gemm_delta_args da{};
     if (delta) {
-        if (!p->perm.empty()) {
+        // the bf16 split of v, unless the shrink has written it already
+        if (!split_done && !p->perm.empty()) {
             LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)p->perm.size()), dim3(64), 0, stream,
                         d->perm, d->token_adapter, d->rank, v, lora_vspec_of(p), (bf16_t*)vb);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
-        if (rm.plan) {
+        if (!rm.split_done && rm.plan) {
             LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)rm.plan->perm.size()), dim3(64), 0, stream,
                         rm.tables->perm, rm.tables->token_adapter, rm.tables->rank, rm.v, lora_vspec_of(rm.plan),
                         (bf16_t*)rm.vb);
@@ -790,10 +852,10 @@ hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int
             if (e != hipSuccess) return e;
         }
         da = gemm_delta_args{d->order, d->row_key, d->rank,
-                             ring_ok ? d->extra_ptr256h : big ? d->extra_ptr256 : d->extra_ptr128,
-                             ring_ok ? d->extra256h : big ? d->extra256 : d->extra128, (const bf16_t*)vb, p->R,
+                             big ? d->extra_ptr256 : d->extra_ptr128,
+                             big ? d->extra256 : d->extra128, (const bf16_t*)vb, p->R,
                              (const bf16_t* const*)Bt, (const bf16_t*)d->zeros,
-                             (const bf16_t*)rm.vb, rm.plan ? rm.plan->R : 0};
+                             (const bf16_t*)rm.vb, rm.plan ? rm.plan->R : 0, rm.plan ? p->merged : -1};
     }
     if (ring_ok)
         return delta ? launch_ring<true>(T, K, N, x, ldx, Wt, ldw, y, ldy, da, stream)

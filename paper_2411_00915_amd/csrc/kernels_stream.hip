@@ -24,7 +24,7 @@ template <int JB, int KW>
 __device__ __forceinline__ void shrink_stream_tile(
     const lora_tile tile, const int32_t* __restrict__ perm,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
-    float* __restrict__ v, lora_vspec vsp, const bf16_t* __restrict__ zeros, uint4* lds)
+    float* __restrict__ v, lora_vspec vsp, const bf16_t* __restrict__ zeros, uint4* lds, bf16_t* __restrict__ vb)
 {
     constexpr int NB = 8 / KW;                    // token blocks of the tile
     constexpr int UW = 4 / KW;                    // k-steps per stage and wavefront
@@ -172,11 +172,26 @@ __device__ __forceinline__ void shrink_stream_tile(
     }
     if (!row_ok) return;
     float* dst = v + kpart * vsp.part + (int64_t)tok * vsp.R + tile.c0 + 4 * g;
+    // vb (only when v has a single K part): the same values as two bf16 terms, rows [tok][0][R] and [tok][1][R],
+    // what the fused forward's GEMM takes as operands
+    bf16_t* dst_hi = vb ? vb + (int64_t)tok * 2 * vsp.R + tile.c0 + 4 * g : nullptr;
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb)
-        if (jb * 16 + 4 * g < tile.cn)
-            *reinterpret_cast<float4*>(dst + jb * 16) =
-                make_float4(s_a * acc[jb][0], s_a * acc[jb][1], s_a * acc[jb][2], s_a * acc[jb][3]);
+        if (jb * 16 + 4 * g < tile.cn) {
+            const float f[4] = {s_a * acc[jb][0], s_a * acc[jb][1], s_a * acc[jb][2], s_a * acc[jb][3]};
+            *reinterpret_cast<float4*>(dst + jb * 16) = make_float4(f[0], f[1], f[2], f[3]);
+            if (vb) {
+                uint32_t h[4], l[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bf16_t hb = f32_to_bf16(f[i]);
+                    h[i] = hb;
+                    l[i] = f32_to_bf16(f[i] - bf16_to_f32(hb));
+                }
+                *reinterpret_cast<uint2*>(dst_hi + jb * 16) = uint2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+                *reinterpret_cast<uint2*>(dst_hi + vsp.R + jb * 16) = uint2{l[0] | (l[1] << 16), l[2] | (l[3] << 16)};
+            }
+        }
 }
 
 extern __shared__ uint4 shrink_stream_lds[];
@@ -187,13 +202,13 @@ template <int JBMAX>
 __global__ __launch_bounds__(512) void shrink_stream_kernel(
     const lora_tile* __restrict__ tiles, const int32_t* __restrict__ perm,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* const* __restrict__ At_ptrs, int K,
-    float* __restrict__ v, lora_vspec R, const bf16_t* __restrict__ zeros)
+    float* __restrict__ v, lora_vspec R, const bf16_t* __restrict__ zeros, bf16_t* __restrict__ vb)
 {
     const lora_tile tile = tiles[blockIdx.x];
     const bf16_t* At = At_ptrs[tile.adapter];
     const int nb = tile.shape & 15, jb = (tile.shape >> 4) & 15;
 #define STREAM_CASE(JB_, KW_) \
-    if (JB_ <= JBMAX && jb == JB_ && nb == 8 / KW_) { shrink_stream_tile<JB_, KW_>(tile, perm, x, ldx, At, K, v, R, zeros, shrink_stream_lds); return; }
+    if (JB_ <= JBMAX && jb == JB_ && nb == 8 / KW_) { shrink_stream_tile<JB_, KW_>(tile, perm, x, ldx, At, K, v, R, zeros, shrink_stream_lds, vb); return; }
     STREAM_CASE(4, 1) STREAM_CASE(4, 2) STREAM_CASE(4, 4)
     STREAM_CASE(2, 1) STREAM_CASE(2, 2) STREAM_CASE(2, 4)
     STREAM_CASE(1, 1) STREAM_CASE(1, 2) STREAM_CASE(1, 4)
@@ -202,16 +217,18 @@ __global__ __launch_bounds__(512) void shrink_stream_kernel(
 }
 
 hipError_t launch_shrink_stream(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
-                                const void* const* At, float* v, hipStream_t stream)
+                                const void* const* At, float* v, hipStream_t stream, void* vb, bool* split_done)
 {
     const int n_tiles = (int)p->shrink_tiles.size();
+    if (p->v_parts != 1) vb = nullptr;            // partial sums: the split is of their sum, a pass of its own
+    if (split_done) *split_done = vb != nullptr;
     // two slabs of 16 JB rows x 256 bytes (the final cross-wavefront sum needs the same 8 JB KB), and a
     // 4 KB patch per wavefront
     const size_t stream_lds = (size_t)p->shrink_max_blocks * 8192 + 32768;
 #define STREAM_LAUNCH(JBMAX_)                                                                                          \
     LORA_LAUNCH(LORA_K_SHRINK_STREAM, shrink_stream_kernel<JBMAX_>, dim3(n_tiles), dim3(512), stream_lds, stream,      \
                 d.shrink_tiles, d.perm, (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, lora_vspec_of(p),    \
-                (const bf16_t*)d.zeros)
+                (const bf16_t*)d.zeros, (bf16_t*)vb)
     if (p->shrink_max_blocks <= 2) STREAM_LAUNCH(2);
     else if (p->shrink_max_blocks <= 4) STREAM_LAUNCH(4);
     else STREAM_LAUNCH(8);

@@ -235,13 +235,14 @@ __global__ __launch_bounds__(512) void shrink_tiled_kernel(
 }
 
 hipError_t launch_shrink_tiled(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
-                               const void* const* At, float* v, hipStream_t stream)
+                               const void* const* At, float* v, hipStream_t stream, void* vb, bool* split_done)
 {
+    if (split_done) *split_done = false;          // only the streaming kernel writes the split
     const int n_tiles = (int)p->shrink_tiles.size();
     if (n_tiles == 0) return hipSuccess;
     const int W = p->shrink_waves;
     const size_t lds_bytes = (size_t)W * p->shrink_max_blocks * 64 * sizeof(floatx4);   // <= 64 KB
-    if (p->shrink_stream) return launch_shrink_stream(p, d, x, ldx, At, v, stream);
+    if (p->shrink_stream) return launch_shrink_stream(p, d, x, ldx, At, v, stream, vb, split_done);
     if (p->shrink_small)
         LORA_LAUNCH(LORA_K_SHRINK_TILED, shrink_tiled_small_kernel, dim3(n_tiles), dim3(64 * W), lds_bytes, stream,
                     d.shrink_tiles, d.perm, d.scale, (const bf16_t*)x, ldx, (const bf16_t* const*)At, p->K, v, lora_vspec_of(p));

@@ -178,8 +178,9 @@ typedef struct {
     /* Tables of lora_fused_forward's GEMM (empty when the plan cannot use the MFMA kernels): the row order it walks
      * (tokens sorted by adapter, then tokens without adapter; whole blocks of 256 rows ordered by decreasing number
      * of adapter stages), and per tile of 256 rows of that order its adapter stages: one entry
-     * adapter | block << 24 per adapter present and per block of 32 columns of the adapter's [v_hi | v_lo]
-     * (2 r columns). */
+     * adapter | block << 24 per adapter present and per block of 64 columns of the adapter's [v_hi | v_lo]
+     * (2 r columns).  The register-staged GEMM kernels walk these lists; the 256 x 256 ring kernel uses the row
+     * order alone (each wavefront finds the adapters of its own 64 rows). */
     int32_t        num_gemm_rows;        /* T, or 0 */
     int32_t        num_gemm_tiles;       /* ceil(T / 256), or 0 */
     const int32_t* gemm_order;           /* [num_gemm_rows] */

@@ -84,7 +84,7 @@ def mixture_tables(T, seg_indptr, seg_adapter, adapter_rank, merged):
     return own.astype(np.int32), removal
 
 
-def check_gemm_tables(T, tok_adapter, adapter_rank, order, stage_offset, stages, rows_per_tile=256, stage_cols=32,
+def check_gemm_tables(T, tok_adapter, adapter_rank, order, stage_offset, stages, rows_per_tile=256, stage_cols=64,
                       merged=-1, removal=None):
     """Validity of the fused forward's tables (they are the planner's free choice; only this is fixed).
 

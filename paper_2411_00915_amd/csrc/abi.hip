@@ -63,7 +63,7 @@ bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p
 
 struct table_layout {
     size_t perm, token_adapter, row_key, rank, scale, shrink_tiles, expand_tiles, sync, sync_bytes, total;
-    size_t order, extra_ptr128, extra128, extra_ptr256, extra256, extra_ptr256h, extra256h, zeros, shrink_rows, expand_rows;
+    size_t order, extra_ptr128, extra128, extra_ptr256, extra256, zeros, shrink_rows, expand_rows;
 };
 
 table_layout layout_of(const lora_plan* p)
@@ -83,8 +83,6 @@ table_layout layout_of(const lora_plan* p)
     L.extra128 = take(p->extra128.size() * sizeof(int32_t));
     L.extra_ptr256 = take(p->extra_ptr256.size() * sizeof(int32_t));
     L.extra256 = take(p->extra256.size() * sizeof(int32_t));
-    L.extra_ptr256h = take(p->extra_ptr256h.size() * sizeof(int32_t));
-    L.extra256h = take(p->extra256h.size() * sizeof(int32_t));
     L.zeros = take(256);
     L.shrink_rows = take(p->shrink_rows.size() * sizeof(int32_t));
     L.expand_rows = take(p->expand_rows.size() * sizeof(int32_t));
@@ -148,8 +146,6 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     put(L.extra128, p->extra128.data(), p->extra128.size() * sizeof(int32_t));
     put(L.extra_ptr256, p->extra_ptr256.data(), p->extra_ptr256.size() * sizeof(int32_t));
     put(L.extra256, p->extra256.data(), p->extra256.size() * sizeof(int32_t));
-    put(L.extra_ptr256h, p->extra_ptr256h.data(), p->extra_ptr256h.size() * sizeof(int32_t));
-    put(L.extra256h, p->extra256h.data(), p->extra256h.size() * sizeof(int32_t));
     std::memset(h + L.zeros, 0, 256);
     put(L.shrink_rows, p->shrink_rows.data(), p->shrink_rows.size() * sizeof(int32_t));
     put(L.expand_rows, p->expand_rows.data(), p->expand_rows.size() * sizeof(int32_t));
@@ -179,8 +175,6 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
     p->d_extra128 = reinterpret_cast<int32_t*>(d + L.extra128);
     p->d_extra_ptr256 = reinterpret_cast<int32_t*>(d + L.extra_ptr256);
     p->d_extra256 = reinterpret_cast<int32_t*>(d + L.extra256);
-    p->d_extra_ptr256h = reinterpret_cast<int32_t*>(d + L.extra_ptr256h);
-    p->d_extra256h = reinterpret_cast<int32_t*>(d + L.extra256h);
     p->d_shrink_rows = reinterpret_cast<int32_t*>(d + L.shrink_rows);
     p->d_expand_rows = reinterpret_cast<int32_t*>(d + L.expand_rows);
     return LORA_OK;
@@ -189,7 +183,7 @@ lora_status ensure_uploaded(lora_plan* p, hipStream_t stream)
 lora_dev_tables tables_of(const lora_plan* p)
 {
     return lora_dev_tables{p->d_perm, p->d_token_adapter, p->d_row_key, p->d_rank, p->d_scale, p->d_shrink_tiles, p->d_expand_tiles,
-                           p->d_sync, p->d_order, p->d_extra_ptr128, p->d_extra128, p->d_extra_ptr256, p->d_extra256, p->d_extra_ptr256h, p->d_extra256h, p->d_zeros,
+                           p->d_sync, p->d_order, p->d_extra_ptr128, p->d_extra128, p->d_extra_ptr256, p->d_extra256, p->d_zeros,
                            p->d_shrink_rows, p->d_expand_rows};
 }
 

@@ -31,8 +31,6 @@ struct lora_dev_tables {
     const int32_t* extra128;
     const int32_t* extra_ptr256;
     const int32_t* extra256;
-    const int32_t* extra_ptr256h;  // the same per 32-column block (ring kernel)
-    const int32_t* extra256h;
     const void* zeros;             // 256 zero bytes
     const int32_t* shrink_rows;    // single-launch decode kernel: 16 tokens per shrink / expand tile, padded
     const int32_t* expand_rows;

@@ -62,10 +62,9 @@ struct lora_plan {
     std::vector<lora_tile> shrink_tiles, expand_tiles;
     // fused GEMM: row order (tokens sorted by adapter, then tokens without adapter) and, per token tile of 128
     // or 256 rows of that order, the adapter stages present: packed adapter | (64-column block of the
-    // adapter's [v_hi | v_lo] concatenation) << 24; the "h" lists of the 256-row tiles count blocks of 32 columns
-    // (the ring kernel's stages), max_extra256h = the longest of them
-    std::vector<int32_t> order, extra_ptr128, extra128, extra_ptr256, extra256, extra_ptr256h, extra256h;
-    int32_t max_extra256h = 0;
+    // adapter's [v_hi | v_lo] concatenation) << 24.  (The 256 x 256 ring kernel uses the row order only: its
+    // wavefronts find the adapters of their own 64 rows themselves.)
+    std::vector<int32_t> order, extra_ptr128, extra128, extra_ptr256, extra256;
     std::vector<int32_t> shrink_rows, expand_rows;   // single-launch decode kernel: 16 tokens per tile, padded
     bool tiled_layout_ok = false;  // K and all active ranks multiples of 8
     // fused GEMM: what a row is matched against an adapter stage by: its adapter in bits 0..22 (all ones: none),
@@ -95,8 +94,6 @@ struct lora_plan {
     int32_t* d_extra128 = nullptr;
     int32_t* d_extra_ptr256 = nullptr;
     int32_t* d_extra256 = nullptr;
-    int32_t* d_extra_ptr256h = nullptr;
-    int32_t* d_extra256h = nullptr;
     int32_t* d_shrink_rows = nullptr;
     int32_t* d_expand_rows = nullptr;
     void* d_zeros = nullptr;          // 256 zero bytes (source of masked chunks in the fused GEMM)

@@ -10,6 +10,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <queue>
 #include <vector>
 
 #include "plan_internal.h"
@@ -357,9 +358,51 @@ static void build_tiles(lora_plan* p)
     std::stable_sort(p->shrink_tiles.begin(), p->shrink_tiles.end(),
                      [&](const lora_tile& x, const lora_tile& y) { return weight(x) > weight(y); });
     // (the streaming expand's tiles differ in size by up to 8x: the same for them)
-    if (p->expand_stream)
+    if (p->expand_stream) {
         std::stable_sort(p->expand_tiles.begin(), p->expand_tiles.end(),
                          [&](const lora_tile& x, const lora_tile& y) { return weight(x) > weight(y); });
+        // Workgroups start in index order, one per compute unit at a time.  With equal tiles a launch of 3.3
+        // rounds of them takes 4: so towards the end of the list the tiles shrink (guided self-scheduling): a
+        // tile heavier than its share of what is left -- the remaining work over the number of compute units --
+        // is cut along the features into 2 or 4, as long as a piece keeps at least 4 stages (the start-up of a
+        // tile has to pay off).
+        constexpr int64_t kComputeUnits = 256;
+        int64_t remaining = 0;
+        for (const lora_tile& t : p->expand_tiles) remaining += weight(t);
+        std::vector<lora_tile> cut;
+        cut.reserve(p->expand_tiles.size() + 4 * (size_t)kComputeUnits);
+        for (const lora_tile& t : p->expand_tiles) {
+            const int64_t w = weight(t);
+            const int32_t stage = 64 * lora_shape_jb(t.shape);           // features per stage (64 FW)
+            const int32_t stages = (t.cn + stage - 1) / stage;
+            int32_t pieces = 1;
+            while (pieces < 4 && w / pieces > std::max<int64_t>(remaining / kComputeUnits, 1) && stages / (pieces * 2) >= 4)
+                pieces *= 2;
+            const int32_t per = (stages + pieces - 1) / pieces * stage;
+            for (int32_t c = 0; c < t.cn; c += per) {
+                lora_tile q = t;
+                q.c0 = t.c0 + c;
+                q.cn = std::min(per, t.cn - c);
+                cut.push_back(q);
+            }
+            remaining -= w;
+        }
+        // Taken only if it pays: finish time of both lists when every compute unit takes the next tile as soon as
+        // it is free, a tile costing its weight plus a start-up of about two stages.
+        auto finish = [&](const std::vector<lora_tile>& tiles) {
+            std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> free_at;
+            for (int64_t c = 0; c < kComputeUnits; ++c) free_at.push(0);
+            int64_t last = 0;
+            for (const lora_tile& t : tiles) {
+                const int64_t at = free_at.top() + weight(t) + (int64_t)((t.nrows + 15) / 16) * 2 * 64 * lora_shape_jb(t.shape);
+                free_at.pop();
+                free_at.push(at);
+                last = std::max(last, at);
+            }
+            return last;
+        };
+        if (finish(cut) * 100 < finish(p->expand_tiles) * 97) p->expand_tiles.swap(cut);
+    }
     // Single-launch decode kernel: the 16 tokens of every tile, in tile order and padded with the tile's
     // first token, so that a workgroup can fetch them by its index alone, at the same time as its
     // tile descriptor instead of after it
@@ -430,17 +473,15 @@ static void build_gemm_tables(lora_plan* p)
                   p->order.begin() + (size_t)b * 256);
     std::copy(sorted.begin() + (size_t)full * 256, sorted.end(), p->order.begin() + (size_t)full * 256);
 
-    p->max_extra256h = 0;
-    for (int h = 0; h < 3; ++h) {
-        const int32_t rows = h == 0 ? 128 : 256, cols = h == 2 ? 32 : 64;
-        std::vector<int32_t>& ptr = h == 0 ? p->extra_ptr128 : h == 1 ? p->extra_ptr256 : p->extra_ptr256h;
-        std::vector<int32_t>& lst = h == 0 ? p->extra128 : h == 1 ? p->extra256 : p->extra256h;
+    for (int h = 0; h < 2; ++h) {
+        const int32_t rows = h == 0 ? 128 : 256, cols = 64;
+        std::vector<int32_t>& ptr = h == 0 ? p->extra_ptr128 : p->extra_ptr256;
+        std::vector<int32_t>& lst = h == 0 ? p->extra128 : p->extra256;
         const int32_t tiles = (p->T + rows - 1) / rows;
         ptr.assign(1, 0);
         lst.clear();
         for (int32_t tile = 0; tile < tiles; ++tile) {
-            const int32_t n = stages_of(p->order, tile * rows, std::min(tile * rows + rows, p->T), cols, &lst);
-            if (h == 2) p->max_extra256h = std::max(p->max_extra256h, n);
+            stages_of(p->order, tile * rows, std::min(tile * rows + rows, p->T), cols, &lst);
             ptr.push_back((int32_t)lst.size());
         }
     }
@@ -603,12 +644,12 @@ extern "C" lora_status lora_plan_export(const lora_plan* p, lora_plan_view* v)
     v->num_shrink_tiles = (int32_t)p->shrink_tiles.size();
     v->expand_tiles = p->expand_tiles.data();
     v->num_expand_tiles = (int32_t)p->expand_tiles.size();
-    const bool gemm_tables = !p->extra_ptr256h.empty() && (int32_t)p->order.size() == p->T;
+    const bool gemm_tables = !p->extra_ptr256.empty() && (int32_t)p->order.size() == p->T;
     v->num_gemm_rows = gemm_tables ? p->T : 0;
-    v->num_gemm_tiles = gemm_tables ? (int32_t)p->extra_ptr256h.size() - 1 : 0;
+    v->num_gemm_tiles = gemm_tables ? (int32_t)p->extra_ptr256.size() - 1 : 0;
     v->gemm_order = gemm_tables ? p->order.data() : nullptr;
-    v->gemm_stage_offset = gemm_tables ? p->extra_ptr256h.data() : nullptr;
-    v->gemm_stage = gemm_tables ? p->extra256h.data() : nullptr;
+    v->gemm_stage_offset = gemm_tables ? p->extra_ptr256.data() : nullptr;
+    v->gemm_stage = gemm_tables ? p->extra256.data() : nullptr;
     const lora_plan* u = p->unmerge;
     v->merged_adapter = p->merged;
     v->num_unmerge = u ? (int32_t)u->perm.size() : 0;

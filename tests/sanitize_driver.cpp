@@ -190,7 +190,7 @@ static void check_plan(const batch& b)
             for (int32_t i = tile * 256; i < std::min(b.T, tile * 256 + 256); ++i) {
                 const int32_t a = tok[v.gemm_order[i]];
                 if (a < 0) continue;
-                for (int32_t jb = 0; jb * 32 < 2 * b.rank[a]; ++jb) want.insert({a, jb});
+                for (int32_t jb = 0; jb * 64 < 2 * b.rank[a]; ++jb) want.insert({a, jb});
             }
             REQUIRE(v.gemm_stage_offset[tile + 1] >= v.gemm_stage_offset[tile]);
             for (int32_t i = v.gemm_stage_offset[tile]; i < v.gemm_stage_offset[tile + 1]; ++i)
@@ -266,7 +266,7 @@ static void check_mixture(const batch& b)
                     REQUIRE((v.gemm_stage[i] & 0x7fffff) == m && (v.gemm_stage[i] >> 24) == marked);
                     ++marked;
                 }
-            REQUIRE(marked == (needs ? (2 * b.rank[m] + 31) / 32 : 0));
+            REQUIRE(marked == (needs ? (2 * b.rank[m] + 63) / 64 : 0));
         }
     }
     lora_plan_destroy(p);

@@ -43,7 +43,8 @@ def _check_gemm_tables(w, v, tok, perm):
         assert v["gemm_order"].shape[0] == 0 and v["gemm_stage"].shape[0] == 0
         return
     assert v["gemm_order"].shape[0] == w.T
-    plan_ref.check_gemm_tables(w.T, tok, w.adapter_rank, v["gemm_order"], v["gemm_stage_offset"], v["gemm_stage"])
+    plan_ref.check_gemm_tables(w.T, tok, w.adapter_rank, v["gemm_order"], v["gemm_stage_offset"], v["gemm_stage"],
+                               stage_cols=64)
 
 
 def _check_tiles(w, v, tok, perm):
@@ -105,7 +106,7 @@ def _check_mixture(w, m, variant=B.LORA_VARIANT_AUTO):
     assert ws_bytes >= v_bytes + 2 * w.T * (R + v["unmerge_v_row_stride"]) * 2 and ws_bytes % 256 == 0
     if v["gemm_order"].shape[0]:
         plan_ref.check_gemm_tables(w.T, tok, w.adapter_rank, v["gemm_order"], v["gemm_stage_offset"], v["gemm_stage"],
-                                   merged=m, removal=removal)
+                                   stage_cols=64, merged=m, removal=removal)
     return v
 
 

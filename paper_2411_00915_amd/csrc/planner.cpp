@@ -11,6 +11,7 @@
 #include <mutex>
 #include <new>
 #include <queue>
+#include <utility>
 #include <vector>
 
 #include "plan_internal.h"

@@ -751,14 +751,16 @@ __global__ __launch_bounds__(512) void gemm_ring_kernel(
     }
 }
 
-// v (sum of its K parts, fp32) -> two bf16 terms hi + lo, rows [t][0][R] and [t][1][R] of vb
-__global__ __launch_bounds__(64) void v_split_kernel(
-    const int32_t* __restrict__ perm, const int32_t* __restrict__ token_adapter, const int32_t* __restrict__ rank,
+// v (sum of its K parts, fp32) -> two bf16 terms hi + lo, rows [t][0][R] and [t][1][R] of vb; one wavefront per token
+__global__ __launch_bounds__(256) void v_split_kernel(
+    const int32_t* __restrict__ perm, int n_active, const int32_t* __restrict__ token_adapter, const int32_t* __restrict__ rank,
     const float* __restrict__ v, lora_vspec vsp, bf16_t* __restrict__ vb)
 {
-    const int t = perm[blockIdx.x];
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n_active) return;
+    const int t = perm[row];
     const int r = rank[token_adapter[t]];
-    for (int j = threadIdx.x; j < r; j += 64) {
+    for (int j = threadIdx.x & 63; j < r; j += 64) {
         float f = v[(int64_t)t * vsp.R + j];
         for (int q = 1; q < vsp.P; ++q) f += v[q * vsp.part + (int64_t)t * vsp.R + j];
         const bf16_t hi = f32_to_bf16(f);
@@ -839,15 +841,15 @@ hipError_t launch_gemm_tiled(int32_t T, int32_t K, int32_t N, const void* x, int
     if (delta) {
         // the bf16 split of v, unless the shrink has written it already
         if (!split_done && !p->perm.empty()) {
-            LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)p->perm.size()), dim3(64), 0, stream,
-                        d->perm, d->token_adapter, d->rank, v, lora_vspec_of(p), (bf16_t*)vb);
+            LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)(p->perm.size() + 3) / 4), dim3(256), 0, stream,
+                        d->perm, (int)p->perm.size(), d->token_adapter, d->rank, v, lora_vspec_of(p), (bf16_t*)vb);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
         if (!rm.split_done && rm.plan) {
-            LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)rm.plan->perm.size()), dim3(64), 0, stream,
-                        rm.tables->perm, rm.tables->token_adapter, rm.tables->rank, rm.v, lora_vspec_of(rm.plan),
-                        (bf16_t*)rm.vb);
+            LORA_LAUNCH(LORA_K_V_SPLIT, v_split_kernel, dim3((unsigned)(rm.plan->perm.size() + 3) / 4), dim3(256), 0, stream,
+                        rm.tables->perm, (int)rm.plan->perm.size(), rm.tables->token_adapter, rm.tables->rank, rm.v,
+                        lora_vspec_of(rm.plan), (bf16_t*)rm.vb);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }

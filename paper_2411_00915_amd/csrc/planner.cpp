@@ -196,9 +196,17 @@ static void build_tiles(lora_plan* p)
     // streaming expand: feature range per workgroup, in stages; halved while the launch would have
     // fewer than two workgroups per CU (but at least 4 stages: the start-up of a tile has to pay off)
     int32_t expand_stages = std::max(1, tu.expand_stream_stages);
+    // (its token tiles: 128 tokens -- every token tile of an adapter fetches Bt_a again, and the launch has feature
+    // ranges to make workgroups of -- unless that leaves fewer than two rounds of tiles)
+    int32_t expand_tokens = 128;
     if (p->expand_stream) {
-        int64_t n_tt = 0;
-        for (int g = 0; g < G; ++g) n_tt += (p->group_offset[g + 1] - p->group_offset[g] + stream_tokens - 1) / stream_tokens;
+        auto token_tiles = [&](int32_t per) {
+            int64_t n = 0;
+            for (int g = 0; g < G; ++g) n += (p->group_offset[g + 1] - p->group_offset[g] + per - 1) / per;
+            return n;
+        };
+        if (token_tiles(128) * ((p->N + expand_stages * 64 - 1) / (expand_stages * 64)) < 512) expand_tokens = stream_tokens;
+        const int64_t n_tt = token_tiles(expand_tokens);
         while (expand_stages > 4 && n_tt * ((p->N + expand_stages * 64 - 1) / (expand_stages * 64)) < 512) expand_stages /= 2;
     }
     for (int g = 0; g < G; ++g) {
@@ -256,8 +264,8 @@ static void build_tiles(lora_plan* p)
         if (p->expand_stream) {
             const int ks = r <= 32 ? 1 : (r <= 64 ? 2 : 4);
             const int fw_max = 8 / ks;
-            for (int32_t row = lo; row < hi; row += stream_tokens) {
-                const int32_t nrows = std::min<int32_t>(stream_tokens, hi - row);
+            for (int32_t row = lo; row < hi; row += expand_tokens) {
+                const int32_t nrows = std::min<int32_t>(expand_tokens, hi - row);
                 const int nblk = (nrows + 15) / 16;
                 const int nb = nblk > 4 ? 8 : (nblk > 2 ? 4 : (nblk > 1 ? 2 : 1));
                 const int fw = std::min(8 / nb, fw_max);

@@ -399,6 +399,8 @@ void lora_tuning_get(int32_t* values, int32_t count);
  *   k, n         in / out features (exact match)
  *   max_rank     largest rank in use, rounded up to 8, 16, 32, 64, 128 or 256 (exact match)
  *   group_class  0: every adapter group has fewer than 64 tokens (decode-shaped), 1: otherwise (exact match)
+ * An entry without values (all <= 0) says that the class was searched and keeps the defaults; it is there so that a
+ * batch of that class is not planned with the entry of the next larger token count.
  * The library ships with the table its offline search (paper_2411_00915_amd/autotune.py) wrote on MI355X;
  * lora_tuning_table_set replaces it for the process (entries are copied; NULL / 0 restores the shipped table),
  * lora_tuning_table_get copies up to `capacity` entries out and returns the table's size.  Plans made earlier keep

@@ -123,22 +123,43 @@ class Bench:
         return us
 
 
-def write_table(path, entries, note, B):
+def search_classes(quick=False):
+    """The shape classes of the search: (tokens, K, N, rank class, group class)."""
+    classes = []
+    for (K, N) in (SHAPES[:1] if quick else SHAPES):
+        for T in (DECODE_TOKENS[3:8:4] if quick else DECODE_TOKENS):
+            for r in DECODE_RANKS:
+                classes.append((T, K, N, r, 0))
+        for T in (PREFILL_TOKENS[1:3] if quick else PREFILL_TOKENS):
+            for r in (PREFILL_RANKS[1:2] if quick else PREFILL_RANKS):
+                classes.append((T, K, N, r, 1))
+    return classes
+
+
+def write_table(path, entries, note, B, classes=()):
+    """entries: the classes that keep tunables of their own.  Every other class of `classes` gets a row without
+    values: the search found nothing better than the defaults for it, and without a row of its own a batch of that
+    class would be planned with the entry of the next larger token count, which was tuned for another size."""
+    have = {(e["tokens"], e["k"], e["n"], e["max_rank"], e["group_class"]) for e in entries}
+    rows = list(entries) + [dict(tokens=c[0], k=c[1], n=c[2], max_rank=c[3], group_class=c[4], tunables={})
+                            for c in classes if tuple(c) not in have]
+    rows.sort(key=lambda e: (e["k"], e["n"], e["group_class"], e["max_rank"], e["tokens"]))
     with open(path, "w") as f:
         f.write("// Shape table shipped with the library: { tokens, k, n, max_rank, group_class, { tunables in the order of\n"
-                "// lora_tuning_set; 0 = default } }.  Written by `python -m paper_2411_00915_amd.autotune --write` on\n"
+                "// lora_tuning_set; 0 = default } }; a row of zeros = the class was searched and keeps the defaults.\n"
+                "// Written by `python -m paper_2411_00915_amd.autotune --write` on\n"
                 f"// {note}\n")
-        for e in entries:
+        for e in rows:
             vals = ", ".join(str(int(e["tunables"].get(k, 0))) for k in B.TUNING_FIELDS)
             f.write(f"{{{e['tokens']}, {e['k']}, {e['n']}, {e['max_rank']}, {e['group_class']}, {{{vals}}}}},\n")
-        if not entries:
+        if not rows:
             f.write("{0, 1, 1, 8, 0, {0}},   // (no class beat the defaults)\n")
 
 
 def revalidate(args, torch, B, device):
     import re
     text = open(args.revalidate).read()
-    note = " ".join(l[2:].strip() for l in text.split("\n")[2:] if l.startswith("//"))
+    note = " ".join(l[2:].strip() for l in text.split("\n")[3:] if l.startswith("//"))
     rows = re.findall(r"^\{(\d+), (\d+), (\d+), (\d+), (\d+), \{([^}]*)\}\},", text, flags=re.M)
     kept, lines = [], []
     t_start = time.time()
@@ -148,6 +169,8 @@ def revalidate(args, torch, B, device):
             continue
         vals = [int(q) for q in row[5].split(",")]
         tun = {k: val for k, val in zip(B.TUNING_FIELDS, vals) if val > 0}
+        if not tun:
+            continue                                                        # (a class that keeps the defaults)
         w = make_case(T, K, N, r, gc, seed=77000 + ci)                      # a fresh batch of the class
         per_layer = 2 * (w.T * w.K + w.T * w.N + sum(int(q) * (w.K + w.N) for q in w.adapter_rank))
         bench = Bench(w, layers_for(per_layer), B, device, torch)
@@ -164,7 +187,7 @@ def revalidate(args, torch, B, device):
     print(f"{len(kept)} of {len(rows)} entries kept ({time.time() - t_start:.0f} s)")
     if args.write:
         write_table(args.write, kept, note + f"  Re-timed on a second machine on fresh batches: {len(kept)} of {len(rows)} entries kept "
-                                             f"(gain over the defaults above {100 * args.min_gain:.0f} % both times).", B)
+                                             f"(gain over the defaults above {100 * args.min_gain:.0f} % both times).", B, search_classes())
     if args.summary:
         with open(args.summary, "a") as f:
             f.write(f"\nRevalidation on a second machine (fresh batches of each class, ten sweeps, twice): {len(kept)} of {len(rows)} "
@@ -195,15 +218,7 @@ def main():
     B.lora_tuning_table_set([dict(tokens=0, k=1, n=1, max_rank=8, group_class=0, tunables={})])
     if args.revalidate:
         return revalidate(args, torch, B, device)
-    classes = []
-    shapes = SHAPES[:1] if args.quick else SHAPES
-    for (K, N) in shapes:
-        for T in (DECODE_TOKENS[3:8:4] if args.quick else DECODE_TOKENS):
-            for r in DECODE_RANKS:
-                classes.append((T, K, N, r, 0))
-        for T in (PREFILL_TOKENS[1:3] if args.quick else PREFILL_TOKENS):
-            for r in (PREFILL_RANKS[1:2] if args.quick else PREFILL_RANKS):
-                classes.append((T, K, N, r, 1))
+    classes = search_classes(args.quick)
     lines, entries, n_candidates = [], [], 0
     t_start = time.time()
     for ci, (T, K, N, r, gc) in enumerate(classes):
@@ -265,7 +280,7 @@ def main():
             f.write(text)
     if args.write:
         write_table(args.write, entries, f"{torch.cuda.get_device_name(0)} ({torch.cuda.get_device_properties(0).gcnArchName}): "
-                                         f"{n_candidates} candidates over {len(classes)} shape classes.", B)
+                                         f"{n_candidates} candidates over {len(classes)} shape classes.", B, classes)
         print(f"wrote {args.write}: the library takes csrc/tuning_table.inc in when it is built")
 
 

@@ -73,9 +73,11 @@ void snapshot_tuning(lora_plan* p, const lora_batch_desc* d, int32_t active_toke
         const bool e_covers = e.tokens >= active_tokens, b_covers = best->tokens >= active_tokens;
         if (e_covers != b_covers ? e_covers : (e_covers ? e.tokens < best->tokens : e.tokens > best->tokens)) best = &e;
     }
-    if (best && active_tokens > 0) {
+    if (best && active_tokens > 0) {                             // (a row of zeros: the class keeps the defaults)
+        bool any = false;
+        for (int32_t i = 0; i < LORA_TUNING_COUNT; ++i) any = any || best->values[i] > 0;
         overlay(&p->tuning, best->values, LORA_TUNING_COUNT);
-        p->tuning_source = 1;
+        if (any) p->tuning_source = 1;
     }
     if (d->tuning && d->tuning_count > 0) {
         bool any = false;

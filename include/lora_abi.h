@@ -398,7 +398,8 @@ void lora_tuning_get(int32_t* values, int32_t count);
  *                are made for multiples of 32), else the one with the largest
  *   k, n         in / out features (exact match)
  *   max_rank     largest rank in use, rounded up to 8, 16, 32, 64, 128 or 256 (exact match)
- *   group_class  0: every adapter group has fewer than 64 tokens (decode-shaped), 1: otherwise (exact match)
+ *   group_class  0: every adapter group has fewer than 64 tokens (decode-shaped); 2: the adapter groups hold 512
+ *                tokens or more on average (few long requests, e.g. image-sized prefill); 1: otherwise (exact match)
  * An entry without values (all <= 0) says that the class was searched and keeps the defaults; it is there so that a
  * batch of that class is not planned with the entry of the next larger token count.
  * The library ships with the table its offline search (paper_2411_00915_amd/autotune.py) wrote on MI355X;

@@ -57,9 +57,14 @@ class Case:
 def make_case(tokens, K, N, rank_class, group_class, seed):
     """A synthetic batch of the class: ranks drawn from the rank classes within a factor 8 below rank_class;
     decode-shaped = single-token requests over about tokens / 4 adapters; prefill-sized = requests of lognormal
-    length (mean 64, sigma 1, as the mixed serving configuration) over about tokens / 64 adapters."""
+    length (mean 64, sigma 1, as the mixed serving configuration) over about tokens / 64 adapters; long requests =
+    requests of 1024 tokens, each with an adapter of its own of the class's rank (image-sized prefill)."""
     rng = np.random.default_rng(seed)
     ranks = [r for r in (8, 16, 32, 64, 128) if r <= rank_class and r * 8 >= rank_class]
+    if group_class == 2:
+        n_a = max(1, -(-tokens // 1024))
+        lengths = np.asarray([min(1024, tokens - 1024 * i) for i in range(n_a)], np.int64)
+        return Case(tokens, K, N, np.concatenate([[0], np.cumsum(lengths)]), np.arange(n_a), np.full(n_a, rank_class))
     if group_class == 0:
         lengths = np.ones(tokens, np.int64)
         n_a = max(2, tokens // 4)
@@ -123,17 +128,27 @@ class Bench:
         return us
 
 
-def search_classes(quick=False):
+def search_classes(quick=False, group_classes=(0, 1, 2)):
     """The shape classes of the search: (tokens, K, N, rank class, group class)."""
     classes = []
     for (K, N) in (SHAPES[:1] if quick else SHAPES):
-        for T in (DECODE_TOKENS[3:8:4] if quick else DECODE_TOKENS):
-            for r in DECODE_RANKS:
-                classes.append((T, K, N, r, 0))
-        for T in (PREFILL_TOKENS[1:3] if quick else PREFILL_TOKENS):
-            for r in (PREFILL_RANKS[1:2] if quick else PREFILL_RANKS):
-                classes.append((T, K, N, r, 1))
+        if 0 in group_classes:
+            for T in (DECODE_TOKENS[3:8:4] if quick else DECODE_TOKENS):
+                for r in DECODE_RANKS:
+                    classes.append((T, K, N, r, 0))
+        for gc in (1, 2):
+            if gc in group_classes:
+                for T in (PREFILL_TOKENS[1:3] if quick else PREFILL_TOKENS):
+                    for r in (PREFILL_RANKS[1:2] if quick else PREFILL_RANKS):
+                        classes.append((T, K, N, r, gc))
     return classes
+
+
+def read_table(path):
+    """Rows of a tuning_table.inc: [(tokens, k, n, max_rank, group_class, [values])]."""
+    import re
+    rows = re.findall(r"^\{(\d+), (\d+), (\d+), (\d+), (\d+), \{([^}]*)\}\},", open(path).read(), flags=re.M)
+    return [tuple(int(q) for q in row[:5]) + ([int(q) for q in row[5].split(",")],) for row in rows]
 
 
 def write_table(path, entries, note, B, classes=()):
@@ -184,13 +199,14 @@ def revalidate(args, torch, B, device):
         del bench
         torch.cuda.empty_cache()
     B.lora_tuning_table_set([])
-    print(f"{len(kept)} of {len(rows)} entries kept ({time.time() - t_start:.0f} s)")
+    n_entries = len(lines)                                                  # (rows that carry values)
+    print(f"{len(kept)} of {n_entries} entries kept ({time.time() - t_start:.0f} s)")
     if args.write:
-        write_table(args.write, kept, note + f"  Re-timed on a second machine on fresh batches: {len(kept)} of {len(rows)} entries kept "
+        write_table(args.write, kept, note + f"  Re-timed on a second machine on fresh batches: {len(kept)} of {n_entries} entries kept "
                                              f"(gain over the defaults above {100 * args.min_gain:.0f} % both times).", B, search_classes())
     if args.summary:
         with open(args.summary, "a") as f:
-            f.write(f"\nRevalidation on a second machine (fresh batches of each class, ten sweeps, twice): {len(kept)} of {len(rows)} "
+            f.write(f"\nRevalidation on a second machine (fresh batches of each class, ten sweeps, twice): {len(kept)} of {n_entries} "
                     f"entries still beat the defaults by more than {100 * args.min_gain:.0f} % and are kept.\n")
     return 0
 
@@ -201,6 +217,10 @@ def main():
     ap.add_argument("--write", nargs="?", const=TABLE_INC, default=None, metavar="FILE",
                     help=f"write the table (default {TABLE_INC}; the library includes that file when it is built)")
     ap.add_argument("--min-gain", type=float, default=0.03)
+    ap.add_argument("--group-class", type=int, action="append", default=None,
+                    help="search these group classes only (0 decode-shaped, 1 mixed prefill, 2 long requests; repeatable)")
+    ap.add_argument("--keep", default=None, metavar="FILE",
+                    help="with --group-class: carry the rows of the other group classes over from this table")
     ap.add_argument("--report", default=None, help="also write the report (markdown) to this file")
     ap.add_argument("--summary", default=None, help="write a short summary of the report (markdown) to this file")
     ap.add_argument("--revalidate", default=None, metavar="FILE",
@@ -218,7 +238,8 @@ def main():
     B.lora_tuning_table_set([dict(tokens=0, k=1, n=1, max_rank=8, group_class=0, tunables={})])
     if args.revalidate:
         return revalidate(args, torch, B, device)
-    classes = search_classes(args.quick)
+    searched = tuple(args.group_class) if args.group_class else (0, 1, 2)
+    classes = search_classes(args.quick, searched)
     lines, entries, n_candidates = [], [], 0
     t_start = time.time()
     for ci, (T, K, N, r, gc) in enumerate(classes):
@@ -279,8 +300,17 @@ def main():
         with open(args.report, "w") as f:
             f.write(text)
     if args.write:
-        write_table(args.write, entries, f"{torch.cuda.get_device_name(0)} ({torch.cuda.get_device_properties(0).gcnArchName}): "
-                                         f"{n_candidates} candidates over {len(classes)} shape classes.", B, classes)
+        carried = []
+        if args.keep:
+            for (T, K, N, r, gc, vals) in read_table(args.keep):
+                if gc not in searched:
+                    carried.append(dict(tokens=T, k=K, n=N, max_rank=r, group_class=gc,
+                                        tunables={k: v for k, v in zip(B.TUNING_FIELDS, vals) if v > 0}))
+        write_table(args.write, entries + [e for e in carried if e["tunables"]],
+                    f"{torch.cuda.get_device_name(0)} ({torch.cuda.get_device_properties(0).gcnArchName}): "
+                    f"{n_candidates} candidates over {len(classes)} shape classes"
+                    + (f" (group classes {list(searched)}; the other rows carried over from an earlier search)" if args.keep else "") + ".",
+                    B, classes + [(e["tokens"], e["k"], e["n"], e["max_rank"], e["group_class"]) for e in carried])
         print(f"wrote {args.write}: the library takes csrc/tuning_table.inc in when it is built")
 
 

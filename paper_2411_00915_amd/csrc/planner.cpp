@@ -65,7 +65,11 @@ void snapshot_tuning(lora_plan* p, const lora_batch_desc* d, int32_t active_toke
     std::lock_guard<std::mutex> lock(g_tuning_mutex);
     p->tuning = g_lora_tuning;
     p->tuning_source = 0;
-    const int32_t rc = rank_class(max_rank), gc = max_group >= 64 ? 1 : 0;
+    // group class: 0 every adapter group below 64 tokens (decode-shaped); 2 groups of 512 tokens or more on average
+    // (few long requests, e.g. image-sized prefill); 1 everything between
+    const int32_t n_groups = (int32_t)p->group_adapter.size();
+    const int32_t rc = rank_class(max_rank),
+                  gc = max_group < 64 ? 0 : ((int64_t)active_tokens >= 512ll * std::max(n_groups, 1) ? 2 : 1);
     const lora_tuning_entry* best = nullptr;
     for (const lora_tuning_entry& e : g_table) {
         if (e.k != p->K || e.n != p->N || e.max_rank != rc || e.group_class != gc) continue;

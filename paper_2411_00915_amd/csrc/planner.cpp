@@ -112,7 +112,7 @@ extern "C" lora_status lora_tuning_table_set(const lora_tuning_entry* entries, i
     if (count < 0 || (count > 0 && !entries)) return LORA_ERR_INVALID_ARG;
     for (int32_t i = 0; i < count; ++i)
         if (entries[i].tokens < 0 || entries[i].k < 1 || entries[i].n < 1 || entries[i].max_rank != rank_class(entries[i].max_rank) ||
-            entries[i].max_rank > LORA_MAX_RANK || entries[i].group_class < 0 || entries[i].group_class > 1)
+            entries[i].max_rank > LORA_MAX_RANK || entries[i].group_class < 0 || entries[i].group_class > 2)
             return LORA_ERR_INVALID_ARG;
     try {
         std::vector<lora_tuning_entry> next = count ? std::vector<lora_tuning_entry>(entries, entries + count)

@@ -330,6 +330,22 @@ def test_shape_table_is_consulted_inside_plan_create():
         other = wl.random_case(6, 100, 512, 512, 30, (8, 64), max_seg=1, with_w=False)
         vo = B.lora_plan_export(device.make_plan(other))
         assert vo["tuning_source"] == 0 and vo["tuning"] == defaults
+        # group classes: 0 every adapter group below 64 tokens, 2 groups of 512 tokens or more on average, 1 between;
+        # an entry without values is a match that keeps the defaults (and is not reported as a source)
+        B.lora_tuning_table_set([
+            dict(tokens=4096, k=4096, n=4096, max_rank=64, group_class=1, tunables={"expand_stream_stages": 8}),
+            dict(tokens=4096, k=4096, n=4096, max_rank=64, group_class=2, tunables={"expand_stream_stages": 32}),
+            dict(tokens=2048, k=4096, n=4096, max_rank=64, group_class=2, tunables={}),
+        ])
+        long_requests = wl.cfg3(with_w=False)                                       # 4 adapters x 1024 tokens
+        assert B.lora_plan_export(device.make_plan(long_requests))["tuning"]["expand_stream_stages"] == 32
+        mixed = wl.random_case(7, 4096, 4096, 4096, 40, (64,), max_seg=200, with_w=False)   # about 100 tokens per adapter
+        assert B.lora_plan_export(device.make_plan(mixed))["tuning"]["expand_stream_stages"] == 8
+        half = wl.random_case(8, 2048, 4096, 4096, 2, (64,), max_seg=2048, with_w=False)
+        half = wl.Workload("h", "bf16", 2048, 4096, 4096, np.array([0, 1024, 2048], np.int32), np.array([0, 1], np.int32),
+                           half.adapter_rank, half.adapter_scale, half.x, None)
+        vh = B.lora_plan_export(device.make_plan(half))
+        assert vh["tuning_source"] == 0 and vh["tuning"] == defaults                 # the row of zeros, not the 4096-token entry
         # replacing the table does not touch plans already made
         B.lora_tuning_table_set([])
         assert B.lora_plan_export(p)["tuning"]["expand_wave_bytes"] == 32768

@@ -68,9 +68,8 @@
  * rounding it once, so a token with an adapter of its own gets
  * rnd(rnd(beta y + removal) + own) -- within u (|beta y + removal| + |y|) of
  * the exact value, u the unit roundoff of the dtype.  lora_fused_forward's
- * GEMM takes the removal in as one more group of adapter stages per tile of
- * rows, inside the same fp32 accumulators: one rounding, as without mixture
- * mode.  "Rows of tokens without adapter are
+ * GEMM takes the removal in as one more adapter for the rows it applies to,
+ * inside the same fp32 accumulators: one rounding, as without mixture mode.  "Rows of tokens without adapter are
  * left untouched" then holds for the tokens of adapter m only.
  * merged_adapter_plus1 naming an adapter of rank 0: same as 0.
  *
@@ -322,8 +321,10 @@ lora_status lora_base_gemm(int32_t num_tokens, int32_t k, int32_t n, int32_t dty
  * inference, sections 2 and 4.4).  Runs the shrink into `workspace` (which
  * holds v and its split into two bf16 terms; size from lora_plan_query,
  * 256-byte aligned), then one GEMM kernel that walks the tokens in
- * adapter-sorted order and takes each adapter's v B_a in as extra k-stages of
- * its pipeline.  LORA_ERR_WORKSPACE if the workspace is too small.
+ * adapter-sorted order and adds each adapter's v B_a to the accumulators of
+ * the rows that carry it (as extra k-stages of its pipeline, or wavefront by
+ * wavefront after the K loop, depending on the kernel).  LORA_ERR_WORKSPACE if
+ * the workspace is too small.
  */
 lora_status lora_fused_forward(lora_plan* plan, const void* x, int64_t ldx,
                                const void* Wt, int64_t ldw,

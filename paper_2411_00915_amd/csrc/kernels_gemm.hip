@@ -6,13 +6,14 @@
 // sections 1-2); adding the delta to the fp32 accumulators before y is rounded
 // makes unmerged inference cost close to merged inference (section 4.4).
 //
-// The delta enters as extra k-stages of the same pipeline.  The kernel walks
-// the tokens in adapter-sorted order, so a tile of rows holds few adapters; for
-// each adapter a present in a row tile it runs ceil(2 r_a / 64) (ring kernel:
-// / 32) more stages whose "W tile" is Bt_a[features, ranks] and whose "x tile"
-// is the matching columns of [v_hi | v_lo] (v split into two bf16 terms, rows
-// of other adapters zero; Bt_a is simply addressed twice).  Their
-// loads are prefetched like any other stage's: nothing is exposed in an epilogue.
+// Both kernels walk the tokens in adapter-sorted order, so that neighbouring rows share an adapter.
+//   gemm_ring_kernel: after the K loop every wavefront adds the deltas of its own 64 tokens to its accumulators,
+//     adapter by adapter and 32 ranks at a time, with Bt_a[its features, ranks] and the tokens' v (split into two
+//     bf16 terms v_hi + v_lo) straight from memory as MFMA operands (see the kernel).
+//   gemm_tiled_kernel: the delta enters as extra k-stages of the same pipeline; for each adapter a present in a
+//     row tile it runs ceil(2 r_a / 64) more stages whose "W tile" is Bt_a[features, ranks] and whose "x tile" is the
+//     matching columns of [v_hi | v_lo] (rows of other adapters zero; Bt_a is simply addressed twice).  Their loads
+//     are prefetched like any other stage's.
 //
 // x [T,K] and Wt [N,K] are both contraction-index-fastest, so tiles arrive in LDS
 // as 16-byte chunks and come back out of it as ready-made MFMA operands (8
@@ -22,7 +23,7 @@
 //     loads HBM -> LDS directly into a ring of four 32-k stages.
 //   gemm_tiled_kernel: everything else.  Loads HBM -> registers -> LDS, double buffered (dynamic LDS,
 //     2 x (BM + BT) x 128 bytes); workgroup tile = 4 wavefronts (2 x 2), each WB x WB MFMA blocks of 32 x 32:
-//     WB = 4: 256 features x 256 tokens x 64 k (K no multiple of 32, or more adapter stages than the ring kernel lists)
+//     WB = 4: 256 features x 256 tokens x 64 k (K no multiple of 32)
 //     WB = 2: 128 x 128 x 64 (small problems, less padding waste)
 //
 // Lane roles in v_mfma_f32_32x32x16_bf16 (D = A*B + C, A 32x16, B 16x32):

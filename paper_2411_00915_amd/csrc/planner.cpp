@@ -436,7 +436,8 @@ static void build_tiles(lora_plan* p)
 }
 
 // Tables of the fused GEMM: it walks the tokens in adapter-sorted order, so a tile of rows holds few
-// adapters, and folds each adapter's delta in as extra k-stages (v_hi, v_lo against Bt_a).  The full
+// adapters, and folds each adapter's delta in (v_hi, v_lo against Bt_a; the register-staged kernels as extra
+// k-stages from the lists below, the ring kernel per wavefront from the row keys).  The full
 // blocks of 256 sorted rows are then put heaviest first (most adapter stages): workgroups start in
 // index order, so the long tiles run early and the short ones fill the tail of the launch.
 // Mixture mode: the removal of the merged adapter concerns every token of `unmerge`'s single adapter group; a tile

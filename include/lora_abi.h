@@ -74,8 +74,11 @@
  * merged_adapter_plus1 naming an adapter of rank 0: same as 0.
  *
  * ALIGNMENT for the tuned bf16 kernels: base pointers 16 bytes; K, ldx, ldy,
- * ldw multiples of 8; ranks multiples of 8.  Anything else (and fp32) runs
- * through a general kernel with no alignment demands.
+ * ldw multiples of 8; ranks multiples of 8, at most 128.  Anything else (and
+ * fp32) runs through general kernels with no alignment demands, which are one
+ * to two orders of magnitude slower per token; padding an adapter's factors
+ * with zero rank rows / columns to a multiple of 8 changes no result and moves
+ * it onto the tuned kernels.
  */
 #ifndef LORA_ABI_H
 #define LORA_ABI_H

@@ -232,11 +232,13 @@ def test_large_tile_gemm_ragged_shapes(T, K, N):
     run_forward_case(w, n_sample=160)
 
 
-def test_large_tile_gemm_with_more_adapter_stages_than_the_tile_lists_hold():
-    """Single-token segments of 400 adapters: a 256-row tile carries about 250 adapters, i.e. far more adapter stages
-    than the kernels cache per tile (256), so the fused forward takes the register-staged kernel, which reads the
-    stages beyond its list from memory."""
-    w = wl.random_case(811, 3840, 256, 3328, 400, (32, 64), max_seg=1, frac_none=0.05)
+@pytest.mark.parametrize("K", [256, 200])
+def test_large_tile_gemm_with_hundreds_of_adapters_per_tile(K):
+    """Single-token segments of 400 adapters: a 256-row tile carries about 250 adapters.  K = 256: the ring kernel,
+    whose wavefronts then walk about 60 adapters each for their 64 rows.  K = 200 (no multiple of 32): the
+    register-staged kernel with far more adapter stages than it caches per tile (256), so that it reads the stages
+    beyond its list from memory."""
+    w = wl.random_case(811, 3840, K, 3328, 400, (32, 64), max_seg=1, frac_none=0.05)
     run_forward_case(w, n_sample=160)
 
 

@@ -25,9 +25,32 @@
 // read it during the same launch without an L2 write-back
 // `rows`: token of the tile's row i at rows[i] (perm + tile.row0).  PUBLISH: rows is the padded 16-entry
 // table of the single-launch kernel instead, whose address does not depend on the tile descriptor.
-template <int TB, int JB, int U, bool PUBLISH = false>
+// The 16 tokens of a tile of the single-launch kernel: they are fetched through the
+// scalar cache (their address depends on the workgroup index alone), not through the compute unit's vector memory
+// pipeline, where a late workgroup's small loads queue behind the bulk loads of the workgroups that started
+// before it, and parked in the first 16 lanes of a register; operator[] reads one by lane index (which may differ
+// per lane).
+struct tile_rows16 {
+    int by_m;        // token of row (lane & 15)
+    // t: the 16 tokens as just loaded from a wavefront-uniform address (one scalar load of 64 bytes, which the
+    // caller requests before it waits for anything else).  Call with all lanes active: the per-lane view is
+    // read out of lanes 0..15 here, once (a cross-lane read under a mask would return what inactive lanes hold).
+    // by_row (may be null): 16 ints of LDS that receive the tokens by row index, for readers after a barrier.
+    __device__ __forceinline__ void park(const int (&t)[16], int* by_row)
+    {
+        int v = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) asm("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(t[q]), "n"(q));
+        by_m = __shfl(v, (int)threadIdx.x & 15, 64);
+        if (by_row && threadIdx.x < 16) by_row[threadIdx.x] = v;
+    }
+    // row must be congruent to lane & 15 modulo 16 (the tiles of the single launch have 16 rows)
+    __device__ __forceinline__ int operator[](int row) const { return by_m; }
+};
+
+template <int TB, int JB, int U, bool PUBLISH = false, typename Rows = const int32_t*>
 __device__ __forceinline__ void shrink_tile(
-    const lora_tile tile, const int32_t* __restrict__ rows,
+    const lora_tile tile, Rows rows,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
     float* __restrict__ v, lora_vspec vsp, floatx4* lds, uint4* patch = nullptr)
 {
@@ -511,10 +534,10 @@ __device__ __forceinline__ unsigned long long ld_agent(const unsigned long long*
 
 template <int KS>
 __device__ __forceinline__ void fused_expand_item(
-    const lora_tile tile, const int32_t* __restrict__ rows, const float* __restrict__ scale,
+    const lora_tile tile, const tile_rows16& rows, const float* __restrict__ scale,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
     const float* v, lora_vspec vsp, const bf16_t* __restrict__ Bt, bf16_t* __restrict__ y, int64_t ldy, int N,
-    float beta, lora_sync_slot* sync, long long wait_ticks, int delay, float* vt, int* flag)
+    float beta, lora_sync_slot* sync, long long wait_ticks, int delay, float* vt, int* flag, const int* row_tok)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
@@ -591,7 +614,7 @@ __device__ __forceinline__ void fused_expand_item(
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         const int row = threadIdx.x >> 4, j4 = (threadIdx.x & 15) * 4;
         if (row < tile.nrows && j4 < r) {
-            const int t = rows[row];
+            const int t = row_tok[row];                    // written before the barrier above
             float pv[4][4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {                  // all parts are requested before the first add
@@ -611,7 +634,7 @@ __device__ __forceinline__ void fused_expand_item(
         const float s_a = scale[tile.adapter];
         for (int idx = wave; idx < tile.nrows * r; idx += 4) {
             const int row = idx / r, j = idx - row * r;
-            const bf16_t* xr = x + (int64_t)rows[row] * ldx;
+            const bf16_t* xr = x + (int64_t)row_tok[row] * ldx;
             const bf16_t* ar = At + (int64_t)j * K;
             float acc = 0.f;
             for (int k = lane * 8; k < K; k += 512) {
@@ -705,25 +728,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
     __shared__ uint4 patches[4 * 256];       // 16 KB: one 4 KB patch per wavefront (whole-line loads -> MFMA operands)
     __shared__ int flag;
     const int b = blockIdx.x;
-    // With at most 64 adapters every lane fetches one entry of the pointer table while the tile
-    // descriptor is still on its way; the tile's entry is then picked out of the wavefront's registers.
-    // The workgroup's chain of dependent loads is descriptor / tokens / pointers -> data.
-    const bool table_fits = n_adapters <= 64;
-    const int lane_a = min((int)(threadIdx.x & 63), n_adapters - 1);
-    auto pick = [&](uint64_t entry, int a) {
-        const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)entry, a);
-        const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(entry >> 32), a);
-        return reinterpret_cast<const bf16_t*>((uint64_t)lo | ((uint64_t)hi << 32));
-    };
+    // A workgroup's chain of dependent loads is descriptor / tokens -> adapter pointer -> data, and the first two
+    // steps go through the scalar cache: descriptor and tokens at addresses that depend on the workgroup index
+    // alone, the pointer at one that depends on the descriptor.  (Fetching tokens and a per-lane copy of the
+    // pointer table with vector loads saved the dependent step but put them behind the bulk loads of the compute
+    // unit's earlier workgroups: late workgroups then got their own loads out 2 to 3 us after their start.)
+    tile_rows16 rows;
+    int t16[16];
+    const int32_t* rows_src = b < n_shrink ? shrink_rows + (int64_t)b * 16 : expand_rows + (int64_t)(b - n_shrink) * 16;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) t16[q] = rows_src[q];
     if (b < n_shrink) {
-        const uint64_t a_entry = table_fits ? reinterpret_cast<uint64_t>(At_ptrs[lane_a]) : 0;
         const lora_tile tile = shrink_tiles[b];
-        const bf16_t* At = table_fits ? pick(a_entry, tile.adapter) : At_ptrs[tile.adapter];
-        const int32_t* rows = shrink_rows + (int64_t)b * 16;
+        const bf16_t* At = At_ptrs[tile.adapter];
+        rows.park(t16, nullptr);
         const int jb = (tile.shape >> 4) & 15;
         uint4* patch = patches + (threadIdx.x >> 6) * 256;
-        if (jb == 1) shrink_tile<1, 1, 8, true>(tile, rows, x, ldx, At, K, v, vsp, lds, patch);
-        else shrink_tile<1, 2, 4, true>(tile, rows, x, ldx, At, K, v, vsp, lds, patch);
+        if (jb == 1) shrink_tile<1, 1, 8, true, const tile_rows16&>(tile, rows, x, ldx, At, K, v, vsp, lds, patch);
+        else shrink_tile<1, 2, 4, true, const tile_rows16&>(tile, rows, x, ldx, At, K, v, vsp, lds, patch);
         // Publish.  v was stored with agent-scope (sc1) stores, which are written through to the level all
         // XCDs share instead of staying in this XCD's L2.  A store's acknowledgement is what takes it off the
         // wavefront's vmcnt counter, so after s_waitcnt vmcnt(0) this thread's part of v is visible to every
@@ -737,17 +759,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
         if (threadIdx.x == 0)
             __hip_atomic_fetch_add(&sync[(unsigned int)tile.shape >> 16].done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     } else {
-        const uint64_t b_entry = table_fits ? reinterpret_cast<uint64_t>(Bt_ptrs[lane_a]) : 0;
         const lora_tile tile = expand_tiles[b - n_shrink];
-        const bf16_t* Bt = table_fits ? pick(b_entry, tile.adapter) : Bt_ptrs[tile.adapter];
+        const bf16_t* Bt = Bt_ptrs[tile.adapter];
         const bf16_t* At = At_ptrs[tile.adapter];        // only the bounded-wait fallback reads it
-        const int32_t* rows = expand_rows + (int64_t)(b - n_shrink) * 16;
+        int* row_tok = reinterpret_cast<int*>(patches);  // an expand workgroup stages nothing through the patches
+        rows.park(t16, row_tok);
         if (tile.reserved0 <= 32)
             fused_expand_item<1>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, wait_ticks, delay,
-                                 reinterpret_cast<float*>(lds), &flag);
+                                 reinterpret_cast<float*>(lds), &flag, row_tok);
         else
             fused_expand_item<2>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, wait_ticks, delay,
-                                 reinterpret_cast<float*>(lds), &flag);
+                                 reinterpret_cast<float*>(lds), &flag, row_tok);
     }
 }
 

@@ -266,52 +266,22 @@ __device__ __forceinline__ void expand_stream_tile(
     const int n_end = tile.c0 + tile.cn;
     const int n_stages = (((tile.cn + 63) >> 6) + FW - 1) / FW;
 
-    // v operands (MFMA columns = tokens): lane holds v[token m][32 s + 8 g .. +7]
-    op16 vhi[KS], vlo[KS];
-    {
-        const int row = blk * 16 + m;
-        const bool row_ok = active && row < tile.nrows;
-        const int tok = perm[tile.row0 + (row_ok ? row : 0)];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int j = s * 32 + g * 8;
-            float4 pa[4], pb[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {                  // all parts are fetched before the first add
-                if (row_ok && j < r && q < vsp.P) {
-                    const float* vq = v + q * vsp.part + (int64_t)tok * vsp.R + j;
-                    pa[q] = *reinterpret_cast<const float4*>(vq);
-                    pb[q] = *reinterpret_cast<const float4*>(vq + 4);
-                } else {
-                    pa[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    pb[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-            }
-            float f[8];
-            f[0] = ((pa[0].x + pa[1].x) + pa[2].x) + pa[3].x; f[1] = ((pa[0].y + pa[1].y) + pa[2].y) + pa[3].y;
-            f[2] = ((pa[0].z + pa[1].z) + pa[2].z) + pa[3].z; f[3] = ((pa[0].w + pa[1].w) + pa[2].w) + pa[3].w;
-            f[4] = ((pb[0].x + pb[1].x) + pb[2].x) + pb[3].x; f[5] = ((pb[0].y + pb[1].y) + pb[2].y) + pb[3].y;
-            f[6] = ((pb[0].z + pb[1].z) + pb[2].z) + pb[3].z; f[7] = ((pb[0].w + pb[1].w) + pb[2].w) + pb[3].w;
-            split_bf16(f, vhi[s], vlo[s]);
-        }
-    }
-
-    // y: instruction i of a stage covers tokens 8i .. 8i+7 of the block, 128 bytes (64 features) each
+    // Start of a tile: one chain of dependent loads, descriptor -> tokens -> data.  All three token loads go out
+    // together, and everything that hangs on them (v, then the first four stages of y) is requested before any of
+    // it is waited for; the first slab of Bt depends on the descriptor alone and goes out first of all.
+    const int vrow = blk * 16 + m;
+    const bool vrow_ok = active && vrow < tile.nrows;
     const int yl_row = lane >> 3, yl_c = lane & 7;
-    bf16_t* ybase[2];
     int y_ok = 0;
+    int tok_v, tok_y[2];
+    tok_v = perm[tile.row0 + (vrow_ok ? vrow : 0)];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int rr = blk * 16 + 8 * i + yl_row;
         const bool ok = active && rr < tile.nrows;
         y_ok |= (int)ok << i;
-        ybase[i] = y + (int64_t)perm[tile.row0 + (ok ? rr : 0)] * ldy + tile.c0 + fw * 64 + yl_c * 8;
+        tok_y[i] = perm[tile.row0 + (ok ? rr : 0)];
     }
-    const int y_n0 = tile.c0 + fw * 64 + yl_c * 8;           // first feature of this lane's 8 in stage 0
-    auto load_y = [&](int s, int i) {
-        const bool ok = ((y_ok >> i) & 1) && y_n0 + s * (FW * 64) < n_end && beta != 0.f;
-        return ld16_stream(ok ? ybase[i] + s * (FW * 64) : zeros);
-    };
 
     // slab staging: unit q = feature row (q / RC) of the stage, 16-byte column q % RC
     const bf16_t* bsrc[NLD];
@@ -333,6 +303,67 @@ __device__ __forceinline__ void expand_stream_tile(
 #pragma unroll
         for (int i = 0; i < NLD; ++i) lds[buf * SLAB + bslot[i]] = rb[i];
     };
+    uint4 rb0[NLD], rb1[NLD];
+    load_b(0, rb1);
+
+    // y: instruction i of a stage covers tokens 8i .. 8i+7 of the block, 128 bytes (64 features) each
+    bf16_t* ybase[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) ybase[i] = y + (int64_t)tok_y[i] * ldy + tile.c0 + fw * 64 + yl_c * 8;
+    const int y_n0 = tile.c0 + fw * 64 + yl_c * 8;           // first feature of this lane's 8 in stage 0
+    auto load_y = [&](int s, int i) {
+        const bool ok = ((y_ok >> i) & 1) && y_n0 + s * (FW * 64) < n_end && beta != 0.f;
+        return ld16_stream(ok ? ybase[i] + s * (FW * 64) : zeros);
+    };
+    uint4 yr0[2], yr1[2], yr2[2], yr3[2];
+
+    // v operands (MFMA columns = tokens): lane holds v[token m][32 s + 8 g .. +7] (rows, ranks and parts
+    // that do not exist read the block of zeros)
+    op16 vhi[KS], vlo[KS];
+    {
+        const float* zf = reinterpret_cast<const float*>(zeros);
+        constexpr int SB = KS;                         // (all steps at once: 128 registers at rank 128, which fit)
+#pragma unroll
+        for (int s0 = 0; s0 < KS; s0 += SB) {
+            float4 pa[SB][4], pb[SB][4];
+#pragma unroll
+            for (int ss = 0; ss < SB; ++ss) {
+                const int j = (s0 + ss) * 32 + g * 8;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float* vq = (vrow_ok && j < r && q < vsp.P) ? v + q * vsp.part + (int64_t)tok_v * vsp.R + j : zf;
+                    pa[ss][q] = *reinterpret_cast<const float4*>(vq);
+                    pb[ss][q] = *reinterpret_cast<const float4*>(vq + 4);
+                }
+            }
+            if (s0 + SB >= KS) {
+                // behind the last of v: loads return in order, so the wait for v does not wait for these, and stage 0
+                // starts as soon as its own y has arrived
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) yr0[i] = load_y(0, i);
+                load_b(1, rb0);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) yr1[i] = load_y(1, i);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) yr2[i] = load_y(2, i);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) yr3[i] = load_y(3, i);
+                __builtin_amdgcn_sched_barrier(0);         // (the compiler would sink them below the wait for v)
+            }
+#pragma unroll
+            for (int ss = 0; ss < SB; ++ss) {
+                const float4 (&a)[4] = pa[ss];
+                const float4 (&b)[4] = pb[ss];
+                float f[8];
+                f[0] = ((a[0].x + a[1].x) + a[2].x) + a[3].x; f[1] = ((a[0].y + a[1].y) + a[2].y) + a[3].y;
+                f[2] = ((a[0].z + a[1].z) + a[2].z) + a[3].z; f[3] = ((a[0].w + a[1].w) + a[2].w) + a[3].w;
+                f[4] = ((b[0].x + b[1].x) + b[2].x) + b[3].x; f[5] = ((b[0].y + b[1].y) + b[2].y) + b[3].y;
+                f[6] = ((b[0].z + b[1].z) + b[2].z) + b[3].z; f[7] = ((b[0].w + b[1].w) + b[2].w) + b[3].w;
+                split_bf16(f, vhi[s0 + ss], vlo[s0 + ss]);
+            }
+        }
+    }
 
     float* patch = reinterpret_cast<float*>(lds + 2 * SLAB) + wave * (16 * PROW);
     // one stage: MFMA rows = features (row 4q+i of block b stands for feature 16q+4b+i of the chunk, so
@@ -375,20 +406,8 @@ __device__ __forceinline__ void expand_stream_tile(
         __builtin_amdgcn_wave_barrier();
     };
 
-    uint4 rb0[NLD], rb1[NLD];
-    uint4 yr0[2], yr1[2], yr2[2], yr3[2];
-    load_b(0, rb0);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) yr0[i] = load_y(0, i);
-    store_b(0, rb0);
-    load_b(1, rb0);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) yr1[i] = load_y(1, i);
+    store_b(0, rb1);
     load_b(2, rb1);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) yr2[i] = load_y(2, i);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) yr3[i] = load_y(3, i);
     __syncthreads();
     // stage s multiplies from slab buffer s%2; the slab of stage s+1 (in registers since two stages ago)
     // goes to the other buffer, and the slab of stage s+3 is requested.  Stages past the last one work

@@ -436,6 +436,31 @@ const char* lora_kernel_name(int32_t kernel_id);
 int32_t     lora_kernel_count(void);
 
 /*
+ * lora_trace_set -- phase time stamps of lora_delta's single launch, for diagnosis (the paper attributes the
+ * operator's cost to kernel context operations and under-used cores, section 3.2; the stamps show where the time
+ * of a launch goes on this machine).  While a buffer is set, lora_delta runs the instrumented build of its
+ * single-launch kernel (plans whose view says so; every other path ignores the buffer): same arithmetic, same
+ * results, a few stores and two extra waits per workgroup slower.  Thread 0 of workgroup b writes 8 int64 values at
+ * device_buffer[8 b ..], ticks of the device's constant-rate wall clock (hipDeviceAttributeWallClockRate, kHz);
+ * workgroups 0 .. num_shrink_tiles-1 are the plan's shrink tiles in list order, the expand tiles follow:
+ *   shrink tile: [0] start  [1] descriptor, tokens and adapter pointer arrived  [2] v stores issued (first
+ *                wavefront)  [3] every thread's v stores acknowledged  [4] the group's count added  [5], [7] unused
+ *   expand tile: [0] start  [1] as above  [2] first Bt / y loads requested  [3] the group's count seen, or the
+ *                bounded wait given up  [4] the tile's rows of v in LDS  [5] first wavefront's y stores
+ *                acknowledged (left alone if that wavefront had no columns)  [7] 1 if the count was seen, 0 if
+ *                the tile recomputed v itself
+ *   both:        [6] where the workgroup ran: XCD number << 32 | the wavefront's hardware id register (compute
+ *                unit in bits 8..11, shader array in bit 12, shader engine in bits 13..15)
+ * device_buffer: device memory, 8-byte aligned, owned by the caller, who also clears it; it must hold 64 bytes per
+ * tile of every plan used while it is set (lora_delta returns LORA_ERR_WORKSPACE otherwise and launches nothing).
+ * NULL switches tracing off.  Process-wide; not for use while another thread launches.
+ * Returns LORA_ERR_INVALID_ARG for a misaligned buffer or bytes == 0.
+ */
+lora_status lora_trace_set(void* device_buffer, size_t bytes);
+/* rate of the clock the stamps count, in kHz, on the current device; 0 if it cannot be read */
+int32_t     lora_trace_tick_khz(void);
+
+/*
  * lora_probe -- measured ceilings of the machine, for benchmark reports (the per-kernel timers above time them
  * like any kernel of the library).  buffer: device memory, 16-byte aligned, `bytes` long.
  *   LORA_PROBE_EMPTY  a launch of 1280 workgroups (iters > 1: of iters workgroups) of 256 threads that does nothing:

@@ -117,6 +117,9 @@ _lib.lora_tuning_table_get.restype = ctypes.c_int32
 _lib.lora_tuning_table_get.argtypes = [ctypes.POINTER(TuningEntry), ctypes.c_int32]
 _lib.lora_probe.restype = ctypes.c_int
 _lib.lora_probe.argtypes = [ctypes.c_int32, _vp, ctypes.c_size_t, ctypes.c_int32, _vp]
+_lib.lora_trace_tick_khz.restype = ctypes.c_int32
+_lib.lora_trace_set.restype = ctypes.c_int
+_lib.lora_trace_set.argtypes = [_vp, ctypes.c_size_t]
 _lib.lora_timing_begin.restype = ctypes.c_int
 _lib.lora_timing_end.restype = ctypes.c_int
 _lib.lora_timing_read.restype = ctypes.c_int
@@ -130,7 +133,7 @@ EXPORTED = ["lora_timing_begin", "lora_timing_end", "lora_timing_read", "lora_ke
             "lora_plan_create", "lora_plan_destroy", "lora_plan_query", "lora_plan_export",
             "lora_plan_upload", "lora_shrink", "lora_expand", "lora_delta", "lora_delta_static", "lora_base_gemm",
             "lora_fused_forward", "lora_merge", "lora_status_str", "lora_tuning_set", "lora_tuning_get",
-            "lora_tuning_table_set", "lora_tuning_table_get", "lora_probe"]
+            "lora_tuning_table_set", "lora_tuning_table_get", "lora_probe", "lora_trace_set", "lora_trace_tick_khz"]
 
 TUNING_FIELDS = ["shrink_waves", "shrink_tb2_min_rows", "shrink_max_jb", "expand_wave_bytes",
                  "expand_tb2_min_rows", "expand_tb4_min_rows", "tiled_min_tokens",
@@ -218,6 +221,18 @@ LORA_PROBE_EMPTY, LORA_PROBE_READ, LORA_PROBE_MFMA = 0, 1, 2
 
 def lora_probe(kind: int, buffer, nbytes: int, iters: int = 1, stream=None):
     _check(_lib.lora_probe(int(kind), _ptr(buffer), int(nbytes), int(iters), _stream(stream)), "lora_probe")
+
+
+def lora_trace_set(buffer=None):
+    """buffer: an int64 device tensor with 8 entries per tile of the plans used while it is set; None switches off"""
+    if buffer is None:
+        _check(_lib.lora_trace_set(None, 0), "lora_trace_set")
+    else:
+        _check(_lib.lora_trace_set(_ptr(buffer), buffer.numel() * buffer.element_size()), "lora_trace_set")
+
+
+def lora_trace_tick_khz() -> int:
+    return int(_lib.lora_trace_tick_khz())
 
 
 def lora_timing_begin():

@@ -319,7 +319,11 @@ static lora_status delta_own(lora_plan* p, const void* x, int64_t ldx,
         hipStream_t stream = static_cast<hipStream_t>(hip_stream);
         lora_status st = ensure_uploaded(p, stream);
         if (st != LORA_OK) return st;
-        const hipError_t e = launch_delta_fused_small(p, tables_of(p), x, ldx, d_At_ptrs, d_Bt_ptrs, v, y, ldy, beta, stream);
+        size_t trace_bytes = 0;
+        long long* trace = lora_trace_buffer(&trace_bytes);
+        const hipError_t e = launch_delta_fused_small(p, tables_of(p), x, ldx, d_At_ptrs, d_Bt_ptrs, v, y, ldy, beta, stream,
+                                                      trace, trace_bytes);
+        if (e == hipErrorInvalidValue && trace != nullptr) return LORA_ERR_WORKSPACE;   // the trace buffer is too small
         return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;
     }
     lora_status st = shrink_own(p, x, ldx, d_At_ptrs, v, hip_stream);

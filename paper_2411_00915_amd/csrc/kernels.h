@@ -57,10 +57,12 @@ hipError_t launch_shrink_stream(const lora_plan* p, const lora_dev_tables& d, co
 hipError_t launch_expand_stream(const lora_plan* p, const lora_dev_tables& d, const float* v,
                                 const void* const* Bt, void* y, int64_t ldy, float beta, hipStream_t stream);
 
-// both steps in one launch (decode regime: every tile small); same layout demands as the tiled family
+// both steps in one launch (decode regime: every tile small); same layout demands as the tiled family.
+// trace != nullptr: the instrumented build, which leaves 8 time stamps per workgroup there (lora_trace_set);
+// hipErrorInvalidValue if trace_bytes does not hold them
 hipError_t launch_delta_fused_small(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
                                     const void* const* At, const void* const* Bt, float* v, void* y, int64_t ldy,
-                                    float beta, hipStream_t stream);
+                                    float beta, hipStream_t stream, long long* trace = nullptr, size_t trace_bytes = 0);
 
 // mixture mode: the second batch (every token that is not the merged adapter's, with that adapter and the negated
 // scale) whose delta the fused GEMM folds in besides the tokens' own; plan == nullptr: none

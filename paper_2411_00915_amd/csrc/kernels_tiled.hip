@@ -532,12 +532,21 @@ __device__ __forceinline__ unsigned long long ld_agent(const unsigned long long*
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Phase time stamps of the instrumented build of the single-launch kernel (stamps == nullptr in the ordinary one,
+// which the compiler then drops): thread 0 of a workgroup writes the device's constant-rate wall clock into
+// slot k of the workgroup's record.
+__device__ __forceinline__ void stamp(long long* stamps, int k)
+{
+    if (stamps != nullptr && threadIdx.x == 0) stamps[k] = (long long)wall_clock64();
+}
+
 template <int KS>
 __device__ __forceinline__ void fused_expand_item(
     const lora_tile tile, const tile_rows16& rows, const float* __restrict__ scale,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* __restrict__ At, int K,
     const float* v, lora_vspec vsp, const bf16_t* __restrict__ Bt, bf16_t* __restrict__ y, int64_t ldy, int N,
-    float beta, lora_sync_slot* sync, long long wait_ticks, int delay, float* vt, int* flag, const int* row_tok)
+    float beta, lora_sync_slot* sync, long long wait_ticks, int delay, float* vt, int* flag, const int* row_tok,
+    long long* stamps)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
@@ -590,6 +599,7 @@ __device__ __forceinline__ void fused_expand_item(
         load_b(c_begin, bop);
         load_y(c_begin, yin);
     }
+    stamp(stamps, 2);                                        // first Bt / y loads requested
 
     // ---- wait for the group's shrink tiles (bounded) -----------------------
     if (threadIdx.x == 0) {
@@ -602,6 +612,10 @@ __device__ __forceinline__ void fused_expand_item(
             __builtin_amdgcn_s_sleep(2);
         }
         *flag = ok;
+        if (stamps != nullptr) {
+            stamps[3] = (long long)wall_clock64();           // the group's count seen (or the wait given up)
+            stamps[7] = ok;
+        }
     }
     __syncthreads();
     const bool published = *flag != 0;
@@ -652,6 +666,7 @@ __device__ __forceinline__ void fused_expand_item(
         }
     }
     __syncthreads();
+    stamp(stamps, 4);                                        // the tile's rows of v are in LDS
     // this tile no longer needs the group's counters: count it as through (also when it
     // recomputed v itself, so that the launch arithmetic above stays exact)
     if (threadIdx.x == 0) __hip_atomic_fetch_add(&slot->cons, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -712,22 +727,36 @@ __device__ __forceinline__ void fused_expand_item(
             load_y(c + 1, yin);
         }
     }
+    if (stamps != nullptr) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        stamp(stamps, 5);                                    // the first wavefront's stores of y acknowledged
+    }
 }
 
 // (five wavefronts per SIMD: the whole launch of a decode batch is then resident at once, expand blocks
 // included, so none of them starts its chain of loads only after a shrink block has retired)
+// TRACE: the instrumented build (lora_trace_set): every workgroup leaves time stamps of its phases in trace[8 b ..]
+template <bool TRACE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) void delta_fused_small_kernel(
     const lora_tile* __restrict__ shrink_tiles, int n_shrink, const lora_tile* __restrict__ expand_tiles,
     const int32_t* __restrict__ shrink_rows, const int32_t* __restrict__ expand_rows, const float* __restrict__ scale,
     const bf16_t* __restrict__ x, int64_t ldx, const bf16_t* const* __restrict__ At_ptrs, int K,
     float* v, lora_vspec vsp, const bf16_t* const* __restrict__ Bt_ptrs,
     bf16_t* __restrict__ y, int64_t ldy, int N, float beta, lora_sync_slot* sync, long long wait_ticks, int delay,
-    int n_adapters)
+    int resident, long long* trace)
 {
     __shared__ floatx4 lds[4 * 2 * 64];      // 8 KB: shrink reduction buffer, or v rows [16][64] of an expand tile
     __shared__ uint4 patches[4 * 256];       // 16 KB: one 4 KB patch per wavefront (whole-line loads -> MFMA operands)
     __shared__ int flag;
     const int b = blockIdx.x;
+    long long* stamps = TRACE ? trace + (int64_t)b * 8 : nullptr;
+    stamp(stamps, 0);                                        // start
+    if (TRACE && threadIdx.x == 0) {                         // where the workgroup runs: XCD, and the hardware id register
+        unsigned int xcc, hw;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+        stamps[6] = (long long)(((unsigned long long)(xcc & 15u) << 32) | hw);
+    }
     // A workgroup's chain of dependent loads is descriptor / tokens -> adapter pointer -> data, and the first two
     // steps go through the scalar cache: descriptor and tokens at addresses that depend on the workgroup index
     // alone, the pointer at one that depends on the descriptor.  (Fetching tokens and a per-lane copy of the
@@ -742,6 +771,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
         const lora_tile tile = shrink_tiles[b];
         const bf16_t* At = At_ptrs[tile.adapter];
         rows.park(t16, nullptr);
+        stamp(stamps, 1);                                    // descriptor, tokens and adapter pointer have arrived
         const int jb = (tile.shape >> 4) & 15;
         uint4* patch = patches + (threadIdx.x >> 6) * 256;
         if (jb == 1) shrink_tile<1, 1, 8, true, const tile_rows16&>(tile, rows, x, ldx, At, K, v, vsp, lds, patch);
@@ -754,31 +784,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
         // loads are served).  A reader that has seen the count and then issues agent-scope loads of v gets
         // the published values.  (A release fence at agent scope would also write back the whole L2, which
         // holds the expand blocks' y stores: microseconds per block.)
+        stamp(stamps, 2);                                    // v stores issued (first wavefront)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        stamp(stamps, 3);                                    // every thread's v stores acknowledged
         if (threadIdx.x == 0)
             __hip_atomic_fetch_add(&sync[(unsigned int)tile.shape >> 16].done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (TRACE) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            stamp(stamps, 4);                                // the count has been added
+        }
     } else {
         const lora_tile tile = expand_tiles[b - n_shrink];
         const bf16_t* Bt = Bt_ptrs[tile.adapter];
         const bf16_t* At = At_ptrs[tile.adapter];        // only the bounded-wait fallback reads it
         int* row_tok = reinterpret_cast<int*>(patches);  // an expand workgroup stages nothing through the patches
         rows.park(t16, row_tok);
+        stamp(stamps, 1);
+        // The head start is for the workgroups that begin together with the shrink tiles.  Workgroups start in index
+        // order; one beyond what the device holds at a time begins when an earlier one has ended, microseconds into
+        // the launch: it does not wait on top of that.
+        if (b >= resident) delay = 0;
         if (tile.reserved0 <= 32)
             fused_expand_item<1>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, wait_ticks, delay,
-                                 reinterpret_cast<float*>(lds), &flag, row_tok);
+                                 reinterpret_cast<float*>(lds), &flag, row_tok, stamps);
         else
             fused_expand_item<2>(tile, rows, scale, x, ldx, At, K, v, vsp, Bt, y, ldy, N, beta, sync, wait_ticks, delay,
-                                 reinterpret_cast<float*>(lds), &flag, row_tok);
+                                 reinterpret_cast<float*>(lds), &flag, row_tok, stamps);
     }
 }
 
 hipError_t launch_delta_fused_small(const lora_plan* p, const lora_dev_tables& d, const void* x, int64_t ldx,
                                     const void* const* At, const void* const* Bt, float* v, void* y, int64_t ldy,
-                                    float beta, hipStream_t stream)
+                                    float beta, hipStream_t stream, long long* trace, size_t trace_bytes)
 {
     const int S = (int)p->shrink_tiles.size(), E = (int)p->expand_tiles.size();
     if (S + E == 0) return hipSuccess;
+    if (trace != nullptr && trace_bytes < (size_t)(S + E) * 8 * sizeof(long long)) return hipErrorInvalidValue;
     lora_sync_slot* sync = reinterpret_cast<lora_sync_slot*>(d.sync);
     // the bound of the hand-off wait, from microseconds to ticks of the wall clock the kernel reads
     static int wall_khz[64] = {0};
@@ -790,9 +832,20 @@ hipError_t launch_delta_fused_small(const lora_plan* p, const lora_dev_tables& d
         wall_khz[dev] = khz;
     }
     const long long wait_ticks = (long long)p->fused_wait_us * wall_khz[dev] / 1000;
-    LORA_LAUNCH(LORA_K_DELTA_FUSED, delta_fused_small_kernel, dim3(S + E), dim3(256), 0, stream,
-                d.shrink_tiles, S, d.expand_tiles, d.shrink_rows, d.expand_rows, d.scale, (const bf16_t*)x, ldx,
-                (const bf16_t* const*)At, p->K, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N, beta,
-                sync, wait_ticks, p->fused_delay, p->n_a);
+    // workgroups the device holds at a time: five of this kernel's per compute unit (its occupancy attribute)
+    static int resident[64] = {0};
+    if (resident[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        resident[dev] = 5 * cus;
+    }
+#define DELTA_FUSED_LAUNCH(TRACE_)                                                                                      \
+    LORA_LAUNCH(LORA_K_DELTA_FUSED, delta_fused_small_kernel<TRACE_>, dim3(S + E), dim3(256), 0, stream,               \
+                d.shrink_tiles, S, d.expand_tiles, d.shrink_rows, d.expand_rows, d.scale, (const bf16_t*)x, ldx,       \
+                (const bf16_t* const*)At, p->K, v, lora_vspec_of(p), (const bf16_t* const*)Bt, (bf16_t*)y, ldy, p->N,  \
+                beta, sync, wait_ticks, p->fused_delay, resident[dev], trace)
+    if (trace != nullptr) DELTA_FUSED_LAUNCH(true);
+    else DELTA_FUSED_LAUNCH(false);
+#undef DELTA_FUSED_LAUNCH
     return hipGetLastError();
 }

@@ -30,6 +30,9 @@ enum lora_kernel_id {
     LORA_K_COUNT
 };
 
+// buffer given to lora_trace_set (nullptr: none)
+long long* lora_trace_buffer(size_t* bytes);
+
 bool lora_timing_on();
 // hands out an event pair and remembers it under kernel_id; false if none could be made
 bool lora_timing_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop);

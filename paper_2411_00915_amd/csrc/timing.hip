@@ -1,4 +1,5 @@
 // Per-kernel timing facility behind lora_timing_begin / _end / _read.
+#include <cstdint>
 #include <mutex>
 #include <vector>
 
@@ -18,7 +19,35 @@ const char* kNames[LORA_K_COUNT] = {"shrink_general_kernel", "expand_general_ker
                                     "gemm_tiled_kernel<delta>", "delta_fused_small_kernel", "v_split_kernel",
                                     "shrink_stream_kernel", "expand_stream_kernel", "merge_kernel",
                                     "gemm_ring_kernel", "gemm_ring_kernel<delta>", "clear_words_kernel", "probe_empty_kernel", "probe_read_kernel", "probe_mfma_kernel"};
+long long* g_trace = nullptr;
+size_t g_trace_bytes = 0;
 }  // namespace
+
+long long* lora_trace_buffer(size_t* bytes)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    *bytes = g_trace_bytes;
+    return g_trace;
+}
+
+extern "C" lora_status lora_trace_set(void* device_buffer, size_t bytes)
+{
+    if (device_buffer != nullptr && ((reinterpret_cast<uintptr_t>(device_buffer) & 7) != 0 || bytes == 0)) return LORA_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_trace = static_cast<long long*>(device_buffer);
+    g_trace_bytes = device_buffer ? bytes : 0;
+    return LORA_OK;
+}
+
+extern "C" int32_t lora_trace_tick_khz(void)
+{
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return khz > 0 ? khz : 0;
+}
 
 bool lora_timing_on() { return g_on; }
 

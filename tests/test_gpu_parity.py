@@ -508,6 +508,56 @@ def test_single_launch_delta_large_decode_batch():
     _delta_case(w)
 
 
+def test_traced_single_launch_gives_the_same_result_and_ordered_stamps():
+    # the instrumented build of the single-launch kernel (lora_trace_set): same arithmetic as the ordinary build,
+    # so the same bits in y; every workgroup's stamps are set and in phase order; a buffer that is too small
+    # for the plan is an error and launches nothing
+    w = wl.cfg2(with_w=False)
+    dl = device.to_device(w, DEV, with_w=False)
+    plan = device.make_plan(w)
+    view = B.lora_plan_export(plan)
+    assert (view["expand_tiles"][:, 5] >> 8).any(), "cfg2 is expected to run as one launch"
+    S, E = view["shrink_tiles"].shape[0], view["expand_tiles"].shape[0]
+    _, v_bytes, _ = B.lora_plan_query(plan)
+    v = torch.zeros(v_bytes // 4, dtype=torch.float32, device=DEV)
+    y0 = torch.from_numpy(wl.bf16_bits(wl.round_to_bf16(
+        np.random.default_rng(5).standard_normal((w.T, w.N), dtype=np.float32))).view(np.int16)).to(DEV).view(torch.bfloat16)
+    y_plain, y_traced = y0.clone(), y0.clone()
+    B.lora_delta(plan, dl.x, w.K, dl.At_ptrs, dl.Bt_ptrs, v, y_plain, w.N, 1.0)
+    trace = torch.zeros(S + E, 8, dtype=torch.int64, device=DEV)
+    small = torch.zeros(S + E - 1, 8, dtype=torch.int64, device=DEV)
+    try:
+        B.lora_trace_set(small)
+        with pytest.raises(B.LoraError) as err:
+            B.lora_delta(plan, dl.x, w.K, dl.At_ptrs, dl.Bt_ptrs, v, y_traced, w.N, 1.0)
+        assert err.value.status == B.LORA_ERR_WORKSPACE
+        B.lora_trace_set(trace)
+        B.lora_delta(plan, dl.x, w.K, dl.At_ptrs, dl.Bt_ptrs, v, y_traced, w.N, 1.0)
+    finally:
+        B.lora_trace_set(None)
+    torch.cuda.synchronize()
+    assert torch.equal(y_plain.view(torch.int16), y_traced.view(torch.int16))
+    assert int(small.abs().sum()) == 0
+    t = trace.cpu().numpy()
+    sh, ex = t[:S], t[S:]
+    assert (sh[:, :5] > 0).all() and (np.diff(sh[:, :5], axis=1) >= 0).all()
+    assert (ex[:, :5] > 0).all() and (np.diff(ex[:, :5], axis=1) >= 0).all()
+    done = ex[:, 5] > 0
+    assert done.any() and (ex[done, 5] >= ex[done, 4]).all()
+    assert set(np.unique(ex[:, 7])) <= {0, 1}
+    assert (sh[:, 5] == 0).all() and (sh[:, 7] == 0).all()
+    where = t[:, 6]
+    assert ((where >> 32) < 8).all() and len(np.unique(where >> 32)) == 8, "every XCD takes part in a launch of this size"
+    span_us = (t[:, :6].max() - t[:, 0].min()) * 1e3 / B.lora_trace_tick_khz()
+    assert 1.0 < span_us < 1000.0, span_us                    # one launch of some microseconds
+    # and the ordinary build again afterwards, untouched by the episode
+    y_again = y0.clone()
+    B.lora_delta(plan, dl.x, w.K, dl.At_ptrs, dl.Bt_ptrs, v, y_again, w.N, 1.0)
+    torch.cuda.synchronize()
+    assert torch.equal(y_plain.view(torch.int16), y_again.view(torch.int16))
+    plan.destroy()
+
+
 # ---------------------------------------------------------------- mixture mode (merged adapter + de-LoRA branch)
 def run_mixture_case(w, m, n_sample=None, seed=11, variant=B.LORA_VARIANT_AUTO):
     """Mixture inference (section 4.4.1): adapter m is merged into the base weight (W' = W + s_m A_m B_m, stored in

@@ -293,6 +293,15 @@ def test_library_exports_every_declared_symbol():
     assert names == set(B.EXPORTED)
 
 
+def test_trace_set_checks_its_arguments_without_a_gpu():
+    import ctypes
+    buf = (ctypes.c_int64 * 16)()
+    base = ctypes.addressof(buf)
+    assert B._lib.lora_trace_set(ctypes.c_void_p(base + 4), 64) == B.LORA_ERR_INVALID_ARG      # not 8-byte aligned
+    assert B._lib.lora_trace_set(ctypes.c_void_p(base), 0) == B.LORA_ERR_INVALID_ARG           # no room at all
+    assert B._lib.lora_trace_set(None, 0) == B.LORA_OK                                         # off (the default)
+
+
 def test_shape_table_is_consulted_inside_plan_create():
     """The shape-keyed table (paper section 4.3.2): lora_plan_create looks the batch's class up -- tokens with an
     adapter (smallest entry at or above, else the largest), K, N, rank class, group class -- and plans with the

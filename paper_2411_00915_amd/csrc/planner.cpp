@@ -357,6 +357,45 @@ static void build_tiles(lora_plan* p)
     p->fused_ok = p->shrink_small && p->expand_small && G <= 4096;
     p->fused_wait_us = tu.fused_wait_us - 1;
     p->fused_delay = std::max(0, std::min(tu.fused_delay - 1, 64));
+    // The single launch holds 5 workgroups per compute unit at a time (1280 on the 256 units of an MI355X).  A few
+    // workgroups beyond that start only when earlier ones end, microseconds into a launch that lasts little longer,
+    // and then end it late.  While the launch is over that number by less than a tenth, the expand tiles of the
+    // adapter groups with the least bytes per tile (lowest rank first, then fewest tokens) are joined in pairs
+    // along the features -- they are the cheapest to double.
+    constexpr size_t kResidentWorkgroups = 1280;
+    if (p->fused_ok && p->shrink_tiles.size() + p->expand_tiles.size() > kResidentWorkgroups &&
+        (p->shrink_tiles.size() + p->expand_tiles.size()) * 10 <= kResidentWorkgroups * 11) {
+        std::vector<int> groups((size_t)G);
+        for (int g = 0; g < G; ++g) groups[(size_t)g] = g;
+        std::stable_sort(groups.begin(), groups.end(), [&](int a, int b) {
+            const int32_t ra = p->rank[p->group_adapter[a]], rb = p->rank[p->group_adapter[b]];
+            if (ra != rb) return ra < rb;
+            return p->group_offset[a + 1] - p->group_offset[a] < p->group_offset[b + 1] - p->group_offset[b];
+        });
+        std::vector<char> join((size_t)G, 0);
+        size_t total = p->shrink_tiles.size() + p->expand_tiles.size();
+        std::vector<size_t> tiles_of((size_t)G, 0);
+        for (const lora_tile& t : p->expand_tiles) tiles_of[(size_t)t.reserved1] += 1;
+        for (int g : groups) {
+            if (total <= kResidentWorkgroups) break;
+            join[(size_t)g] = 1;
+            total -= tiles_of[(size_t)g] / 2;
+        }
+        std::vector<lora_tile> joined;
+        joined.reserve(p->expand_tiles.size());
+        for (size_t i = 0; i < p->expand_tiles.size(); ++i) {
+            lora_tile t = p->expand_tiles[i];
+            if (join[(size_t)t.reserved1] && i + 1 < p->expand_tiles.size()) {
+                const lora_tile& n = p->expand_tiles[i + 1];
+                if (n.reserved1 == t.reserved1 && n.row0 == t.row0 && n.c0 == t.c0 + t.cn) {
+                    t.cn += n.cn;
+                    ++i;
+                }
+            }
+            joined.push_back(t);
+        }
+        p->expand_tiles.swap(joined);
+    }
     if (p->fused_ok) {
         std::vector<int32_t> need((size_t)G, 0), ncons((size_t)G, 0);
         for (const lora_tile& t : p->shrink_tiles) need[(size_t)((uint32_t)t.shape >> 16)] += 1;

@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, scaled by a 256 MiB copy; measured in a separate
 # profiler run of this benchmark, not in this run (keyed by workload and kernel; the file holds the figures)
-PROFILED_TRAFFIC = {("cfg2_decode", "delta_fused_small_kernel"): (45.74e6, "profiles/decode_cfg2_hbm_traffic.txt"),
+PROFILED_TRAFFIC = {("cfg2_decode", "delta_fused_small_kernel"): (45.80e6, "profiles/decode_cfg2_hbm_traffic.txt"),
                     ("cfg5_large_attn", "expand_stream_kernel"): (533.80e6, "profiles/prefill_cfg5_shrink_expand_hbm_traffic.txt"),
                     ("cfg5_large_attn", "shrink_stream_kernel"): (332.18e6, "profiles/prefill_cfg5_shrink_expand_hbm_traffic.txt"),
                     ("cfg4_mixed", "expand_stream_kernel"): (487.85e6, "profiles/prefill_cfg4_shrink_expand_hbm_traffic.txt")}

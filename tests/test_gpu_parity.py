@@ -494,7 +494,7 @@ def test_single_launch_delta_small_and_mixed_cases():
         _delta_case(w, fallback=True)
     wf = wl.random_case(410, 33, 40, 48, 3, (4, 8), dtype="f32", max_seg=6, frac_none=0.2)
     _delta_case(wf)
-    # more than 64 adapters (the pointer table no longer fits one wavefront's lanes), and exactly one
+    # more adapters than a wavefront has lanes, and exactly one
     wm = wl.random_case(411, 200, 1024, 320, 150, (8, 16, 32, 64), max_seg=2, scales=(1.0, 2.0))
     _delta_case(wm)
     _delta_case(wm, fallback=True)

@@ -78,7 +78,11 @@
  * fp32) runs through general kernels with no alignment demands, which are one
  * to two orders of magnitude slower per token; padding an adapter's factors
  * with zero rank rows / columns to a multiple of 8 changes no result and moves
- * it onto the tuned kernels.
+ * it onto the tuned kernels.  The rank demands are the expand's (rows of Bt_a
+ * have r elements): lora_shrink alone runs on the tuned kernels for any rank
+ * up to LORA_MAX_RANK when the rest holds (the plan view's
+ * shrink_kernel_family says so) -- the case of task heads of arbitrary width
+ * (section 4.2.2), which are a shrink with rank = number of outputs.
  */
 #ifndef LORA_ABI_H
 #define LORA_ABI_H
@@ -170,7 +174,8 @@ typedef struct {
     int32_t        tuning_source;   /* where this plan's tunables came from: 0 process defaults only, 1 an entry of
                                        the shape table, + 2 if the descriptor gave values of its own */
     int32_t        tuning[LORA_TUNING_COUNT];   /* the tunables this plan was made with (order of lora_tuning_set) */
-    int32_t        reserved;
+    int32_t        shrink_kernel_family;   /* the family lora_shrink runs: TILED also when kernel_family is GENERAL only
+                                              because of ranks the expand kernels cannot take (see ALIGNMENT) */
     const int32_t* token_adapter;   /* [T]  adapter of each token, -1 = none */
     const int32_t* perm;            /* [num_active] tokens with an adapter, stably sorted by adapter */
     const int32_t* group_adapter;   /* [num_groups] ascending adapter ids */

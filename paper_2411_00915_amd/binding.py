@@ -56,7 +56,7 @@ class PlanView(ctypes.Structure):
                 ("num_groups", ctypes.c_int32), ("v_row_stride", ctypes.c_int32),
                 ("kernel_family", ctypes.c_int32), ("shrink_waves", ctypes.c_int32),
                 ("v_parts", ctypes.c_int32), ("tuning_source", ctypes.c_int32),
-                ("tuning", ctypes.c_int32 * LORA_TUNING_COUNT), ("reserved", ctypes.c_int32),
+                ("tuning", ctypes.c_int32 * LORA_TUNING_COUNT), ("shrink_kernel_family", ctypes.c_int32),
                 ("token_adapter", _i32p), ("perm", _i32p), ("group_adapter", _i32p), ("group_offset", _i32p),
                 ("shrink_tiles", ctypes.POINTER(Tile)), ("num_shrink_tiles", ctypes.c_int32),
                 ("expand_tiles", ctypes.POINTER(Tile)), ("num_expand_tiles", ctypes.c_int32),
@@ -333,7 +333,8 @@ def lora_plan_export(plan: Plan) -> dict:
         return raw.reshape(n, 8)
 
     return dict(num_tokens=v.num_tokens, num_active=v.num_active, num_groups=v.num_groups,
-                v_row_stride=v.v_row_stride, kernel_family=v.kernel_family, shrink_waves=v.shrink_waves,
+                v_row_stride=v.v_row_stride, kernel_family=v.kernel_family, shrink_kernel_family=v.shrink_kernel_family,
+                shrink_waves=v.shrink_waves,
                 v_parts=v.v_parts, tuning_source=v.tuning_source,
                 tuning={f: int(v.tuning[j]) for j, f in enumerate(TUNING_FIELDS)},
                 token_adapter=arr(v.token_adapter, v.num_tokens), perm=arr(v.perm, v.num_active),

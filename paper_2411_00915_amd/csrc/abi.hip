@@ -251,7 +251,7 @@ static lora_status shrink_own(lora_plan* p, const void* x, int64_t ldx,
     if (st != LORA_OK) return st;
     const lora_dev_tables d = tables_of(p);
     hipError_t e;
-    if (p->family == LORA_VARIANT_TILED && tiled_call_ok(x, ldx))
+    if ((p->family == LORA_VARIANT_TILED || p->shrink_tiled_only) && tiled_call_ok(x, ldx))
         e = launch_shrink_tiled(p, d, x, ldx, d_At_ptrs, v, stream, vb, split_done);
     else if (p->family == LORA_VARIANT_TILED && p->variant_req == LORA_VARIANT_TILED)
         return LORA_ERR_UNSUPPORTED;                           // tiled kernels were demanded but x is not laid out for them

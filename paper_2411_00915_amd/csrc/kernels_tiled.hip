@@ -208,8 +208,11 @@ __device__ __forceinline__ void shrink_tile(
             __hip_atomic_store(dst + 1, o.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(dst + 2, o.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(dst + 3, o.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
+        } else if (out_j + 4 <= tile.c0 + tile.cn) {
             *reinterpret_cast<float4*>(dst) = o;
+        } else {                                             // the rank is no multiple of 4: the row ends inside this slot
+            const float ov[4] = {o.x, o.y, o.z, o.w};
+            for (int i = 0; out_j + i < tile.c0 + tile.cn; ++i) dst[i] = ov[i];
         }
     }
 }

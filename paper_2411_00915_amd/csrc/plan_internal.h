@@ -67,6 +67,8 @@ struct lora_plan {
     std::vector<int32_t> order, extra_ptr128, extra128, extra_ptr256, extra256;
     std::vector<int32_t> shrink_rows, expand_rows;   // single-launch decode kernel: 16 tokens per tile, padded
     bool tiled_layout_ok = false;  // K and all active ranks multiples of 8
+    bool shrink_tiled_only = false; // family GENERAL, but the shrink has tiles and runs on the MFMA kernels (ranks that
+                                    // only the expand cannot take: not multiples of 8, or above 128)
     // fused GEMM: what a row is matched against an adapter stage by: its adapter in bits 0..22 (all ones: none),
     // bit 23 set when the removal of the merged adapter applies to it
     std::vector<int32_t> row_key;

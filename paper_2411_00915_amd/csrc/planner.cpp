@@ -164,7 +164,9 @@ static int32_t round_up(int32_t v, int32_t m) { return (v + m - 1) / m * m; }
 // adapter times 16*JB of its rank indices over the whole K range (the
 // workgroup's wavefronts split K).  An expand tile is 16*TB tokens times a range
 // of output features that the workgroup's four wavefronts split evenly.
-static void build_tiles(lora_plan* p)
+// shrink_only: tiles for the shrink alone (ranks the expand kernels cannot take), for the kernels that tile the rank
+// axis in blocks of 16 rows -- no streaming, no single launch.
+static void build_tiles(lora_plan* p, bool shrink_only = false)
 {
     const lora_tuning& tu = p->tuning;
     p->shrink_max_blocks = 1;
@@ -190,6 +192,7 @@ static void build_tiles(lora_plan* p)
     p->shrink_stream = max_rank <= 128 && p->K >= 1024 &&
                        (active >= tu.shrink_stream_min_tokens ||
                         (tu.shrink_stream_min_tokens < (1 << 30) && !small_tiles_only && (max_group >= 64 || active >= 128)));
+    if (shrink_only) p->shrink_stream = false;
     p->expand_stream = p->shrink_stream && p->N >= 64;
     p->expand_stream_ks = 1;
     p->expand_stream_lds = 0;
@@ -267,7 +270,9 @@ static void build_tiles(lora_plan* p)
         // ---- expand, prefill-sized batches: streaming tiles, the same token ranges as the streaming shrink;
         // with fewer than 8 token blocks the wavefronts also spread over FW 64-feature chunks per stage
         // (as far as the slab of Bt rows, 64 FW x 32 KS ranks, stays within 32 KB)
-        if (p->expand_stream) {
+        if (shrink_only) {
+            p->expand_small = false;
+        } else if (p->expand_stream) {
             const int ks = r <= 32 ? 1 : (r <= 64 ? 2 : 4);
             const int fw_max = 8 / ks;
             for (int32_t row = lo; row < hi; row += expand_tokens) {
@@ -607,6 +612,16 @@ static lora_status create_plain(const lora_batch_desc* d, int32_t merged, lora_p
         else
             p->family = (n_active >= p->tuning.tiled_min_tokens) ? LORA_VARIANT_TILED : LORA_VARIANT_GENERAL;
         if (p->family == LORA_VARIANT_TILED) build_tiles(p);
+        // Ranks that only the expand kernels cannot take (not multiples of 8: rows of Bt_a would not be 16-byte
+        // aligned; above 128): the shrink still runs on the MFMA kernels, which tile the rank axis in blocks of 16
+        // rows of At_a and mask what they store.  That is also the path of task heads, whose widths are arbitrary.
+        p->shrink_tiled_only = false;
+        if (p->family == LORA_VARIANT_GENERAL && !p->tiled_layout_ok && p->variant_req != LORA_VARIANT_GENERAL &&
+            p->dtype == LORA_BF16 && p->K % 8 == 0 && max_rank <= LORA_MAX_RANK &&
+            (p->variant_req == LORA_VARIANT_TILED || n_active >= p->tuning.tiled_min_tokens)) {
+            build_tiles(p, true);
+            p->shrink_tiled_only = !p->shrink_tiles.empty();
+        }
         // (in mixture mode the removal's v must have the layout the GEMM's stages read, too)
         if (p->tiled_layout_ok && p->n_a < LORA_UNMERGE_BIT && (!unmerge || unmerge->tiled_layout_ok)) build_gemm_tables(p);
     } catch (const std::bad_alloc&) {
@@ -686,11 +701,11 @@ extern "C" lora_status lora_plan_export(const lora_plan* p, lora_plan_view* v)
     v->num_groups = (int32_t)p->group_adapter.size();
     v->v_row_stride = p->R;
     v->kernel_family = p->family;
+    v->shrink_kernel_family = (p->family == LORA_VARIANT_TILED || p->shrink_tiled_only) ? LORA_VARIANT_TILED : LORA_VARIANT_GENERAL;
     v->shrink_waves = p->shrink_waves;
     v->v_parts = p->v_parts;
     v->tuning_source = p->tuning_source;
     std::memcpy(v->tuning, &p->tuning, sizeof(p->tuning));
-    v->reserved = 0;
     v->token_adapter = p->token_adapter.data();
     v->perm = p->perm.data();
     v->group_adapter = p->group_adapter.data();

@@ -131,8 +131,10 @@ static void check_plan(const batch& b)
         }
     REQUIRE(g == v.num_groups && v.group_offset[g] == (int32_t)perm.size());
 
-    if (v.kernel_family == LORA_VARIANT_TILED) {
-        // exactly-once cover: shrink tiles over (token, rank index) per K part, expand tiles over (token, feature)
+    REQUIRE(v.shrink_kernel_family == LORA_VARIANT_TILED || v.kernel_family != LORA_VARIANT_TILED);
+    if (v.shrink_kernel_family == LORA_VARIANT_TILED) {
+        // exactly-once cover: shrink tiles over (token, rank index) per K part, expand tiles over (token, feature);
+        // a plan whose shrink alone is tiled has no expand tiles
         const int32_t P = v.v_parts;
         REQUIRE(P == 1 || P == 2 || P == 4 || P == 8);
         // K parts per adapter (bits 12..15 of a shrink tile's shape): the same on every tile of the adapter, <= P
@@ -159,6 +161,7 @@ static void check_plan(const batch& b)
             for (size_t i = 0; i < perm.size(); ++i)
                 for (int32_t c : canvas[i]) REQUIRE(c == (part < parts_of.at(tok[perm[i]]) ? 1 : 0));
         }
+        if (v.kernel_family != LORA_VARIANT_TILED) REQUIRE(v.num_expand_tiles == 0);
         std::vector<std::vector<int32_t>> canvas(perm.size(), std::vector<int32_t>((size_t)b.N, 0));
         for (int32_t i = 0; i < v.num_expand_tiles; ++i) {
             const lora_tile& t = v.expand_tiles[i];
@@ -170,7 +173,7 @@ static void check_plan(const batch& b)
             }
         }
         for (auto& row : canvas)
-            for (int32_t c : row) REQUIRE(c == 1);
+            for (int32_t c : row) REQUIRE(c == (v.kernel_family == LORA_VARIANT_TILED ? 1 : 0));
     } else {
         REQUIRE(v.num_shrink_tiles == 0 && v.num_expand_tiles == 0);
     }

@@ -761,8 +761,8 @@ def test_vision_task_heads_batched_through_the_shrink():
     # Vision task heads (paper section 4.2.2): a linear layer per adapter that maps the final feature of a
     # request's last token to C_a task outputs; heads of different width run in one batch.  In this library
     # that is the shrink with "rank" = C_a, Ht_a stored [C_a, K] like At_a, and scale 1: logits land in v.
-    for seed, (classes, variant) in enumerate([((2, 5, 10, 101, 174, 256), B.LORA_VARIANT_AUTO),     # general kernels
-                                               ((8, 16, 24, 64, 128), B.LORA_VARIANT_TILED)]):      # MFMA kernels
+    for seed, (classes, variant) in enumerate([((2, 5, 10, 101, 174, 256), B.LORA_VARIANT_AUTO),     # shrink alone tiled
+                                               ((8, 16, 24, 64, 128), B.LORA_VARIANT_TILED)]):      # everything tiled
         w = wl.random_case(900 + seed, 96, 4096, 64, len(classes), classes, max_seg=1, frac_none=0.1,
                            scales=(1.0,), with_w=False)
         w.adapter_rank = np.asarray(classes, dtype=np.int32)         # one head of every width
@@ -772,7 +772,10 @@ def test_vision_task_heads_batched_through_the_shrink():
         dl = device.to_device(w, DEV, with_w=False)
         plan = device.make_plan(w, variant)
         R, v_bytes, _ = B.lora_plan_query(plan)
-        P = B.lora_plan_export(plan)["v_parts"]
+        view = B.lora_plan_export(plan)
+        # widths of any kind run on the MFMA shrink (the rank demands of the tuned kernels are the expand's)
+        assert view["shrink_kernel_family"] == B.LORA_VARIANT_TILED and view["shrink_tiles"].shape[0] > 0
+        P = view["v_parts"]
         v = torch.full((P, w.T, R), -12345.0, dtype=torch.float32, device=DEV)
         B.lora_shrink(plan, dl.x, w.K, dl.At_ptrs, v)
         torch.cuda.synchronize()

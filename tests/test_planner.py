@@ -48,8 +48,10 @@ def _check_gemm_tables(w, v, tok, perm):
 
 
 def _check_tiles(w, v, tok, perm):
-    if v["kernel_family"] != B.LORA_VARIANT_TILED:
-        assert v["shrink_tiles"].shape[0] == 0 and v["expand_tiles"].shape[0] == 0
+    both = v["kernel_family"] == B.LORA_VARIANT_TILED
+    assert both or v["expand_tiles"].shape[0] == 0
+    if v["shrink_kernel_family"] != B.LORA_VARIANT_TILED:          # (it is TILED whenever kernel_family is)
+        assert not both and v["shrink_tiles"].shape[0] == 0
         return
     max_r = int(w.adapter_rank.max()) if w.num_adapters else 0
     P = v["v_parts"]
@@ -60,7 +62,8 @@ def _check_tiles(w, v, tok, perm):
             st_ = [(t[0], t[1], t[2], t[3], t[4]) for t in v["shrink_tiles"] if (t[5] >> 8) & 15 == part]
             plan_ref.check_cover(st_, tok, perm, max(max_r, 1), adapter_rank=w.adapter_rank, rank_axis=True)
         assert all((t[5] >> 12) & 15 == P and (t[5] >> 8) & 15 < P for t in v["shrink_tiles"])
-        plan_ref.check_cover(et_, tok, perm, w.N)
+        if both:
+            plan_ref.check_cover(et_, tok, perm, w.N)
     else:
         assert v["shrink_tiles"].shape[0] == 0 and not et_
     for t in v["shrink_tiles"]:
@@ -151,7 +154,8 @@ def test_config_tables_bit_exact(name):
 
 @settings(max_examples=150, deadline=None)
 @given(st.lists(st.tuples(st.integers(0, 40), st.integers(-1, 5)), min_size=0, max_size=20),
-       st.lists(st.sampled_from([0, 8, 16, 24, 32, 64, 128]), min_size=6, max_size=6),
+       st.lists(st.sampled_from([0, 8, 16, 24, 32, 64, 128]), min_size=6, max_size=6) |
+       st.lists(st.sampled_from([0, 3, 8, 20, 100, 129, 256]), min_size=6, max_size=6),     # also ranks only the shrink tiles
        st.sampled_from([64, 200, 1000]))
 def test_random_tables_and_tiles(segs, ranks, N):
     lengths = [s[0] for s in segs]
@@ -176,15 +180,24 @@ def test_plan_is_deterministic():
 
 def test_unaligned_layouts_take_general_kernels():
     base = dict(seed=1, T=10, N=32, n_a=2, with_w=False)
-    w = wl.random_case(K=36, ranks=(8,), **base)           # K not a multiple of 8
-    assert _export(w)[0]["kernel_family"] == B.LORA_VARIANT_GENERAL
-    w = wl.random_case(K=64, ranks=(5,), **base)           # rank not a multiple of 8
-    assert _export(w, B.LORA_VARIANT_TILED)[0]["kernel_family"] == B.LORA_VARIANT_GENERAL
-    w = wl.random_case(K=64, ranks=(256,), **base)         # rank beyond the tiled kernels
-    assert _export(w)[0]["kernel_family"] == B.LORA_VARIANT_GENERAL
+    G, T_ = B.LORA_VARIANT_GENERAL, B.LORA_VARIANT_TILED
+    fam = lambda v: (v["kernel_family"], v["shrink_kernel_family"])
+    w = wl.random_case(K=36, ranks=(8,), **base)           # K not a multiple of 8: nothing is tiled
+    assert fam(_export(w)[0]) == (G, G)
+    # ranks that only the expand cannot take: the shrink alone keeps the MFMA kernels (tiles for it, none for the expand)
+    for ranks in ((5,), (256,), (3, 12, 100, 174)):
+        w = wl.random_case(K=64, ranks=ranks, **base)
+        for variant in (B.LORA_VARIANT_AUTO, T_):
+            v = _export(w, variant)[0]
+            assert fam(v) == (G, T_) and v["shrink_tiles"].shape[0] > 0 and v["expand_tiles"].shape[0] == 0
+            tok, perm = _check_tables(w, v)
+            _check_tiles(w, v, tok, perm)
+        assert fam(_export(w, G)[0]) == (G, G)
+    wf = wl.random_case(K=64, ranks=(5,), dtype="f32", **base)
+    assert fam(_export(wf)[0]) == (G, G)                    # fp32: general throughout
     w = wl.random_case(K=64, ranks=(8,), **base)
-    assert _export(w, B.LORA_VARIANT_GENERAL)[0]["kernel_family"] == B.LORA_VARIANT_GENERAL
-    assert _export(w)[0]["kernel_family"] == B.LORA_VARIANT_TILED
+    assert fam(_export(w, G)[0]) == (G, G)
+    assert fam(_export(w)[0]) == (T_, T_)
 
 
 def _desc(T=4, indptr=(0, 2, 4), seg_ad=(0, 1), ranks=(8, 16), scales=(1.0, 2.0), k=64, n=64,

@@ -316,6 +316,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(
     int s = 0;
     const bool steady = WB == 4 && !KTAIL && stages_k >= 3 && n_extra <= META_MAX;
     if (!steady) {
+        // (the adapter stages' descriptors in LDS are read by every thread: with a single K stage the load of
+        // stage 1 below is already an adapter stage's)
+        if constexpr (DELTA) __syncthreads();
         load_stage(0);
         store_stage(0);
         if (stages > 1) load_stage(1);

@@ -307,6 +307,18 @@ def test_ragged_small_cases(variant):
         run_forward_case(w, variant=variant)
 
 
+def test_fused_forward_with_a_single_k_stage():
+    # K of at most 64 is one stage of the register-staged GEMM: the first stage fetched ahead is then already an
+    # adapter stage, whose descriptors every thread reads from LDS (a missing barrier there once let a workgroup read
+    # them before they were written; found by a random sweep).  Several row tiles, many adapters per tile, plain and
+    # mixture mode, different batches back to back.
+    for seed, (T, K, N, n_a, ranks) in enumerate([(700, 64, 200, 9, (64,)), (300, 40, 328, 30, (8, 16, 32)),
+                                                  (520, 64, 136, 5, (128,)), (130, 32, 72, 12, (8, 64))]):
+        w = wl.random_case(600 + seed, T, K, N, n_a, ranks, max_seg=3, frac_none=0.1, scales=(1.0, 2.0, -0.5))
+        run_forward_case(w, n_sample=min(T, 160), variant=B.LORA_VARIANT_TILED)
+        run_mixture_case(w, seed % n_a, n_sample=min(T, 96))
+
+
 def test_streaming_kernels_ragged_cases():
     # the prefill-sized (streaming) shrink / expand kernels forced onto small ragged batches: adapter
     # groups from 1 to a few hundred tokens (every tile shape: 8, 4, 2, 1 token blocks), all ranks up to

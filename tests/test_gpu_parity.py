@@ -319,6 +319,39 @@ def test_fused_forward_with_a_single_k_stage():
         run_mixture_case(w, seed % n_a, n_sample=min(T, 96))
 
 
+def test_seeded_sweep_of_random_batches():
+    # Many small batches drawn from a seeded generator -- token counts from one to a few thousand, K from one GEMM
+    # stage to 4096, ragged N, one to 150 adapters, aligned and odd rank sets, segment lengths from decode to
+    # prefill -- through lora_delta (both kernel families decide for themselves), the single launch with and without
+    # its fallback, the fused forward and mixture mode.  (A sweep like this found the missing barrier that
+    # test_fused_forward_with_a_single_k_stage pins.)
+    rng = np.random.default_rng(20241128)
+    rank_sets = [(8, 16, 32, 64), (8, 64), (16, 128), (8, 16, 24, 40, 128), (64,), (128,), (3, 12, 100), (8, 20, 256), (4, 8)]
+    for i in range(36):
+        T = int(rng.choice([1, 7, 33, 100, 256, 300, 700, 1500, 2600]))
+        K = int(rng.choice([64, 328, 1024, 2048, 4096]))
+        N = int(rng.choice([64, 200, 1000, 2048, 4096]))
+        n_a = int(rng.choice([1, 3, 9, 40, 150]))
+        ranks = rank_sets[int(rng.integers(len(rank_sets)))]
+        max_seg = int(rng.choice([1, 2, 12, 64, 300, 1024]))
+        frac_none, empty = float(rng.choice([0.0, 0.2])), bool(rng.integers(2))
+        m = int(rng.integers(n_a))
+        if T * N < 400:
+            continue                                # the normwise bound is a statement about many roundings
+        w = wl.random_case(7000 + i, T, K, N, n_a, ranks, max_seg=max_seg, frac_none=frac_none,
+                           scales=(0.5, 2.0, -1.5), empty_segments=empty)
+        print(f"[{i}] T={T} K={K} N={N} adapters={n_a} ranks={ranks} max_seg={max_seg}", flush=True)
+        run_delta_case(w, check_beta0=bool(i % 2))
+        if i % 3 == 0:
+            run_forward_case(w, n_sample=min(T, 96))
+        if i % 4 == 1:
+            _delta_case(w)
+            _delta_case(w, fallback=True)
+        # (mixture's identity check against unmerged inference assumes an update that does not dwarf W)
+        if i % 5 == 0 and K >= 1024 and max(ranks) <= 64 and all(r % 8 == 0 for r in ranks):
+            run_mixture_case(w, m, n_sample=min(T, 64))
+
+
 def test_streaming_kernels_ragged_cases():
     # the prefill-sized (streaming) shrink / expand kernels forced onto small ragged batches: adapter
     # groups from 1 to a few hundred tokens (every tile shape: 8, 4, 2, 1 token blocks), all ranks up to

@@ -490,7 +490,9 @@ extern "C" lora_status lora_delta_static(lora_plan* p, const void* x, int64_t ld
     } else if (p->family == LORA_VARIANT_TILED && p->variant_req == LORA_VARIANT_TILED) {
         return LORA_ERR_UNSUPPORTED;
     } else {
-        e = launch_shrink_general(p, d, x, ldx, d_At_ptrs, v, stream);
+        // (the same choice of shrink as lora_delta's: tiled also where only the expand is general)
+        if (p->shrink_tiled_only && tiled_call_ok(x, ldx)) e = launch_shrink_tiled(p, d, x, ldx, d_At_ptrs, v, stream);
+        else e = launch_shrink_general(p, d, x, ldx, d_At_ptrs, v, stream);
         if (e == hipSuccess) e = launch_expand_general(p, d, v, d_Bt_ptrs, y, ldy, beta, stream);
     }
     return e == hipSuccess ? LORA_OK : LORA_ERR_DEVICE;

@@ -55,7 +55,9 @@ def test_static_entry_point_matches_lora_delta_on_two_calls_in_a_row():
     small_decode = wl.random_case(952, 150, 1024, 640, 40, (8, 16, 32, 64), max_seg=2, frac_none=0.1, scales=(1.0, 2.0))
     big_decode = wl.random_case(953, 700, 512, 1024, 200, (8, 16, 32, 64), max_seg=1, scales=(1.0, -2.0))
     tiny_general = wl.random_case(954, 33, 77, 53, 4, (3, 5, 12), max_seg=6, frac_none=0.2)
-    for first, second in ((big_stream, small_decode), (big_decode, small_decode), (small_decode, tiny_general)):
+    odd_ranks = wl.random_case(955, 90, 1024, 328, 6, (3, 12, 100, 200), max_seg=4, frac_none=0.1)   # tiled shrink, general expand
+    for first, second in ((big_stream, small_decode), (big_decode, small_decode), (small_decode, tiny_general),
+                          (big_decode, odd_ranks)):
         for beta in (1.0, 0.0):
             _case(first, beta)
             _case(second, beta)

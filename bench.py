@@ -38,8 +38,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # profiler run of this benchmark, not in this run (keyed by workload and kernel; the file holds the figures)
 PROFILED_TRAFFIC = {("cfg2_decode", "delta_fused_small_kernel"): (45.80e6, "profiles/decode_cfg2_hbm_traffic.txt"),
                     ("cfg5_large_attn", "expand_stream_kernel"): (533.80e6, "profiles/prefill_cfg5_shrink_expand_hbm_traffic.txt"),
-                    ("cfg5_large_attn", "shrink_stream_kernel"): (332.18e6, "profiles/prefill_cfg5_shrink_expand_hbm_traffic.txt"),
-                    ("cfg4_mixed", "expand_stream_kernel"): (487.85e6, "profiles/prefill_cfg4_shrink_expand_hbm_traffic.txt")}
+                    ("cfg5_large_attn", "shrink_stream_kernel"): (332.16e6, "profiles/prefill_cfg5_shrink_expand_hbm_traffic.txt"),
+                    ("cfg4_mixed", "expand_stream_kernel"): (487.72e6, "profiles/prefill_cfg4_shrink_expand_hbm_traffic.txt")}
 
 KERNEL_KEYS = {"shrink_tiled_kernel": "shrink", "expand_tiled_kernel": "expand", "delta_fused_small_kernel": "delta",
                "shrink_stream_kernel": "shrink", "expand_stream_kernel": "expand", "v_split_kernel": "v_split",

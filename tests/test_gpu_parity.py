@@ -352,6 +352,17 @@ def test_seeded_sweep_of_random_batches():
             run_mixture_case(w, m, n_sample=min(T, 64))
 
 
+def test_large_token_counts():
+    # four times the tokens of the largest benchmark configuration (64-bit row offsets, tile lists of tens of
+    # thousands of entries, thousands of adapter groups); the oracle checks v in full and y on sampled rows
+    rng = np.random.default_rng(9)
+    for seed, (T, K, N, n_a, ranks, max_seg) in enumerate([(65536, 1024, 2048, 512, (8, 16, 32, 64, 128), 64),
+                                                           (50000, 2048, 1024, 2000, (8, 16), 1)]):
+        w = wl.random_case(800 + seed, T, K, N, n_a, ranks, max_seg=max_seg, frac_none=0.05, scales=(2.0, -0.5))
+        run_delta_case(w, check_beta0=False, rows=np.sort(rng.choice(T, size=256, replace=False)))
+        run_forward_case(w, n_sample=160)
+
+
 def test_streaming_kernels_ragged_cases():
     # the prefill-sized (streaming) shrink / expand kernels forced onto small ragged batches: adapter
     # groups from 1 to a few hundred tokens (every tile shape: 8, 4, 2, 1 token blocks), all ranks up to

@@ -127,7 +127,7 @@ class LayerSets:
             self.layers.append((x, At_ptrs, Bt_ptrs, y, Wt, At_buf, Bt_buf))
 
 
-def measure(w, path, steps, warmup, layers_max, torch, B, device, dev, graph=True):
+def measure(w, path, steps, warmup, layers_max, torch, B, device, dev, graph=True, merged_adapter=None):
     """One workload through one path: steps of (lora_plan + L layers), per-step event pairs, per-kernel timers."""
     import numpy as np
     need_w = path in ("fused", "base")
@@ -135,7 +135,9 @@ def measure(w, path, steps, warmup, layers_max, torch, B, device, dev, graph=Tru
     L = int(max(2, min(layers_max, 8e9 // max(per_layer_bytes, 1))))
     sets = LayerSets(w, L, need_w, torch, device, dev)
     abi_dtype = B.LORA_BF16
-    plan0 = B.lora_plan(w.T, w.seg_indptr, w.seg_adapter, w.adapter_rank, w.adapter_scale, w.K, w.N, abi_dtype)
+    make_plan = lambda: B.lora_plan(w.T, w.seg_indptr, w.seg_adapter, w.adapter_rank, w.adapter_scale, w.K, w.N, abi_dtype,
+                                    merged_adapter=merged_adapter)
+    plan0 = make_plan()
     _, v_bytes, ws_bytes = B.lora_plan_query(plan0)
     v = torch.zeros(max(v_bytes // 4, 64), dtype=torch.float32, device=dev)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
@@ -156,7 +158,7 @@ def measure(w, path, steps, warmup, layers_max, torch, B, device, dev, graph=Tru
     keep = []
 
     def step():
-        plan = B.lora_plan(w.T, w.seg_indptr, w.seg_adapter, w.adapter_rank, w.adapter_scale, w.K, w.N, abi_dtype)
+        plan = make_plan()
         B.lora_plan_upload(plan, stream)
         run_layers(plan, stream)
         keep.append(plan)          # destroyed after the work has finished
@@ -184,16 +186,21 @@ def measure(w, path, steps, warmup, layers_max, torch, B, device, dev, graph=Tru
 
     tp0 = time.perf_counter()
     for _ in range(20):
-        B.lora_plan(w.T, w.seg_indptr, w.seg_adapter, w.adapter_rank, w.adapter_scale, w.K, w.N, abi_dtype).destroy()
+        make_plan().destroy()
     plan_us = (time.perf_counter() - tp0) * 1e6 / 20
 
     # per-kernel durations (event pair attached to every launch)
     B.lora_plan_upload(plan0, stream)
     torch.cuda.synchronize()
     B.lora_timing_begin()
-    for _ in range(max(2, min(steps, 10))):
+    sweeps = max(2, min(steps, 10))
+    for _ in range(sweeps):
         run_layers(plan0, stream)
     kern = B.lora_timing_end()
+    # per layer: a kernel that runs more than once per layer (mixture mode: the removal's batch, then the tokens'
+    # own) counts with all its launches
+    for d in kern.values():
+        d["avg_us"] = d["avg_us"] * d["count"] / (sweeps * L)
 
     graph_us = None
     if graph:
@@ -310,6 +317,48 @@ def measure_merge(steps, warmup, torch, B, dev):
     return dict(ms_per_step=ms_per_step, step_ms=percentiles(step_ms), kernel_avg_us=kern["avg_us"], kernel_min_us=kern["min_us"],
                 launches=kern["count"], algorithmic_bytes=by, algorithmic_flops=2 * L * N * K * r,
                 GBs=by / kern["avg_us"] * 1e-3, config=dict(layers=L, n=N, k=K, rank=r))
+
+
+def measure_heads(steps, torch, B, device, dev):
+    """Task heads (section 4.2.2): 256 requests, one final feature each, 64 heads of different widths in one batch
+    through lora_shrink (rank = outputs of the head, scale 1); rotating, cold head matrices."""
+    import numpy as np
+    from paper_2411_00915_amd import workloads as wl
+    widths = (2, 5, 10, 101, 174, 256)
+    with wl.tables_only():
+        w = wl.random_case(4220, 256, 4096, 64, 64, widths, max_seg=1, scales=(1.0,), with_w=False)
+    w.adapter_rank = np.asarray([widths[i % len(widths)] for i in range(64)], dtype=np.int32)
+    plan = B.lora_plan(w.T, w.seg_indptr, w.seg_adapter, w.adapter_rank, w.adapter_scale, w.K, w.N, B.LORA_BF16)
+    view = B.lora_plan_export(plan)
+    _, v_bytes, _ = B.lora_plan_query(plan)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4220)
+    off = np.concatenate([[0], np.cumsum([(int(r) * w.K + 7) // 8 * 8 for r in w.adapter_rank])])
+    L = 16
+    sets = []
+    for _ in range(L):
+        Ht = (torch.randn(int(off[-1]) + 8, generator=gen, device=dev) * w.K ** -0.5).to(torch.bfloat16)
+        ptrs = torch.tensor([Ht.data_ptr() + int(o) * 2 for o in off[:-1]], dtype=torch.int64, device=dev)
+        x = torch.randn(w.T * w.K, generator=gen, device=dev).to(torch.bfloat16).view(w.T, w.K)
+        sets.append((x, ptrs, Ht))
+    v = torch.zeros(max(v_bytes // 4, 64), dtype=torch.float32, device=dev)
+    B.lora_plan_upload(plan)
+    for x, ptrs, _h in sets:
+        B.lora_shrink(plan, x, w.K, ptrs, v)
+    torch.cuda.synchronize()
+    B.lora_timing_begin()
+    for _ in range(max(2, min(steps, 10))):
+        for x, ptrs, _h in sets:
+            B.lora_shrink(plan, x, w.K, ptrs, v)
+    kern = B.lora_timing_end()
+    plan.destroy()
+    (name, d), = kern.items()
+    used = np.bincount(w.seg_adapter[w.seg_adapter >= 0], minlength=64) > 0
+    by = 2 * (w.T * w.K + int(w.adapter_rank[used].sum()) * w.K) + 4 * int(w.adapter_rank[w.seg_adapter].sum())
+    return {"requests": w.T, "k": w.K, "heads": 64, "widths": list(widths), "kernel": name,
+            "shrink_kernel_family": "tiled" if view["shrink_kernel_family"] == B.LORA_VARIANT_TILED else "general",
+            "kernel_avg_us": round(d["avg_us"], 2), "algorithmic_bytes": by, "GBs": round(by / d["avg_us"] * 1e-3, 1),
+            "roofline": {"bound": "hbm", "kernel": name, "frac": round(by / d["avg_us"] * 1e-3 / HBM_PEAK_GBS, 4)}}
 
 
 def measure_ceilings(torch, B, dev):
@@ -469,6 +518,26 @@ def main():
             entry["fusion_gain"] = round(sep / res["fused"]["gpu_kernel_us_per_layer"], 3)
             entry["fusion_gain_note"] = "(own base GEMM + lora_delta) / lora_fused_forward, GPU kernel time per layer"
             configs[wt.name] = entry
+        # mixture mode (section 4.4.1) on the mixed batch: its most popular adapter stays merged in the weight
+        wm = load_workload("cfg4", tables_only=True)
+        import numpy as np
+        seg_len = np.diff(wm.seg_indptr)
+        popular = int(np.argmax(np.bincount(wm.seg_adapter[wm.seg_adapter >= 0], weights=seg_len[wm.seg_adapter >= 0], minlength=wm.num_adapters)))
+        mix = {}
+        for path in ("delta", "fused"):
+            r = measure(wm, path, args.configs_steps, args.warmup, 8, torch, B, device, dev, graph=False, merged_adapter=popular)
+            e = brief(r, path)
+            e["roofline"] = None                     # (the byte and flop counts above are those of plain cfg4)
+            for kd in e["kernels"].values():
+                for key in ("algorithmic_bytes", "GBs", "algorithmic_flops", "TFLOPs"):
+                    kd.pop(key, None)
+            mix[{"delta": "lora_delta", "fused": "lora_fused_forward"}[path]] = e
+            torch.cuda.empty_cache()
+        mix["merged_adapter"] = popular
+        mix["note"] = "cfg4 with its most popular adapter merged: every other token also takes that adapter's update off again"
+        configs["cfg4_mixture"] = mix
+        configs["task_heads"] = measure_heads(args.configs_steps, torch, B, device, dev)
+        torch.cuda.empty_cache()
         m = measure_merge(args.configs_steps, args.warmup, torch, B, dev)
         configs["merge7b"] = {"ms_per_launch": round(m["ms_per_step"], 4), **{k + "_ms": round(val, 4) for k, val in m["step_ms"].items()},
                               "kernel_avg_us": round(m["kernel_avg_us"], 1), "algorithmic_bytes": m["algorithmic_bytes"],

@@ -130,7 +130,7 @@ class LayerSets:
 def measure(w, path, steps, warmup, layers_max, torch, B, device, dev, graph=True, merged_adapter=None):
     """One workload through one path: steps of (lora_plan + L layers), per-step event pairs, per-kernel timers."""
     import numpy as np
-    need_w = path in ("fused", "base")
+    need_w = path in ("fused", "base", "vendor-gemm")
     per_layer_bytes = 2 * (w.T * w.K + w.T * w.N + int(w.adapter_rank.sum()) * (w.K + w.N) + (w.K * w.N if need_w else 0))
     L = int(max(2, min(layers_max, 8e9 // max(per_layer_bytes, 1))))
     sets = LayerSets(w, L, need_w, torch, device, dev)
@@ -151,6 +151,8 @@ def measure(w, path, steps, warmup, layers_max, torch, B, device, dev, graph=Tru
                 B.lora_expand(plan, v, Bt_ptrs, y, w.N, 1.0, stream)
             elif path == "base":
                 B.lora_base_gemm(w.T, w.K, w.N, abi_dtype, x, w.K, Wt, w.K, y, w.N, stream)
+            elif path == "vendor-gemm":
+                torch.matmul(x, Wt.t(), out=y)
             else:
                 B.lora_fused_forward(plan, x, w.K, Wt, w.K, At_ptrs, Bt_ptrs, y, w.N, ws, ws.numel(), stream)
 
@@ -251,6 +253,11 @@ def measure(w, path, steps, warmup, layers_max, torch, B, device, dev, graph=Tru
     view = B.lora_plan_export(plan0)
     plan0.destroy()
     us_per_layer = ms_per_step * 1e3 / L
+    if path == "vendor-gemm":                     # not this library's kernel: rate from the per-layer wall time
+        tf = 2.0 * w.T * w.K * w.N / us_per_layer * 1e-6
+        roofline = dict(bound="mfma", kernel="vendor library GEMM behind torch.matmul", achieved=round(tf, 1),
+                        peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=round(tf / MFMA_BF16_PEAK_TFLOPS, 4), traffic=None,
+                        avg_kernel_us=None, algorithmic_flops=2 * w.T * w.K * w.N)
     pct = {k: round(val * 1e3 / L, 3) for k, val in percentiles(step_ms).items()}
     del sets
     return dict(w=w, L=L, ms_per_step=ms_per_step, us_per_layer=us_per_layer, step_us_per_layer=pct,
@@ -446,7 +453,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--workload", default="cfg2", choices=WORKLOADS + ["merge7b"])
-    ap.add_argument("--path", default="delta", choices=["delta", "two-launches", "fused", "base"])
+    ap.add_argument("--path", default="delta", choices=["delta", "two-launches", "fused", "base", "vendor-gemm"],
+                    help="vendor-gemm: torch.matmul (the vendor library) on the operands of `base`, for comparison and for counter runs")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time budget of the oracle leg (0 = skip)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the `configs` and `ceilings` objects")
@@ -486,7 +494,7 @@ def main():
             "cpu_baseline": None, "step_ms": rnd(m["step_ms"])}))
         return
 
-    fused = args.path in ("fused", "base")
+    fused = args.path in ("fused", "base", "vendor-gemm")
     w = load_workload(args.workload, tables_only=False)
     head = measure(w, args.path, args.steps, args.warmup, args.layers, torch, B, device, dev, graph=not args.no_graph)
 
@@ -499,7 +507,7 @@ def main():
         del src, dst
 
     cpu = None
-    if args.cpu_seconds > 0 and args.path != "base":
+    if args.cpu_seconds > 0 and args.path not in ("base", "vendor-gemm"):
         y0 = (torch.randn(w.T * w.N, device=dev)).to(torch.bfloat16).view(w.T, w.N)
         cpu = oracle_leg(w, y0, args.cpu_seconds)
 
@@ -548,7 +556,7 @@ def main():
 
     what = {"delta": "lora_delta per layer", "two-launches": "lora_shrink + lora_expand per layer",
             "fused": "lora_fused_forward per layer (shrink + base GEMM with delta epilogue)",
-            "base": "lora_base_gemm per layer"}[args.path]
+            "base": "lora_base_gemm per layer", "vendor-gemm": "torch.matmul per layer (vendor library, comparison only)"}[args.path]
     out = {
         "metric": ("LoRA-delta us/layer (shrink+expand, plan amortised over the layers of a step)" if not fused else
                    "fused layer us/layer (xW + delta, plan amortised over the layers of a step)"),
